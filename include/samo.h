@@ -1,0 +1,186 @@
+/*
+ * samo.h — C ABI of libsamo: the per-iteration compressed-parameter pipeline of
+ * Sparsity-aware Memory Optimization (SAMO; Singh & Bhatele, "Exploiting
+ * Sparsity in Pruned Neural Networks to Optimize Large Model Training",
+ * Section III) for one AMD MI355X (gfx950).
+ *
+ * Storage (Section III-A, III-B).  For every pruned layer, with N = number of
+ * elements of its flattened 1-D view and nnz = number of unpruned elements:
+ *   idx      int32[nnz]   ascending flat positions of the unpruned elements
+ *                         (the paper's ind_i), shared by all compressed tensors
+ *   p, m, v  float[nnz]   fp32 master parameters and the two Adam states, values
+ *                         at the unpruned positions only (theta32, os)
+ *   gc       float[nnz]   compressed, up-cast, unscaled gradient (grad theta32)
+ *   w        fp16[N]      dense half-precision parameters (theta16) with +0
+ *                         stored explicitly at every pruned position
+ *   g        fp16[N]      dense half-precision gradient as backward produced it
+ *   seg_ptr  int32[ceil(N / SAMO_SEG_ELEMS) + 1]
+ *                         seg_ptr[s] = #{ i : idx[i] < s * SAMO_SEG_ELEMS };
+ *                         seg_ptr[last] = nnz.  Not in the paper: a small table
+ *                         (4 bytes per 1024 dense elements) that lets a
+ *                         workgroup owning a dense tile find its slice of the
+ *                         compressed arrays without searching.
+ * fp16 values cross this boundary as uint16_t bit patterns (IEEE binary16).
+ *
+ * Conventions common to every entry point
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller
+ *     owns every buffer.  The library allocates device memory only inside
+ *     samo_plan_create (one small table, freed by samo_plan_destroy).
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *     Calls only enqueue work and return; there is no hidden synchronisation.
+ *     Outputs (including *d_nnz) are valid once the stream reaches that point.
+ *   - Arguments are validated on the host BEFORE anything is enqueued.  On a
+ *     negative status nothing was launched and no output was touched.
+ *   - Sizes: 0 <= N <= 2^31 - 1 per layer (the index is 32-bit, Section III-B);
+ *     0 <= nnz <= N.  N = 0 and nnz = 0 are valid and do nothing / zero-fill.
+ *   - Alignment: every array pointer must be 16-byte aligned (SAMO_ERR_ALIGN).
+ *   - Preconditions NOT checked on the hot path (results undefined if violated;
+ *     samo_validate_index checks them): idx strictly ascending, 0 <= idx[i] < N,
+ *     seg_ptr consistent with idx.  Strictly ascending indices make scatter
+ *     race-free without atomics.
+ *   - Aliasing: w and g of a layer must not overlap; p, m, v are updated in place.
+ *   - Every result is deterministic: same inputs give the same bits.
+ */
+#ifndef SAMO_H
+#define SAMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAMO_ABI_VERSION 1
+#define SAMO_SEG_ELEMS 1024 /* dense elements per seg_ptr entry */
+
+typedef int32_t samo_status;
+enum {
+    SAMO_OK = 0,
+    SAMO_ERR_NULL = -1,  /* a required pointer is NULL */
+    SAMO_ERR_SIZE = -2,  /* N or nnz out of range, or capacity/length too small */
+    SAMO_ERR_ARG = -3,   /* invalid hyper-parameter or scale */
+    SAMO_ERR_ALIGN = -4, /* pointer not 16-byte aligned */
+    SAMO_ERR_HIP = -5,   /* HIP runtime reported an error on launch/alloc */
+    SAMO_ERR_PLAN = -6   /* plan lacks a buffer this entry point needs */
+};
+
+/* Static string for a status code (never NULL). */
+const char *samo_status_string(samo_status s);
+int32_t samo_abi_version(void);
+/* ceil(n / SAMO_SEG_ELEMS) + 1, the required length of seg_ptr; -1 if n is out of range. */
+int64_t samo_seg_ptr_len(int64_t n);
+
+/* Adam hyper-parameters (Kingma & Ba; the optimizer assumed by Section III-D).
+ * step >= 1 is Adam's t; eps > 0 is added after the square root of the
+ * bias-corrected second moment; 0 <= beta < 1.  weight_decay is added to the
+ * gradient (decoupled_wd = 0, L2) or applied to the parameter directly
+ * (decoupled_wd = 1, AdamW as used for the paper's GPT runs, Section V). */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t decoupled_wd;
+    int32_t step;
+} samo_adam_cfg;
+
+/* ---------------------------------------------------------------- index (ind_i, Section III / III-B)
+ * The pruning algorithm's output is taken as a byte mask over the flattened
+ * layer: mask[j] != 0 means element j is unpruned.
+ *
+ * samo_count_nonzero: fills d_seg_ptr[0 .. samo_seg_ptr_len(n)) and *d_nnz.
+ * samo_build_index:   the same, and writes the ascending positions to d_idx.
+ *   If nnz > idx_capacity only the first idx_capacity positions are stored;
+ *   *d_nnz still holds the true count, so the caller can detect it.
+ *   d_idx may be NULL only if idx_capacity == 0.
+ * Typical use: count, read *d_nnz, allocate idx, build; or build with capacity n. */
+samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_ptr,
+                               int64_t *d_nnz, void *stream);
+samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx,
+                             int64_t idx_capacity, int32_t *d_seg_ptr, int64_t *d_nnz,
+                             void *stream);
+/* seg_ptr for an index that came from elsewhere (e.g. straight from a pruner). */
+samo_status samo_build_seg_ptr(const int32_t *d_idx, int64_t nnz, int64_t n,
+                               int32_t *d_seg_ptr, void *stream);
+/* *d_ok = 1 if idx is strictly ascending within [0, n) and (when d_seg_ptr is
+ * not NULL) seg_ptr matches it; else 0. */
+samo_status samo_validate_index(const int32_t *d_idx, int64_t nnz, int64_t n,
+                                const int32_t *d_seg_ptr, int32_t *d_ok, void *stream);
+
+/* ---------------------------------------------------------------- expansion (Section III-C, optimizer step)
+ * w[idx[i]] = fp16(p[i]) (round to nearest even, subnormals kept, overflow to
+ * infinity); every other element of w[0..n) = +0, whatever w held before. */
+samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_t *d_seg_ptr,
+                            int64_t nnz, uint16_t *d_w, int64_t n, void *stream);
+
+/* ---------------------------------------------------------------- gradient compression (Section III-C, backward pass;
+ * merged with the fp32 up-cast of the optimizer step and loss-scale division)
+ * gc[i] = float(g[idx[i]]) * inv_loss_scale — one exact conversion, one fp32
+ * multiply.  Gradient values at pruned positions are ignored.
+ * inv_loss_scale must be finite and > 0. */
+samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_idx,
+                              int64_t nnz, float inv_loss_scale, float *d_gc, void *stream);
+
+/* ---------------------------------------------------------------- optimizer on compressed state (Section III-C, III-D)
+ * One Adam step over p, m, v [0..nnz) with gradient gc, all fp32, in place. */
+samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,
+                           const samo_adam_cfg *h_cfg, void *stream);
+
+/* ---------------------------------------------------------------- fused optimizer phase (Section III-C: compress + up-cast,
+ * optimizer, 16-bit copy, expansion — in one pass)
+ * Equivalent to samo_gather_grads -> samo_adam_step -> samo_decompress without
+ * materialising gc or the temporary compressed fp16 copy.
+ * Dense (unpruned) layer: d_idx == NULL, d_seg_ptr == NULL and nnz == n. */
+samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                            const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m,
+                            float *d_v, float inv_loss_scale, const samo_adam_cfg *h_cfg,
+                            void *stream);
+
+/* ---------------------------------------------------------------- whole-model (batched) forms
+ * One launch covers every layer, so small layers do not pay a launch and a
+ * tail each.  A plan is built once per pruning from a HOST array of layer
+ * descriptors holding DEVICE pointers; it copies the descriptors and its
+ * workgroup-to-layer maps to the device.  The plan does not own the layers'
+ * buffers, which must stay valid while the plan is used.  A descriptor with
+ * idx == NULL (then seg_ptr == NULL and nnz == n) is a dense layer.  Buffers an
+ * entry point does not use may be NULL in the descriptor (e.g. gc for the
+ * fused step); an entry point that needs a missing one returns SAMO_ERR_PLAN. */
+typedef struct {
+    int64_t n, nnz;
+    const int32_t *idx;
+    const int32_t *seg_ptr;
+    float *p, *m, *v;
+    uint16_t *w;
+    const uint16_t *g;
+    float *gc;
+} samo_layer;
+
+typedef struct samo_plan samo_plan;
+
+samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, samo_plan **out);
+samo_status samo_plan_destroy(samo_plan *plan); /* NULL is accepted */
+/* Sum over layers, as given at creation. */
+samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *nnz_total);
+
+samo_status samo_decompress_batched(const samo_plan *plan, void *stream);
+samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, void *stream);
+samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, void *stream);
+samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale,
+                                    const samo_adam_cfg *h_cfg, void *stream);
+
+/* ---------------------------------------------------------------- byte accounting (Section III-D, Eq. 1-5)  [host only]
+ * paper_default = 20 * n_total; paper_samo = 24 * nnz_total + 2 * n_total;
+ * resident = what this library's fused pipeline keeps allocated:
+ * 16 * nnz_total (idx, p, m, v) + 2 * n_total (w) + 4 bytes per seg_ptr entry
+ * is NOT included (layer-count dependent); any output pointer may be NULL. */
+samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper_default,
+                              int64_t *paper_samo, int64_t *resident);
+
+/* ---------------------------------------------------------------- diagnostics
+ * Plain device-to-device copy of `bytes` bytes (multiple of 16) with the same
+ * launch shape as the pipeline's kernels: measures the achievable HBM stream
+ * rate and calibrates hardware byte counters.  Not part of the method. */
+samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMO_H */

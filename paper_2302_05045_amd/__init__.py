@@ -1,0 +1,306 @@
+"""Python binding of libsamo — the SAMO compressed-parameter pipeline for MI355X.
+
+Argument marshalling only: every function takes torch tensors that already live
+on the GPU, passes their device pointers and the current HIP stream through the
+C ABI declared in ``include/samo.h``, and returns.  All arithmetic and data
+movement happens in the library's HIP kernels.  There is no CPU fallback: if the
+shared library has not been built, importing the first symbol raises.
+
+Names and semantics follow ``samo.h`` one to one (Section III of the paper):
+``samo_build_index``, ``samo_decompress``, ``samo_gather_grads``,
+``samo_adam_step``, ``samo_fused_step`` and the ``*_batched`` forms on a ``Plan``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsamo.so")
+SEG_ELEMS = 1024
+
+SAMO_OK = 0
+SAMO_ERR_NULL, SAMO_ERR_SIZE, SAMO_ERR_ARG, SAMO_ERR_ALIGN, SAMO_ERR_HIP, SAMO_ERR_PLAN = -1, -2, -3, -4, -5, -6
+
+
+class SamoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+class AdamCfg(ctypes.Structure):
+    """samo_adam_cfg"""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("decoupled_wd", ctypes.c_int32), ("step", ctypes.c_int32)]
+
+
+class LayerDesc(ctypes.Structure):
+    """samo_layer"""
+    _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("idx", ctypes.c_void_p), ("seg_ptr", ctypes.c_void_p),
+                ("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("gc", ctypes.c_void_p)]
+
+
+_lib = None
+
+_SIGNATURES = {
+    "samo_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
+    "samo_abi_version": (ctypes.c_int32, []),
+    "samo_seg_ptr_len": (ctypes.c_int64, [ctypes.c_int64]),
+    "samo_count_nonzero": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p]),
+    "samo_build_index": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_build_seg_ptr": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                            ctypes.c_void_p]),
+    "samo_validate_index": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_decompress": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
+    "samo_gather_grads": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                           ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_adam_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int64, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_fused_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_plan_create": (ctypes.c_int32, [ctypes.POINTER(LayerDesc), ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]),
+    "samo_plan_destroy": (ctypes.c_int32, [ctypes.c_void_p]),
+    "samo_plan_totals": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+                                          ctypes.POINTER(ctypes.c_int64)]),
+    "samo_decompress_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_gather_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]),
+    "samo_adam_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_fused_step_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+                                                 ctypes.c_void_p]),
+    "samo_memory_model": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+    "samo_stream_copy": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
+}
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built — there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libsamo.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(or `python -m paper_2302_05045_amd._build`) first; there is no CPU fallback")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        if handle.samo_abi_version() != 1:
+            raise ImportError("libsamo.so has an unexpected ABI version")
+        _lib = handle
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().samo_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != SAMO_OK:
+        raise SamoError(status, where)
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, name: str, length: Optional[int] = None) -> Optional[int]:
+    """Device pointer of a contiguous 1-D CUDA tensor of the given dtype (None passes NULL)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a tensor on the GPU" % name)
+    if t.dtype != dtype or t.dim() != 1 or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous 1-D %s tensor" % (name, dtype))
+    if length is not None and t.numel() < length:
+        raise ValueError("%s holds %d elements, needs %d" % (name, t.numel(), length))
+    return t.data_ptr() if t.numel() else None
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+_F16 = torch.float16
+
+
+def adam_cfg(step: int, lr: float = 1e-4, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+             weight_decay: float = 0.0, decoupled_wd: int = 0) -> AdamCfg:
+    return AdamCfg(lr, beta1, beta2, eps, weight_decay, int(decoupled_wd), int(step))
+
+
+def samo_seg_ptr_len(n: int) -> int:
+    r = lib().samo_seg_ptr_len(int(n))
+    if r < 0:
+        raise SamoError(SAMO_ERR_SIZE, "samo_seg_ptr_len")
+    return r
+
+
+class Index(NamedTuple):
+    idx: torch.Tensor       # int32[nnz]
+    seg_ptr: torch.Tensor   # int32[ceil(n / 1024) + 1]
+    nnz: int
+    n: int
+
+
+def samo_count_nonzero(mask: torch.Tensor, seg_ptr: torch.Tensor, nnz_out: torch.Tensor) -> None:
+    n = mask.numel()
+    _check(lib().samo_count_nonzero(_dev(mask, torch.uint8, "mask"), n,
+                                    _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)),
+                                    _dev(nnz_out, torch.int64, "nnz_out", 1), _stream()), "samo_count_nonzero")
+
+
+def samo_build_index(mask: torch.Tensor) -> Index:
+    """mask: uint8[n] on the GPU (non-zero keeps).  Counts, allocates idx, fills it.
+
+    Reads the count back to size the index (one host synchronisation; the index is built
+    once per pruning, not per iteration)."""
+    n = mask.numel()
+    seg_ptr = torch.empty(samo_seg_ptr_len(n), dtype=torch.int32, device=mask.device)
+    nnz_out = torch.empty(1, dtype=torch.int64, device=mask.device)
+    samo_count_nonzero(mask, seg_ptr, nnz_out)
+    nnz = int(nnz_out.item())
+    idx = torch.empty(nnz, dtype=torch.int32, device=mask.device)
+    samo_build_index_into(mask, idx, seg_ptr, nnz_out)
+    return Index(idx, seg_ptr, nnz, n)
+
+
+def samo_build_index_into(mask: torch.Tensor, idx: torch.Tensor, seg_ptr: torch.Tensor,
+                          nnz_out: torch.Tensor) -> None:
+    """Raw form: caller-provided idx (capacity = idx.numel()), seg_ptr and nnz_out (int64[1])."""
+    n = mask.numel()
+    _check(lib().samo_build_index(_dev(mask, torch.uint8, "mask"), n, _dev(idx, torch.int32, "idx"), idx.numel(),
+                                  _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)),
+                                  _dev(nnz_out, torch.int64, "nnz_out", 1), _stream()), "samo_build_index")
+
+
+def samo_build_seg_ptr(idx: torch.Tensor, n: int) -> torch.Tensor:
+    seg_ptr = torch.empty(samo_seg_ptr_len(n), dtype=torch.int32, device=idx.device)
+    _check(lib().samo_build_seg_ptr(_dev(idx, torch.int32, "idx"), idx.numel(), int(n),
+                                    _dev(seg_ptr, torch.int32, "seg_ptr"), _stream()), "samo_build_seg_ptr")
+    return seg_ptr
+
+
+def samo_validate_index(idx: torch.Tensor, n: int, seg_ptr: Optional[torch.Tensor] = None) -> bool:
+    ok = torch.empty(1, dtype=torch.int32, device=idx.device)
+    _check(lib().samo_validate_index(_dev(idx, torch.int32, "idx"), idx.numel(), int(n),
+                                     _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)),
+                                     _dev(ok, torch.int32, "ok"), _stream()), "samo_validate_index")
+    return bool(ok.item())
+
+
+def samo_decompress(p: torch.Tensor, idx: Optional[torch.Tensor], seg_ptr: Optional[torch.Tensor],
+                    w: torch.Tensor) -> None:
+    n, nnz = w.numel(), p.numel()
+    _check(lib().samo_decompress(_dev(p, torch.float32, "p"), _dev(idx, torch.int32, "idx", nnz),
+                                 _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)), nnz,
+                                 _dev(w, _F16, "w"), n, _stream()), "samo_decompress")
+
+
+def samo_gather_grads(g: torch.Tensor, idx: Optional[torch.Tensor], inv_loss_scale: float, gc: torch.Tensor) -> None:
+    n, nnz = g.numel(), gc.numel()
+    _check(lib().samo_gather_grads(_dev(g, _F16, "g"), n, _dev(idx, torch.int32, "idx", nnz), nnz,
+                                   float(inv_loss_scale), _dev(gc, torch.float32, "gc"), _stream()),
+           "samo_gather_grads")
+
+
+def samo_adam_step(p: torch.Tensor, m: torch.Tensor, v: torch.Tensor, gc: torch.Tensor, cfg: AdamCfg) -> None:
+    nnz = p.numel()
+    _check(lib().samo_adam_step(_dev(p, torch.float32, "p"), _dev(m, torch.float32, "m", nnz),
+                                _dev(v, torch.float32, "v", nnz), _dev(gc, torch.float32, "gc", nnz), nnz,
+                                ctypes.byref(cfg), _stream()), "samo_adam_step")
+
+
+def samo_fused_step(g: torch.Tensor, w: torch.Tensor, idx: Optional[torch.Tensor], seg_ptr: Optional[torch.Tensor],
+                    p: torch.Tensor, m: torch.Tensor, v: torch.Tensor, inv_loss_scale: float, cfg: AdamCfg) -> None:
+    n, nnz = w.numel(), p.numel()
+    _check(lib().samo_fused_step(_dev(g, _F16, "g", n), _dev(w, _F16, "w"), n, _dev(idx, torch.int32, "idx", nnz),
+                                 _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)), nnz,
+                                 _dev(p, torch.float32, "p"), _dev(m, torch.float32, "m", nnz),
+                                 _dev(v, torch.float32, "v", nnz), float(inv_loss_scale), ctypes.byref(cfg),
+                                 _stream()), "samo_fused_step")
+
+
+class Layer(NamedTuple):
+    """Device tensors of one layer for the batched entry points (None where unused)."""
+    n: int
+    idx: Optional[torch.Tensor]
+    seg_ptr: Optional[torch.Tensor]
+    p: torch.Tensor
+    m: Optional[torch.Tensor] = None
+    v: Optional[torch.Tensor] = None
+    w: Optional[torch.Tensor] = None
+    g: Optional[torch.Tensor] = None
+    gc: Optional[torch.Tensor] = None
+
+
+class Plan:
+    """samo_plan: one launch per entry point over all layers of a model."""
+
+    def __init__(self, layers: Sequence[Layer]):
+        self._handle = ctypes.c_void_p()
+        self._layers = list(layers)          # keeps the tensors alive
+        descs = (LayerDesc * max(len(self._layers), 1))()
+        for d, L in zip(descs, self._layers):
+            nnz = L.p.numel()
+            d.n, d.nnz = int(L.n), nnz
+            d.idx = _dev(L.idx, torch.int32, "idx", nnz)
+            d.seg_ptr = _dev(L.seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(L.n))
+            d.p = _dev(L.p, torch.float32, "p")
+            d.m = _dev(L.m, torch.float32, "m", nnz)
+            d.v = _dev(L.v, torch.float32, "v", nnz)
+            d.w = _dev(L.w, _F16, "w", L.n)
+            d.g = _dev(L.g, _F16, "g", L.n)
+            d.gc = _dev(L.gc, torch.float32, "gc", nnz)
+        _check(lib().samo_plan_create(descs, len(self._layers), ctypes.byref(self._handle)), "samo_plan_create")
+
+    def close(self) -> None:
+        if self._handle:
+            lib().samo_plan_destroy(self._handle)
+            self._handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def totals(self):
+        n, nnz = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().samo_plan_totals(self._handle, ctypes.byref(n), ctypes.byref(nnz)), "samo_plan_totals")
+        return n.value, nnz.value
+
+    def samo_decompress_batched(self) -> None:
+        _check(lib().samo_decompress_batched(self._handle, _stream()), "samo_decompress_batched")
+
+    def samo_gather_batched(self, inv_loss_scale: float) -> None:
+        _check(lib().samo_gather_batched(self._handle, float(inv_loss_scale), _stream()), "samo_gather_batched")
+
+    def samo_adam_batched(self, cfg: AdamCfg) -> None:
+        _check(lib().samo_adam_batched(self._handle, ctypes.byref(cfg), _stream()), "samo_adam_batched")
+
+    def samo_fused_step_batched(self, inv_loss_scale: float, cfg: AdamCfg) -> None:
+        _check(lib().samo_fused_step_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg), _stream()),
+               "samo_fused_step_batched")
+
+
+def samo_memory_model(n_total: int, nnz_total: int):
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().samo_memory_model(int(n_total), int(nnz_total), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+           "samo_memory_model")
+    return a.value, b.value, c.value
+
+
+def samo_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst is smaller than src")
+    _check(lib().samo_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream()), "samo_stream_copy")

@@ -1,0 +1,336 @@
+// C ABI of libsamo: host-side argument validation, plan management, launches.
+// Every entry point validates on the host first and enqueues only if all
+// arguments are acceptable, so the error paths can be exercised without a GPU.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace samo;
+
+struct samo_plan {
+    std::vector<samo_layer> layers;   // host copy
+    samo_layer *d_layers = nullptr;
+    WgRec *d_tiles = nullptr;
+    WgRec *d_chunks = nullptr;
+    int64_t ntiles = 0, nchunks = 0;
+    int64_t n_total = 0, nnz_total = 0;
+    bool has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true;
+};
+
+namespace {
+
+constexpr int64_t kMaxN = 2147483647LL;   // the per-layer index is 32-bit (Section III-B)
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline samo_status hip_status(hipError_t e) { return e == hipSuccess ? SAMO_OK : SAMO_ERR_HIP; }
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+samo_status check_sizes(int64_t n, int64_t nnz)
+{
+    if (n < 0 || n > kMaxN) return SAMO_ERR_SIZE;
+    if (nnz < 0 || nnz > n) return SAMO_ERR_SIZE;
+    return SAMO_OK;
+}
+
+samo_status check_scale(float s)
+{
+    return (std::isfinite(s) && s > 0.f) ? SAMO_OK : SAMO_ERR_ARG;
+}
+
+samo_status make_adam(const samo_adam_cfg *c, AdamK *k)
+{
+    if (!c) return SAMO_ERR_NULL;
+    if (!std::isfinite(c->lr)) return SAMO_ERR_ARG;
+    if (!(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f)) return SAMO_ERR_ARG;
+    if (!(std::isfinite(c->eps) && c->eps > 0.f)) return SAMO_ERR_ARG;
+    if (!(std::isfinite(c->weight_decay) && c->weight_decay >= 0.f)) return SAMO_ERR_ARG;
+    if (c->step < 1) return SAMO_ERR_ARG;
+    const double b1 = c->beta1, b2 = c->beta2;
+    k->lr = c->lr;
+    k->b1 = c->beta1;
+    k->b2 = c->beta2;
+    k->omb1 = (float)(1.0 - b1);
+    k->omb2 = (float)(1.0 - b2);
+    k->eps = c->eps;
+    k->wd = c->weight_decay;
+    k->rbc1 = (float)(1.0 / (1.0 - std::pow(b1, (double)c->step)));
+    k->rbc2 = (float)(1.0 / (1.0 - std::pow(b2, (double)c->step)));
+    k->l2 = (c->weight_decay != 0.f && !c->decoupled_wd) ? 1 : 0;
+    k->decoupled = (c->weight_decay != 0.f && c->decoupled_wd) ? 1 : 0;
+    return SAMO_OK;
+}
+
+// Index arguments of a layer: (idx, seg_ptr) both given (idx may be NULL when nnz == 0), or, where
+// a dense layer is allowed, both NULL with nnz == n.
+samo_status check_index_args(const int32_t *idx, const int32_t *seg_ptr, int64_t n, int64_t nnz, bool allow_dense)
+{
+    if (!idx && !seg_ptr) {
+        if (!allow_dense) return SAMO_ERR_NULL;
+        return nnz == n ? SAMO_OK : SAMO_ERR_SIZE;
+    }
+    if (!seg_ptr || (!idx && nnz > 0)) return SAMO_ERR_NULL;
+    if (misaligned(idx) || misaligned(seg_ptr)) return SAMO_ERR_ALIGN;
+    return SAMO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *samo_status_string(samo_status s)
+{
+    switch (s) {
+    case SAMO_OK: return "ok";
+    case SAMO_ERR_NULL: return "a required pointer is NULL";
+    case SAMO_ERR_SIZE: return "size out of range (0 <= nnz <= n <= 2^31-1) or capacity too small";
+    case SAMO_ERR_ARG: return "invalid hyper-parameter or loss scale";
+    case SAMO_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case SAMO_ERR_HIP: return "HIP runtime error";
+    case SAMO_ERR_PLAN: return "plan lacks a buffer this entry point needs";
+    default: return "unknown status";
+    }
+}
+
+int32_t samo_abi_version(void) { return SAMO_ABI_VERSION; }
+
+int64_t samo_seg_ptr_len(int64_t n)
+{
+    if (n < 0 || n > kMaxN) return -1;
+    return ceil_div(n, kSeg) + 1;
+}
+
+samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_ptr, int64_t *d_nnz, void *stream)
+{
+    if (n < 0 || n > kMaxN) return SAMO_ERR_SIZE;
+    if ((!d_mask && n > 0) || !d_seg_ptr || !d_nnz) return SAMO_ERR_NULL;
+    if (misaligned(d_mask) || misaligned(d_seg_ptr) || (reinterpret_cast<uintptr_t>(d_nnz) & 7u)) return SAMO_ERR_ALIGN;
+    return hip_status(launch_count(d_mask, n, d_seg_ptr, d_nnz, as_stream(stream)));
+}
+
+samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx, int64_t idx_capacity,
+                             int32_t *d_seg_ptr, int64_t *d_nnz, void *stream)
+{
+    if (n < 0 || n > kMaxN || idx_capacity < 0) return SAMO_ERR_SIZE;
+    if ((!d_mask && n > 0) || !d_seg_ptr || !d_nnz || (!d_idx && idx_capacity > 0)) return SAMO_ERR_NULL;
+    if (misaligned(d_mask) || misaligned(d_seg_ptr) || misaligned(d_idx) ||
+        (reinterpret_cast<uintptr_t>(d_nnz) & 7u))
+        return SAMO_ERR_ALIGN;
+    hipError_t e = launch_count(d_mask, n, d_seg_ptr, d_nnz, as_stream(stream));
+    if (e != hipSuccess) return SAMO_ERR_HIP;
+    return hip_status(launch_fill(d_mask, n, d_seg_ptr, d_idx, idx_capacity, as_stream(stream)));
+}
+
+samo_status samo_build_seg_ptr(const int32_t *d_idx, int64_t nnz, int64_t n, int32_t *d_seg_ptr, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if ((!d_idx && nnz > 0) || !d_seg_ptr) return SAMO_ERR_NULL;
+    if (misaligned(d_idx) || misaligned(d_seg_ptr)) return SAMO_ERR_ALIGN;
+    return hip_status(launch_seg_ptr_from_idx(d_idx, nnz, n, d_seg_ptr, as_stream(stream)));
+}
+
+samo_status samo_validate_index(const int32_t *d_idx, int64_t nnz, int64_t n, const int32_t *d_seg_ptr,
+                                int32_t *d_ok, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if ((!d_idx && nnz > 0) || !d_ok) return SAMO_ERR_NULL;
+    if (misaligned(d_idx) || misaligned(d_seg_ptr) || (reinterpret_cast<uintptr_t>(d_ok) & 3u)) return SAMO_ERR_ALIGN;
+    return hip_status(launch_validate(d_idx, nnz, n, d_seg_ptr, d_ok, as_stream(stream)));
+}
+
+samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz,
+                            uint16_t *d_w, int64_t n, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (samo_status s = check_index_args(d_idx, d_seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
+    if ((!d_p && nnz > 0) || (!d_w && n > 0)) return SAMO_ERR_NULL;
+    if (misaligned(d_p) || misaligned(d_w)) return SAMO_ERR_ALIGN;
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, const_cast<float *>(d_p), nullptr, nullptr, d_w, nullptr, nullptr};
+    return hip_status(launch_decompress(L, as_stream(stream)));
+}
+
+samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_idx, int64_t nnz,
+                              float inv_loss_scale, float *d_gc, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (!d_idx && nnz > 0 && nnz != n) return SAMO_ERR_NULL;      /* NULL idx = dense layer */
+    if (nnz > 0 && (!d_g || !d_gc)) return SAMO_ERR_NULL;
+    if (misaligned(d_g) || misaligned(d_idx) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, d_gc};
+    return hip_status(launch_gather(L, inv_loss_scale, as_stream(stream)));
+}
+
+samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,
+                           const samo_adam_cfg *h_cfg, void *stream)
+{
+    if (nnz < 0 || nnz > kMaxN) return SAMO_ERR_SIZE;
+    if (nnz > 0 && (!d_p || !d_m || !d_v || !d_gc)) return SAMO_ERR_NULL;
+    if (misaligned(d_p) || misaligned(d_m) || misaligned(d_v) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
+    AdamK k;
+    if (samo_status s = make_adam(h_cfg, &k)) return s;
+    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_m, d_v, nullptr, nullptr, const_cast<float *>(d_gc)};
+    return hip_status(launch_adam(L, k, as_stream(stream)));
+}
+
+samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                            const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m, float *d_v,
+                            float inv_loss_scale, const samo_adam_cfg *h_cfg, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (samo_status s = check_index_args(d_idx, d_seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
+    if (n > 0 && (!d_g || !d_w)) return SAMO_ERR_NULL;
+    if (nnz > 0 && (!d_p || !d_m || !d_v)) return SAMO_ERR_NULL;
+    if (misaligned(d_g) || misaligned(d_w) || misaligned(d_p) || misaligned(d_m) || misaligned(d_v))
+        return SAMO_ERR_ALIGN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    AdamK k;
+    if (samo_status s = make_adam(h_cfg, &k)) return s;
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr};
+    return hip_status(launch_fused(L, inv_loss_scale, k, as_stream(stream)));
+}
+
+// ------------------------------------------------------------------------------ plan
+samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, samo_plan **out)
+{
+    if (!out) return SAMO_ERR_NULL;
+    *out = nullptr;
+    if (num_layers < 0) return SAMO_ERR_SIZE;
+    if (num_layers > 0 && !h_layers) return SAMO_ERR_NULL;
+
+    samo_plan *plan = new (std::nothrow) samo_plan;
+    if (!plan) return SAMO_ERR_HIP;
+    samo_status st = SAMO_OK;
+    for (int32_t l = 0; l < num_layers && st == SAMO_OK; ++l) {
+        const samo_layer &L = h_layers[l];
+        st = check_sizes(L.n, L.nnz);
+        if (st == SAMO_OK) st = check_index_args(L.idx, L.seg_ptr, L.n, L.nnz, /*allow_dense=*/true);
+        if (st == SAMO_OK && !L.p && L.nnz > 0) st = SAMO_ERR_NULL;
+        if (st == SAMO_OK && (misaligned(L.p) || misaligned(L.m) || misaligned(L.v) || misaligned(L.w) ||
+                              misaligned(L.g) || misaligned(L.gc)))
+            st = SAMO_ERR_ALIGN;
+        if (st != SAMO_OK) break;
+        if (L.nnz > 0) {
+            plan->has_m &= L.m != nullptr;
+            plan->has_v &= L.v != nullptr;
+            plan->has_gc &= L.gc != nullptr;
+        }
+        if (L.n > 0) {
+            plan->has_w &= L.w != nullptr;
+            plan->has_g &= L.g != nullptr;
+        }
+        plan->n_total += L.n;
+        plan->nnz_total += L.nnz;
+        plan->ntiles += ceil_div(L.n, kTile);
+        plan->nchunks += ceil_div(L.nnz, kChunk);
+    }
+    if (st == SAMO_OK && (plan->ntiles > kMaxN || plan->nchunks > kMaxN)) st = SAMO_ERR_SIZE;
+    if (st != SAMO_OK) {
+        delete plan;
+        return st;
+    }
+    plan->layers.assign(h_layers, h_layers + num_layers);
+
+    std::vector<WgRec> tiles((size_t)plan->ntiles), chunks((size_t)plan->nchunks);
+    size_t ti = 0, ci = 0;
+    for (int32_t l = 0; l < num_layers; ++l) {
+        const int64_t nt = ceil_div(h_layers[l].n, kTile), nc = ceil_div(h_layers[l].nnz, kChunk);
+        for (int64_t t = 0; t < nt; ++t) tiles[ti++] = WgRec{l, (int32_t)t};
+        for (int64_t c = 0; c < nc; ++c) chunks[ci++] = WgRec{l, (int32_t)c};
+    }
+
+    hipError_t e = hipSuccess;
+    auto upload = [&e](const void *src, size_t bytes, void **dst) {
+        if (e != hipSuccess || bytes == 0) return;
+        e = hipMalloc(dst, bytes);
+        if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
+    };
+    upload(plan->layers.data(), plan->layers.size() * sizeof(samo_layer), reinterpret_cast<void **>(&plan->d_layers));
+    upload(tiles.data(), tiles.size() * sizeof(WgRec), reinterpret_cast<void **>(&plan->d_tiles));
+    upload(chunks.data(), chunks.size() * sizeof(WgRec), reinterpret_cast<void **>(&plan->d_chunks));
+    if (e != hipSuccess) {
+        samo_plan_destroy(plan);
+        return SAMO_ERR_HIP;
+    }
+    *out = plan;
+    return SAMO_OK;
+}
+
+samo_status samo_plan_destroy(samo_plan *plan)
+{
+    if (!plan) return SAMO_OK;
+    hipError_t e = hipSuccess;
+    if (plan->d_layers) e = hipFree(plan->d_layers);
+    if (plan->d_tiles) { hipError_t e2 = hipFree(plan->d_tiles); if (e == hipSuccess) e = e2; }
+    if (plan->d_chunks) { hipError_t e2 = hipFree(plan->d_chunks); if (e == hipSuccess) e = e2; }
+    delete plan;
+    return hip_status(e);
+}
+
+samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *nnz_total)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (n_total) *n_total = plan->n_total;
+    if (nnz_total) *nnz_total = plan->nnz_total;
+    return SAMO_OK;
+}
+
+samo_status samo_decompress_batched(const samo_plan *plan, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_w) return SAMO_ERR_PLAN;
+    return hip_status(launch_decompress_batched(plan->d_layers, plan->d_tiles, plan->ntiles, as_stream(stream)));
+}
+
+samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_g || !plan->has_gc) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    return hip_status(launch_gather_batched(plan->d_layers, plan->d_chunks, plan->nchunks, inv_loss_scale,
+                                            as_stream(stream)));
+}
+
+samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_m || !plan->has_v || !plan->has_gc) return SAMO_ERR_PLAN;
+    AdamK k;
+    if (samo_status s = make_adam(h_cfg, &k)) return s;
+    return hip_status(launch_adam_batched(plan->d_layers, plan->d_chunks, plan->nchunks, k, as_stream(stream)));
+}
+
+samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale, const samo_adam_cfg *h_cfg,
+                                    void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_m || !plan->has_v || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    AdamK k;
+    if (samo_status s = make_adam(h_cfg, &k)) return s;
+    return hip_status(launch_fused_batched(plan->d_layers, plan->d_tiles, plan->ntiles, inv_loss_scale, k,
+                                           as_stream(stream)));
+}
+
+samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper_default, int64_t *paper_samo,
+                              int64_t *resident)
+{
+    if (n_total < 0 || nnz_total < 0 || nnz_total > n_total) return SAMO_ERR_SIZE;
+    if (n_total > (INT64_MAX / 64)) return SAMO_ERR_SIZE;
+    if (paper_default) *paper_default = 20 * n_total;
+    if (paper_samo) *paper_samo = 24 * nnz_total + 2 * n_total;
+    if (resident) *resident = 16 * nnz_total + 2 * n_total;
+    return SAMO_OK;
+}
+
+samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void *stream)
+{
+    if (bytes < 0 || (bytes & 15)) return SAMO_ERR_SIZE;
+    if (bytes > 0 && (!d_dst || !d_src)) return SAMO_ERR_NULL;
+    if (misaligned(d_dst) || misaligned(d_src)) return SAMO_ERR_ALIGN;
+    return hip_status(launch_copy(d_dst, d_src, bytes, as_stream(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Internal declarations shared by the translation units of libsamo (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "samo.h"
+
+namespace samo {
+
+constexpr int kThreads = 256;           // 4 wavefronts of 64 lanes per workgroup
+constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
+constexpr int kTile = 8192;             // dense elements owned by one workgroup (16 KiB of fp16)
+constexpr int kSegsPerTile = kTile / kSeg;
+constexpr int kChunk = 2048;            // compressed elements per workgroup in the flat kernels
+
+static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");
+static_assert(kTile % (8 * kThreads) == 0, "a tile is written out as whole 16-byte vectors per thread");
+static_assert(kChunk % (4 * kThreads) == 0, "a chunk is whole float4 vectors per thread");
+
+// Adam constants prepared on the host in double precision, rounded once to fp32.
+struct AdamK {
+    float lr, b1, b2, omb1, omb2, eps, wd;
+    float rbc1, rbc2;   // 1 / (1 - beta^t)
+    int l2, decoupled;
+};
+
+// Workgroup -> (layer, local tile or chunk) record of the batched launches.
+struct WgRec {
+    int32_t layer;
+    int32_t local;
+};
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- launchers (each returns hipGetLastError() after enqueueing) -----------------------
+hipError_t launch_count(const uint8_t *mask, int64_t n, int32_t *seg_ptr, int64_t *nnz, hipStream_t s);
+hipError_t launch_fill(const uint8_t *mask, int64_t n, const int32_t *seg_ptr, int32_t *idx,
+                       int64_t cap, hipStream_t s);
+hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr,
+                                   hipStream_t s);
+hipError_t launch_validate(const int32_t *idx, int64_t nnz, int64_t n, const int32_t *seg_ptr,
+                           int32_t *ok, hipStream_t s);
+
+hipError_t launch_decompress(const samo_layer &layer, hipStream_t s);
+hipError_t launch_fused(const samo_layer &layer, float inv_scale, const AdamK &k, hipStream_t s);
+hipError_t launch_gather(const samo_layer &layer, float inv_scale, hipStream_t s);
+hipError_t launch_adam(const samo_layer &layer, const AdamK &k, hipStream_t s);
+
+hipError_t launch_decompress_batched(const samo_layer *d_layers, const WgRec *d_tiles, int64_t ntiles,
+                                     hipStream_t s);
+hipError_t launch_fused_batched(const samo_layer *d_layers, const WgRec *d_tiles, int64_t ntiles,
+                                float inv_scale, const AdamK &k, hipStream_t s);
+hipError_t launch_gather_batched(const samo_layer *d_layers, const WgRec *d_chunks, int64_t nchunks,
+                                 float inv_scale, hipStream_t s);
+hipError_t launch_adam_batched(const samo_layer *d_layers, const WgRec *d_chunks, int64_t nchunks,
+                               const AdamK &k, hipStream_t s);
+
+hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
+
+}  // namespace samo

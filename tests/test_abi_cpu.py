@@ -1,0 +1,135 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2302_05045_amd as samo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # non-null, 16-byte aligned; never dereferenced on these paths
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "samo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(samo_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"samo_build_index", "samo_decompress", "samo_gather_grads", "samo_adam_step",
+            "samo_fused_step", "samo_fused_step_batched"} <= set(names)
+    handle = ctypes.CDLL(samo.LIB_PATH)
+    for name in names:
+        assert hasattr(handle, name), name
+    assert set(names) == set(samo._SIGNATURES), "binding and header disagree"
+
+
+def test_abi_version_and_strings():
+    L = samo.lib()
+    assert L.samo_abi_version() == 1
+    assert samo.status_string(0) == "ok"
+    for s in range(-6, 0):
+        assert samo.status_string(s) not in ("ok", "unknown status")
+    assert samo.status_string(-99) == "unknown status"
+
+
+def test_seg_ptr_len():
+    L = samo.lib()
+    assert L.samo_seg_ptr_len(0) == 1
+    assert L.samo_seg_ptr_len(1) == 2
+    assert L.samo_seg_ptr_len(1024) == 2
+    assert L.samo_seg_ptr_len(1025) == 3
+    assert L.samo_seg_ptr_len(2**31 - 1) == 2**21 + 1
+    assert L.samo_seg_ptr_len(2**31) == -1
+    assert L.samo_seg_ptr_len(-1) == -1
+
+
+def _cfg(**kw):
+    base = dict(step=1, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, decoupled_wd=0)
+    base.update(kw)
+    return samo.adam_cfg(**base)
+
+
+def test_size_and_null_rejection():
+    L = samo.lib()
+    big = 2**31
+    assert L.samo_decompress(FAKE, FAKE, FAKE, 1, FAKE, big, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_decompress(FAKE, FAKE, FAKE, 5, FAKE, 4, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_decompress(FAKE, FAKE, FAKE, -1, FAKE, 4, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_decompress(None, FAKE, FAKE, 1, FAKE, 4, None) == samo.SAMO_ERR_NULL
+    assert L.samo_decompress(FAKE, None, FAKE, 1, FAKE, 4, None) == samo.SAMO_ERR_NULL
+    assert L.samo_decompress(FAKE, FAKE, None, 1, FAKE, 4, None) == samo.SAMO_ERR_NULL
+    assert L.samo_decompress(FAKE, FAKE, FAKE, 1, None, 4, None) == samo.SAMO_ERR_NULL
+    assert L.samo_decompress(FAKE, None, None, 3, FAKE, 4, None) == samo.SAMO_ERR_SIZE  # dense needs nnz == n
+    assert L.samo_decompress(FAKE + 4, FAKE, FAKE, 1, FAKE, 4, None) == samo.SAMO_ERR_ALIGN
+    assert L.samo_decompress(FAKE, FAKE, FAKE, 1, FAKE + 2, 4, None) == samo.SAMO_ERR_ALIGN
+    assert L.samo_build_index(FAKE, big, FAKE, 1, FAKE, FAKE, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_build_index(None, 8, FAKE, 8, FAKE, FAKE, None) == samo.SAMO_ERR_NULL
+    assert L.samo_build_index(FAKE, 8, None, 8, FAKE, FAKE, None) == samo.SAMO_ERR_NULL
+    assert L.samo_build_index(FAKE, 8, FAKE, -1, FAKE, FAKE, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_count_nonzero(FAKE, 8, None, FAKE, None) == samo.SAMO_ERR_NULL
+    assert L.samo_count_nonzero(FAKE + 1, 8, FAKE, FAKE, None) == samo.SAMO_ERR_ALIGN
+    assert L.samo_gather_grads(FAKE, 8, None, 4, 1.0, FAKE, None) == samo.SAMO_ERR_NULL
+    assert L.samo_gather_grads(None, 8, FAKE, 4, 1.0, FAKE, None) == samo.SAMO_ERR_NULL
+    assert L.samo_stream_copy(FAKE, FAKE, 24, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_validate_index(FAKE, 4, 8, None, None, None) == samo.SAMO_ERR_NULL
+
+
+@pytest.mark.parametrize("kw", [dict(step=0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0), dict(eps=float("nan")),
+                                dict(lr=float("inf")), dict(weight_decay=-1.0)])
+def test_bad_adam_hyperparameters(kw):
+    L = samo.lib()
+    cfg = _cfg(**kw)
+    assert L.samo_adam_step(FAKE, FAKE, FAKE, FAKE, 4, ctypes.byref(cfg), None) == samo.SAMO_ERR_ARG
+    assert L.samo_fused_step(FAKE, FAKE, 8, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 1.0, ctypes.byref(cfg), None) \
+        == samo.SAMO_ERR_ARG
+
+
+@pytest.mark.parametrize("scale", [0.0, -1.0, float("inf"), float("nan")])
+def test_bad_loss_scale(scale):
+    L = samo.lib()
+    cfg = _cfg()
+    assert L.samo_gather_grads(FAKE, 8, FAKE, 4, scale, FAKE, None) == samo.SAMO_ERR_ARG
+    assert L.samo_fused_step(FAKE, FAKE, 8, FAKE, FAKE, 4, FAKE, FAKE, FAKE, scale, ctypes.byref(cfg), None) \
+        == samo.SAMO_ERR_ARG
+
+
+def test_null_cfg_and_plan():
+    L = samo.lib()
+    assert L.samo_adam_step(FAKE, FAKE, FAKE, FAKE, 4, None, None) == samo.SAMO_ERR_NULL
+    assert L.samo_fused_step_batched(None, 1.0, ctypes.byref(_cfg()), None) == samo.SAMO_ERR_NULL
+    assert L.samo_plan_destroy(None) == samo.SAMO_OK
+    out = ctypes.c_void_p()
+    bad = (samo.LayerDesc * 1)()
+    bad[0].n, bad[0].nnz = 8, 9
+    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_SIZE
+    bad[0].nnz = 4
+    bad[0].idx, bad[0].seg_ptr = FAKE, FAKE
+    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_NULL      # p missing
+    bad[0].p = FAKE + 8
+    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_ALIGN
+    assert not out.value
+
+
+def test_memory_model_matches_paper_formulas(golden_dir):
+    from conftest import read_golden
+    gold = read_golden(golden_dir + "/memory_model.txt")
+    phi, nnz = 2_516_582_400, 251_658_240
+    d, s, r = samo.samo_memory_model(phi, nnz)
+    assert d == int(gold["default_bytes_per_param"]) * phi
+    assert s == int(gold["samo_bytes_per_kept_param"]) * nnz + int(gold["samo_bytes_per_param"]) * phi
+    assert round(100 * (d - s) / d) == int(gold["saved_percent_at_0.9"])
+    assert r == 16 * nnz + 2 * phi
+    with pytest.raises(samo.SamoError):
+        samo.samo_memory_model(10, 11)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        samo.samo_decompress(torch.zeros(4), torch.zeros(4, dtype=torch.int32), torch.zeros(2, dtype=torch.int32),
+                             torch.zeros(8, dtype=torch.float16))
