@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the SAMO compressed-parameter pipeline on one MI355X.
+
+A "step" is one fused optimizer phase (Section III-C of the paper: gradient
+compression + up-cast + unscale, Adam on the compressed fp32 state, 16-bit copy,
+expansion into the zero-filled dense fp16 weights) over every weight matrix of
+the workload, issued as ONE batched launch (samo_fused_step_batched).  The
+default workload is the GPT-3 2.7B shape of Table I at 90 % magnitude pruning
+(32 layers x {QKV, proj, FC1, FC2}, hidden 2560, FFN 10240): synthetic weights,
+gradients and masks (samo_inputs), resident in HBM before the timed region.
+
+Prints one JSON line: nonzero params/s for the step, the HBM roofline of the
+fused kernel (algorithmic bytes 28*nnz + 4*N per launch over the mean launch
+duration from HIP events on the launch stream), the same figures for the
+unfused entries, and the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt2.7b", choices=["fc1024", "gpt350m", "gpt1.3b", "gpt2.7b", "gpt6.7b"])
+    ap.add_argument("--sparsity", type=float, default=0.9)
+    ap.add_argument("--layers", type=int, default=None, help="truncate the model (debugging only)")
+    ap.add_argument("--cpu-layers", type=int, default=None,
+                    help="transformer layers in the CPU-oracle sample (default: whole workload up to 32 layers)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-entries", action="store_true", help="skip the per-entry (unfused) timings")
+    ap.add_argument("--gen-workers", type=int, default=int(os.environ.get("SAMO_GEN_WORKERS", "12")))
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2302_05045_amd as samo
+    import samo_inputs as si
+
+    samo.lib()                                    # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    specs = si.config(args.workload, args.sparsity, layers=args.layers)
+    inv = 1.0 / si.LOSS_SCALE
+
+    # ---------------------------------------------------------------- inputs -> HBM
+    t_gen = time.time()
+    cpu_keep = 0
+    if not args.no_cpu_baseline:
+        per_layer = 4 if args.workload.startswith("gpt") else 1
+        nl = args.cpu_layers if args.cpu_layers is not None else 32
+        cpu_keep = min(len(specs), nl * per_layer)
+    host = []                                     # host copies for the CPU-oracle sample
+    layers = []
+    index_ms = []
+
+    def consume(i, data):
+        spec = data.spec
+        dense = spec.mask_kind == "dense"
+        if dense:
+            idx = seg_ptr = None
+            p_host = data.w32
+        else:
+            d_mask = torch.from_numpy(data.mask).to(dev)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            seg_ptr = torch.empty(samo.samo_seg_ptr_len(spec.n), dtype=torch.int32, device=dev)
+            nnz_out = torch.empty(1, dtype=torch.int64, device=dev)
+            samo.samo_count_nonzero(d_mask, seg_ptr, nnz_out)
+            idx = torch.empty(int(nnz_out.item()), dtype=torch.int32, device=dev)
+            e0.record(stream)
+            samo.samo_build_index_into(d_mask, idx, seg_ptr, nnz_out)     # a0: count + scan + fill
+            e1.record(stream)
+            e1.synchronize()
+            index_ms.append((e0.elapsed_time(e1), spec.n, idx.numel()))
+            del d_mask
+            p_host = data.w32[data.mask != 0]                    # the pruner hands over kept weights
+        p = torch.from_numpy(p_host).to(dev)
+        g = torch.from_numpy(data.g16.view(np.int16)).to(dev).view(torch.float16)
+        layers.append(samo.Layer(spec.n, idx, seg_ptr, p, torch.zeros_like(p), torch.zeros_like(p),
+                                 torch.empty(spec.n, dtype=torch.float16, device=dev), g,
+                                 torch.empty_like(p)))
+        if i < cpu_keep:
+            host.append((spec, data.mask, np.ascontiguousarray(p_host), data.g16))
+
+    si.generate(specs, consume, workers=args.gen_workers)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    plan = samo.Plan(layers)
+    n_total, nnz_total = plan.totals()
+    fused_bytes = 28 * nnz_total + 4 * n_total
+
+    def cfg(t):
+        return samo.adam_cfg(t, **si.ADAM)
+
+    # ---------------------------------------------------------------- the timed step
+    plan.samo_decompress_batched()                # theta16 for the first forward pass (not timed)
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        plan.samo_fused_step_batched(inv, cfg(t))
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    events[0].record(stream)
+    for k in range(args.steps):
+        t += 1
+        plan.samo_fused_step_batched(inv, cfg(t))
+        events[k + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    launch_ms = [events[k].elapsed_time(events[k + 1]) for k in range(args.steps)]
+    kernel_ms = float(np.mean(launch_ms))
+    ms_per_step = wall * 1e3 / args.steps
+    value = nnz_total / (ms_per_step * 1e-3)
+
+    def time_entry(fn, iters=10, warm=2):
+        for _ in range(warm):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record(stream)
+        for k in range(iters):
+            fn()
+            ev[k + 1].record(stream)
+        torch.cuda.synchronize()
+        return float(np.mean([ev[k].elapsed_time(ev[k + 1]) for k in range(iters)]))
+
+    entries = {}
+    if not args.no_entries:
+        def entry(name, ms, nbytes):
+            entries[name] = {"ms": round(ms, 4), "algorithmic_GB": round(nbytes / 1e9, 4),
+                             "GB/s": round(nbytes / ms / 1e6, 1), "frac_of_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        entry("samo_gather_batched", time_entry(lambda: plan.samo_gather_batched(inv)), 8 * nnz_total + 2 * n_total)
+        entry("samo_adam_batched", time_entry(lambda: plan.samo_adam_batched(cfg(t + 1))), 28 * nnz_total)
+        entry("samo_decompress_batched", time_entry(plan.samo_decompress_batched), 8 * nnz_total + 2 * n_total)
+        if index_ms:
+            ms = sum(x[0] for x in index_ms)
+            entry("samo_build_index(per layer, summed)", ms, sum(2 * x[1] + 4 * x[2] for x in index_ms))
+        nb = min(4 << 30, max(1 << 20, (fused_bytes // 2) & ~15))
+        src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        entry("samo_stream_copy(ceiling)", time_entry(lambda: samo.samo_stream_copy(dst, src)), 2 * nb)
+        del src, dst
+
+    achieved = fused_bytes / kernel_ms / 1e6
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_fused_%s_p%02d.json" % (args.workload, round(args.sparsity * 100)))
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch")
+
+    # ---------------------------------------------------------------- CPU oracle on this host
+    cpu = None
+    if host:
+        import oracle
+        ocfg = oracle.AdamCfg(**si.ADAM)
+        state = []
+        for spec, mask, p_host, g16 in host:
+            idx = oracle.build_index(mask)
+            state.append((spec, idx, p_host.copy(), np.zeros_like(p_host), np.zeros_like(p_host), g16,
+                          np.empty(spec.n, np.uint16)))
+        best = None
+        for rep in (1, 2):
+            t0 = time.perf_counter()
+            for spec, idx, p, m, v, g16, w in state:
+                oracle.step(g16, spec.n, idx, p, m, v, inv, ocfg, rep, w)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            if dt > 20:
+                break
+        cpu_nnz = sum(s[1].shape[0] for s in state)
+        cpu = {"value": round(cpu_nnz / best, 1), "unit": "nonzero params/s", "cores": 1, "kind": "oracle",
+               "sample": "%d of %d weight matrices of the workload (%d nonzeros), one gather+Adam+expand step, "
+                         "best of <=2, single thread" % (len(state), len(specs), cpu_nnz),
+               "seconds": round(best, 3), "host_cpus": os.cpu_count()}
+
+    out = {
+        "metric": "nonzero params/sec per SAMO step",
+        "value": round(value, 1),
+        "unit": "nonzero params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s shape, %d weight matrices, %.0f%% %s-pruned, fused gather+Adam+expand step, "
+                               "one batched launch" % (args.workload, len(specs), 100 * args.sparsity,
+                                                       specs[0].mask_kind),
+                   "N": n_total, "nnz": nnz_total, "sparsity": args.sparsity,
+                   "resident_bytes": samo.samo_memory_model(n_total, nnz_total)[2]},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": "tile_kernel<fused,batched>", "kernel_ms": round(kernel_ms, 4),
+                     "algorithmic_bytes_per_launch": fused_bytes},
+        "cpu_baseline": cpu,
+        "entries": entries,
+        "setup_seconds": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+    plan.close()
+
+
+if __name__ == "__main__":
+    main()
