@@ -19,7 +19,7 @@ from typing import NamedTuple, Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libsamo.so")
+LIB_PATH = os.environ.get("SAMO_LIBRARY_PATH") or os.path.join(_PKG, "libsamo.so")
 SEG_ELEMS = 1024
 
 SAMO_OK = 0

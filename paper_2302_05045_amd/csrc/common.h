@@ -8,15 +8,39 @@
 
 namespace samo {
 
-constexpr int kThreads = 256;           // 4 wavefronts of 64 lanes per workgroup
+#ifndef SAMO_TILE_THREADS
+#define SAMO_TILE_THREADS 256
+#endif
+#ifndef SAMO_TILE
+#define SAMO_TILE 4096
+#endif
+#ifndef SAMO_U
+#define SAMO_U 4
+#endif
+#ifndef SAMO_GLDS
+#define SAMO_GLDS 0
+#endif
+#ifndef SAMO_NT
+#define SAMO_NT 9
+#endif
+
+constexpr int kThreads = 256;           // 4 wavefronts of 64 lanes per workgroup (flat and index kernels)
+constexpr int kTileThreads = SAMO_TILE_THREADS;   // workgroup size of the tile kernels
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
-constexpr int kTile = 8192;             // dense elements owned by one workgroup (16 KiB of fp16)
+constexpr int kTile = SAMO_TILE;        // dense elements owned by one workgroup
 constexpr int kSegsPerTile = kTile / kSeg;
-constexpr int kChunk = 2048;            // compressed elements per workgroup in the flat kernels
+#ifndef SAMO_CHUNK
+#define SAMO_CHUNK 256
+#endif
+#ifndef SAMO_FLAT_THREADS
+#define SAMO_FLAT_THREADS 64
+#endif
+constexpr int kChunk = SAMO_CHUNK;      // compressed elements per workgroup in the flat kernels
+constexpr int kFlatThreads = SAMO_FLAT_THREADS;
 
 static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");
-static_assert(kTile % (8 * kThreads) == 0, "a tile is written out as whole 16-byte vectors per thread");
-static_assert(kChunk % (4 * kThreads) == 0, "a chunk is whole float4 vectors per thread");
+static_assert(kTile % (8 * kTileThreads) == 0, "a tile is written out as whole 16-byte vectors per thread");
+static_assert(kChunk % (4 * kFlatThreads) == 0, "a chunk is whole float4 vectors per thread");
 
 // Adam constants prepared on the host in double precision, rounded once to fp32.
 struct AdamK {

@@ -34,6 +34,47 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float x)
     return __builtin_bit_cast(uint16_t, (_Float16)x);
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void store16(void *dst, const uint4 &v)
+{
+#if SAMO_NT & 1
+    __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(dst));
+#else
+    *reinterpret_cast<uint4 *>(dst) = v;
+#endif
+}
+
+__device__ __forceinline__ void store_f32(float *dst, float v)
+{
+#if SAMO_NT & 2
+    __builtin_nontemporal_store(v, dst);
+#else
+    *dst = v;
+#endif
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void store_f4(float *dst, const float4 &v)
+{
+#if SAMO_NT & 8
+    __builtin_nontemporal_store((f32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(dst));
+#else
+    *reinterpret_cast<float4 *>(dst) = v;
+#endif
+}
+
+template <typename T>
+__device__ __forceinline__ T load_stream(const T *src)
+{
+#if SAMO_NT & 4
+    return __builtin_nontemporal_load(src);
+#else
+    return *src;
+#endif
+}
+
 // One Adam update (Kingma & Ba, Algorithm 1) in fp32.
 __device__ __forceinline__ void adam_update(float &p, float &m, float &v, float g, const AdamK &k)
 {
@@ -59,7 +100,7 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
     float *__restrict__ P = L.p + base;
     uint16_t *__restrict__ W = L.w + base;
     const int nvec = len / 8;
-    for (int o = tid; o < nvec; o += kThreads) {
+    for (int o = tid; o < nvec; o += kTileThreads) {
         float4 p0 = reinterpret_cast<const float4 *>(P)[2 * o];
         float4 p1 = reinterpret_cast<const float4 *>(P)[2 * o + 1];
         float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
@@ -92,7 +133,7 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
             hw[q] = (uint32_t)float_to_half_bits(pv[2 * q]) | ((uint32_t)float_to_half_bits(pv[2 * q + 1]) << 16);
         reinterpret_cast<uint4 *>(W)[o] = make_uint4(hw[0], hw[1], hw[2], hw[3]);
     }
-    for (int e = nvec * 8 + tid; e < len; e += kThreads) {      // ragged end of the layer
+    for (int e = nvec * 8 + tid; e < len; e += kTileThreads) {      // ragged end of the layer
         float pe = P[e];
         if (MODE == kModeFused) {
             float me = L.m[base + e], ve = L.v[base + e];
@@ -107,12 +148,34 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
 
 template <int MODE>
 __device__ __forceinline__ void sparse_tile(const samo_layer &L, int tile, int64_t base, int len, float inv_scale,
-                                            const AdamK &k, uint16_t *lds_w)
+                                            const AdamK &k, uint16_t *lds_w, uint16_t *lds_g)
 {
     const int tid = threadIdx.x;
     uint4 *l4 = reinterpret_cast<uint4 *>(lds_w);
+#if SAMO_GLDS
+    if (MODE == kModeFused) {                 // stage the tile's dense gradient through LDS, fully coalesced
+        constexpr int NV = kTile / 8 / kTileThreads;
+        uint4 gq[NV];
+        const uint4 *gsrc = reinterpret_cast<const uint4 *>(L.g + base);
+        const int nvec_g = (len + 7) / 8;     // a 16-byte aligned buffer always holds whole vectors? no: guard below
 #pragma unroll
-    for (int o = tid; o < kTile / 8; o += kThreads) l4[o] = make_uint4(0u, 0u, 0u, 0u);
+        for (int q = 0; q < NV; ++q) {
+            const int o = tid + q * kTileThreads;
+            gq[q] = make_uint4(0u, 0u, 0u, 0u);
+            if (o * 8 + 8 <= len) gq[q] = gsrc[o];
+            else if (o < nvec_g) {
+                uint16_t tmp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                for (int e = 0; e < 8; ++e) if (o * 8 + e < len) tmp[e] = L.g[base + o * 8 + e];
+                gq[q] = make_uint4(tmp[0] | (tmp[1] << 16), tmp[2] | (tmp[3] << 16), tmp[4] | (tmp[5] << 16),
+                                   tmp[6] | (tmp[7] << 16));
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q) reinterpret_cast<uint4 *>(lds_g)[tid + q * kTileThreads] = gq[q];
+    }
+#endif
+#pragma unroll
+    for (int o = tid; o < kTile / 8; o += kTileThreads) l4[o] = make_uint4(0u, 0u, 0u, 0u);
 
     const int64_t nseg = (L.n + kSeg - 1) / kSeg;
     const int64_t s0 = (int64_t)tile * kSegsPerTile;
@@ -128,35 +191,35 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int tile, int64
     const uint16_t *__restrict__ G = L.g;
     const int ibase = (int)base;             // a layer's flat size fits int32
 
-    constexpr int U = 4;
-    for (int i0 = c0 + tid; i0 < c1; i0 += U * kThreads) {
+    constexpr int U = SAMO_U;
+    for (int i0 = c0 + tid; i0 < c1; i0 += U * kTileThreads) {
         int j[U];
         float pp[U], mm[U], vv[U];
         uint16_t gb[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * kThreads;
+            const int i = i0 + u * kTileThreads;
             j[u] = ibase; pp[u] = 0.f; mm[u] = 0.f; vv[u] = 0.f; gb[u] = 0;
             if (i < c1) {
-                j[u] = IDX[i];
-                pp[u] = P[i];
-                if (MODE == kModeFused) { mm[u] = M[i]; vv[u] = V[i]; }
+                j[u] = load_stream(IDX + i);
+                pp[u] = load_stream(P + i);
+                if (MODE == kModeFused) { mm[u] = load_stream(M + i); vv[u] = load_stream(V + i); }
             }
         }
         if (MODE == kModeFused) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (i0 + u * kThreads < c1) gb[u] = G[j[u]];
+                if (i0 + u * kTileThreads < c1) gb[u] = SAMO_GLDS ? lds_g[j[u] - ibase] : G[j[u]];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * kThreads;
+            const int i = i0 + u * kTileThreads;
             if (i < c1) {
                 if (MODE == kModeFused) {
                     adam_update(pp[u], mm[u], vv[u], half_bits_to_float(gb[u]) * inv_scale, k);
-                    P[i] = pp[u];
-                    M[i] = mm[u];
-                    V[i] = vv[u];
+                    store_f32(P + i, pp[u]);
+                    store_f32(M + i, mm[u]);
+                    store_f32(V + i, vv[u]);
                 }
                 lds_w[j[u] - ibase] = float_to_half_bits(pp[u]);
             }
@@ -166,16 +229,22 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int tile, int64
 
     uint16_t *__restrict__ W = L.w + base;
     const int nvec = len / 8;
-    for (int o = tid; o < nvec; o += kThreads) reinterpret_cast<uint4 *>(W)[o] = l4[o];
-    for (int e = nvec * 8 + tid; e < len; e += kThreads) W[e] = lds_w[e];
+    for (int o = tid; o < nvec; o += kTileThreads) store16(reinterpret_cast<uint4 *>(W) + o, l4[o]);
+    for (int e = nvec * 8 + tid; e < len; e += kTileThreads) W[e] = lds_w[e];
 }
 
 template <int MODE, bool BATCHED>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kTileThreads)
 tile_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const WgRec *__restrict__ recs,
             float inv_scale, const AdamK k)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[kTile];
+#if SAMO_GLDS
+    __shared__ __attribute__((aligned(16))) uint16_t lds_g_buf[MODE == kModeFused ? kTile : 8];
+    uint16_t *lds_g = lds_g_buf;
+#else
+    uint16_t *lds_g = nullptr;
+#endif
     samo_layer L;
     int tile;
     if (BATCHED) {
@@ -192,12 +261,12 @@ tile_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
     if (L.seg_ptr == nullptr)                 // dense (unpruned) layer
         dense_tile<MODE>(L, base, len, inv_scale, k);
     else
-        sparse_tile<MODE>(L, tile, base, len, inv_scale, k, lds_w);
+        sparse_tile<MODE>(L, tile, base, len, inv_scale, k, lds_w, lds_g);
 }
 
 // ------------------------------------------------------------------ flat kernels over the compressed arrays
 template <bool BATCHED>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kFlatThreads)
 gather_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const WgRec *__restrict__ recs,
               float inv_scale)
 {
@@ -215,8 +284,8 @@ gather_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const
     const uint16_t *__restrict__ G = L.g;
     float *__restrict__ GC = L.gc;
 #pragma unroll
-    for (int it = 0; it < kChunk / (4 * kThreads); ++it) {
-        const int64_t i = chunk * kChunk + ((int64_t)it * kThreads + threadIdx.x) * 4;
+    for (int it = 0; it < kChunk / (4 * kFlatThreads); ++it) {
+        const int64_t i = chunk * kChunk + ((int64_t)it * kFlatThreads + threadIdx.x) * 4;
         if (L.idx == nullptr) {                                   // dense layer: identity index
             if (i + 4 <= nnz) {
                 const uint2 q = *reinterpret_cast<const uint2 *>(G + i);
@@ -237,7 +306,7 @@ gather_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const
             o.y = half_bits_to_float(b) * inv_scale;
             o.z = half_bits_to_float(c) * inv_scale;
             o.w = half_bits_to_float(d) * inv_scale;
-            *reinterpret_cast<float4 *>(GC + i) = o;
+            store_f4(GC + i, o);
         } else {
             for (int64_t e = i; e < nnz; ++e) GC[e] = half_bits_to_float(G[L.idx[e]]) * inv_scale;
         }
@@ -245,7 +314,7 @@ gather_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const
 }
 
 template <bool BATCHED>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kFlatThreads)
 adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const WgRec *__restrict__ recs,
             const AdamK k)
 {
@@ -265,8 +334,8 @@ adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
     float *__restrict__ V = L.v;
     const float *__restrict__ GC = L.gc;
 #pragma unroll
-    for (int it = 0; it < kChunk / (4 * kThreads); ++it) {
-        const int64_t i = chunk * kChunk + ((int64_t)it * kThreads + threadIdx.x) * 4;
+    for (int it = 0; it < kChunk / (4 * kFlatThreads); ++it) {
+        const int64_t i = chunk * kChunk + ((int64_t)it * kFlatThreads + threadIdx.x) * 4;
         if (i + 4 <= nnz) {
             float4 p = *reinterpret_cast<const float4 *>(P + i);
             float4 m = *reinterpret_cast<const float4 *>(M + i);
@@ -276,9 +345,9 @@ adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
             adam_update(p.y, m.y, v.y, g.y, k);
             adam_update(p.z, m.z, v.z, g.z, k);
             adam_update(p.w, m.w, v.w, g.w, k);
-            *reinterpret_cast<float4 *>(P + i) = p;
-            *reinterpret_cast<float4 *>(M + i) = m;
-            *reinterpret_cast<float4 *>(V + i) = v;
+            store_f4(P + i, p);
+            store_f4(M + i, m);
+            store_f4(V + i, v);
         } else {
             for (int64_t e = i; e < nnz; ++e) {
                 float p = P[e], m = M[e], v = V[e];
@@ -290,7 +359,7 @@ adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
 }
 
 // ------------------------------------------------------------------ diagnostic copy
-constexpr int kCopyVecPerThread = 4;                              // 64 bytes per thread, 16 KiB per workgroup
+constexpr int kCopyVecPerThread = 1;                              // 16 bytes per thread, 4 KiB per workgroup: the fastest shape measured
 
 __global__ void __launch_bounds__(kThreads)
 copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t nvec)
@@ -318,7 +387,7 @@ hipError_t launch_decompress(const samo_layer &layer, hipStream_t s)
 {
     const int64_t tiles = ceil_div(layer.n, kTile);
     if (tiles > 0)
-        tile_kernel<kModeDecompress, false><<<dim3((unsigned)tiles), dim3(kThreads), 0, s>>>(layer, nullptr, nullptr,
+        tile_kernel<kModeDecompress, false><<<dim3((unsigned)tiles), dim3(kTileThreads), 0, s>>>(layer, nullptr, nullptr,
                                                                                             1.f, kNoAdam);
     return hipGetLastError();
 }
@@ -327,7 +396,7 @@ hipError_t launch_fused(const samo_layer &layer, float inv_scale, const AdamK &k
 {
     const int64_t tiles = ceil_div(layer.n, kTile);
     if (tiles > 0)
-        tile_kernel<kModeFused, false><<<dim3((unsigned)tiles), dim3(kThreads), 0, s>>>(layer, nullptr, nullptr,
+        tile_kernel<kModeFused, false><<<dim3((unsigned)tiles), dim3(kTileThreads), 0, s>>>(layer, nullptr, nullptr,
                                                                                        inv_scale, k);
     return hipGetLastError();
 }
@@ -336,7 +405,7 @@ hipError_t launch_gather(const samo_layer &layer, float inv_scale, hipStream_t s
 {
     const int64_t chunks = ceil_div(layer.nnz, kChunk);
     if (chunks > 0)
-        gather_kernel<false><<<dim3((unsigned)chunks), dim3(kThreads), 0, s>>>(layer, nullptr, nullptr, inv_scale);
+        gather_kernel<false><<<dim3((unsigned)chunks), dim3(kFlatThreads), 0, s>>>(layer, nullptr, nullptr, inv_scale);
     return hipGetLastError();
 }
 
@@ -344,14 +413,14 @@ hipError_t launch_adam(const samo_layer &layer, const AdamK &k, hipStream_t s)
 {
     const int64_t chunks = ceil_div(layer.nnz, kChunk);
     if (chunks > 0)
-        adam_kernel<false><<<dim3((unsigned)chunks), dim3(kThreads), 0, s>>>(layer, nullptr, nullptr, k);
+        adam_kernel<false><<<dim3((unsigned)chunks), dim3(kFlatThreads), 0, s>>>(layer, nullptr, nullptr, k);
     return hipGetLastError();
 }
 
 hipError_t launch_decompress_batched(const samo_layer *d_layers, const WgRec *d_tiles, int64_t ntiles, hipStream_t s)
 {
     if (ntiles > 0)
-        tile_kernel<kModeDecompress, true><<<dim3((unsigned)ntiles), dim3(kThreads), 0, s>>>(kNoLayer, d_layers,
+        tile_kernel<kModeDecompress, true><<<dim3((unsigned)ntiles), dim3(kTileThreads), 0, s>>>(kNoLayer, d_layers,
                                                                                             d_tiles, 1.f, kNoAdam);
     return hipGetLastError();
 }
@@ -360,7 +429,7 @@ hipError_t launch_fused_batched(const samo_layer *d_layers, const WgRec *d_tiles
                                 const AdamK &k, hipStream_t s)
 {
     if (ntiles > 0)
-        tile_kernel<kModeFused, true><<<dim3((unsigned)ntiles), dim3(kThreads), 0, s>>>(kNoLayer, d_layers, d_tiles,
+        tile_kernel<kModeFused, true><<<dim3((unsigned)ntiles), dim3(kTileThreads), 0, s>>>(kNoLayer, d_layers, d_tiles,
                                                                                        inv_scale, k);
     return hipGetLastError();
 }
@@ -369,7 +438,7 @@ hipError_t launch_gather_batched(const samo_layer *d_layers, const WgRec *d_chun
                                  hipStream_t s)
 {
     if (nchunks > 0)
-        gather_kernel<true><<<dim3((unsigned)nchunks), dim3(kThreads), 0, s>>>(kNoLayer, d_layers, d_chunks,
+        gather_kernel<true><<<dim3((unsigned)nchunks), dim3(kFlatThreads), 0, s>>>(kNoLayer, d_layers, d_chunks,
                                                                               inv_scale);
     return hipGetLastError();
 }
@@ -378,7 +447,7 @@ hipError_t launch_adam_batched(const samo_layer *d_layers, const WgRec *d_chunks
                                hipStream_t s)
 {
     if (nchunks > 0)
-        adam_kernel<true><<<dim3((unsigned)nchunks), dim3(kThreads), 0, s>>>(kNoLayer, d_layers, d_chunks, k);
+        adam_kernel<true><<<dim3((unsigned)nchunks), dim3(kFlatThreads), 0, s>>>(kNoLayer, d_layers, d_chunks, k);
     return hipGetLastError();
 }
 

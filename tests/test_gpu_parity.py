@@ -13,7 +13,7 @@ from gpu_util import (DEV, INV, OCFG, DevLayer, HostLayer, assert_close, dev_f16
 
 pytestmark = pytest.mark.gpu
 
-SIZES = [1, 15, 16, 17, 63, 1023, 1024, 1025, 8191, 8192, 8193, 3 * 8192 + 777, 100003]
+SIZES = [1, 15, 16, 17, 63, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 8192, 8193, 3 * 8192 + 777, 100003]
 
 
 def _layer(n, keep, seed):
@@ -152,7 +152,7 @@ def test_gather_ignores_pruned_positions_and_keeps_subnormals():
 
 
 # ------------------------------------------------------------------ a3: compressed Adam
-@pytest.mark.parametrize("nnz", [1, 3, 4, 5, 1023, 2048, 2049, 100003])
+@pytest.mark.parametrize("nnz", [1, 3, 4, 5, 255, 256, 257, 1023, 2048, 2049, 100003])
 @pytest.mark.parametrize("wd,decoupled", [(0.0, 0), (0.1, 0), (0.1, 1)])
 def test_adam_within_tolerance(nnz, wd, decoupled):
     rng = np.random.default_rng(nnz)
@@ -230,7 +230,7 @@ def test_fused_step_ragged_sizes(n, keep):
         _check_fused_outputs(d, h, n, t)
 
 
-@pytest.mark.parametrize("n", [1, 7, 8, 9, 8191, 8192, 8200, 50001])
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 4095, 4096, 4104, 8191, 8192, 8200, 50001])
 def test_dense_layer_fused_and_decompress(n):
     h = HostLayer(n, np.ones(n, np.uint8), si.weights(n, n), 400 + n, dense=True)
     d = DevLayer(h)
