@@ -1,0 +1,126 @@
+"""GPU parity at the benchmark's full sizes and launch configuration: every weight matrix of
+a model processed by ONE batched launch, compared with the CPU oracle element by element
+(the C oracle finishes a 2.7B-shape step in a few seconds, so nothing is sampled)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2302_05045_amd as samo
+import samo_inputs as si
+from gpu_util import DEV, INV, OCFG, assert_close, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+class Model:
+    """All layers of a configuration on the GPU (index built by the library) and on the host
+    (index built by the oracle)."""
+
+    def __init__(self, specs, with_gc=False, workers=12):
+        self.specs = specs
+        self.host = []      # (spec, mask, idx, p, m, v, g16)
+        self.layers = []
+
+        def consume(i, data):
+            spec = data.spec
+            ref_idx = oracle.build_index(data.mask)
+            p_host = np.ascontiguousarray(data.w32[ref_idx])
+            if spec.mask_kind == "dense":
+                idx = seg_ptr = None
+            else:
+                ix = samo.samo_build_index(torch.from_numpy(data.mask).to(DEV))
+                assert ix.nnz == ref_idx.shape[0], spec.name
+                assert np.array_equal(ix.idx.cpu().numpy(), ref_idx), spec.name      # bit-exact index
+                idx, seg_ptr = ix.idx, ix.seg_ptr
+            p = torch.from_numpy(p_host).to(DEV)
+            g = torch.from_numpy(data.g16.view(np.int16)).to(DEV).view(torch.float16)
+            w = torch.full((spec.n,), float("nan"), dtype=torch.float16, device=DEV)
+            gc = torch.full_like(p, float("nan")) if with_gc else None
+            self.layers.append(samo.Layer(spec.n, idx, seg_ptr, p, torch.zeros_like(p), torch.zeros_like(p), w, g, gc))
+            self.host.append([spec, data.mask, ref_idx, p_host.copy(), np.zeros_like(p_host), np.zeros_like(p_host),
+                              data.g16])
+
+        si.generate(specs, consume, workers=workers)
+        self.plan = samo.Plan(self.layers)
+
+    def oracle_step(self, t):
+        for spec, mask, idx, p, m, v, g16 in self.host:
+            oracle.step(g16, spec.n, idx, p, m, v, INV, OCFG, t)
+
+    def check(self, t):
+        for L, (spec, mask, idx, p, m, v, g16) in zip(self.layers, self.host):
+            got_p = L.p.cpu().numpy()
+            assert_close(got_p, p, "%s p t=%d" % (spec.name, t))
+            assert_close(L.m.cpu().numpy(), m, "%s m t=%d" % (spec.name, t))
+            assert_close(L.v.cpu().numpy(), v, "%s v t=%d" % (spec.name, t))
+            w_bits = host_bits(L.w)
+            assert np.array_equal(w_bits, oracle.decompress(got_p, idx, spec.n)), "%s w t=%d" % (spec.name, t)
+
+    def poison_w(self):
+        for L in self.layers:
+            L.w.fill_(float("nan"))
+
+
+def test_gpt2p7b_90pct_fused_batched_two_steps():
+    """The configuration bench.py times: 128 matrices, N = 2,516,582,400, one launch per step."""
+    model = Model(si.config("gpt2.7b", 0.9))
+    n_total, nnz_total = model.plan.totals()
+    assert n_total == 2_516_582_400 and nnz_total == 251_658_240
+    for t in (1, 2):
+        model.poison_w()
+        model.plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        model.oracle_step(t)
+        model.check(t)
+
+
+def test_gpt350m_unfused_then_fused():
+    model = Model(si.config("gpt350m", 0.9), with_gc=True)
+    assert model.plan.totals() == (301_989_888, 30_198_984)
+    model.plan.samo_decompress_batched()
+    for L, h in zip(model.layers, model.host):
+        assert np.array_equal(host_bits(L.w), oracle.decompress(h[3], h[2], h[0].n)), h[0].name
+    model.poison_w()
+    model.plan.samo_gather_batched(INV)
+    for L, h in zip(model.layers, model.host):
+        assert np.array_equal(L.gc.cpu().numpy().view(np.uint32), oracle.gather(h[6], h[2], INV).view(np.uint32))
+    model.plan.samo_adam_batched(samo.adam_cfg(1, **si.ADAM))
+    model.plan.samo_decompress_batched()
+    model.oracle_step(1)
+    model.check(1)
+    model.poison_w()
+    model.plan.samo_fused_step_batched(INV, samo.adam_cfg(2, **si.ADAM))
+    model.oracle_step(2)
+    model.check(2)
+
+
+@pytest.mark.parametrize("sparsity", [0.8, 0.95])
+def test_gpt2p7b_sparsity_sweep_slice(sparsity):
+    """Eight layers (32 matrices) of the 2.7B shape at the other sparsities of the sweep."""
+    model = Model(si.config("gpt2.7b", sparsity, layers=8))
+    n_total, nnz_total = model.plan.totals()
+    assert nnz_total == sum(si.kept_count(s.n, sparsity) for s in model.specs)
+    model.poison_w()
+    model.plan.samo_fused_step_batched(INV, samo.adam_cfg(1, **si.ADAM))
+    model.oracle_step(1)
+    model.check(1)
+
+
+def test_gpt6p7b_row_clustered_slice_with_dense_embedding():
+    """Config 5 structure: per-matrix sparsity in [0.8, 0.97], row-clustered masks, plus the dense
+    50304x4096 embedding; SAMO_TEST_6P7B_LAYERS transformer layers (default 2) of the 32."""
+    nl = int(os.environ.get("SAMO_TEST_6P7B_LAYERS", "2"))
+    specs = si.config("gpt6.7b", layers=nl)
+    assert specs[-1].mask_kind == "dense" and specs[-1].n == 50304 * 4096
+    model = Model(specs, workers=6)
+    for t in (1, 2):
+        model.poison_w()
+        model.plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        model.oracle_step(t)
+        model.check(t)
+    # hot rows are ~10x denser than cold rows: tiles differ widely in their compressed slice
+    spec, mask, idx = model.host[0][0], model.host[0][1], model.host[0][2]
+    per_row = mask.reshape(spec.rows, spec.cols).sum(axis=1)
+    assert per_row.max() > 5 * np.median(per_row)
