@@ -32,7 +32,8 @@
  *   - Arguments are validated on the host BEFORE anything is enqueued.  On a
  *     negative status nothing was launched and no output was touched.
  *   - Sizes: 0 <= N <= 2^31 - 1 per layer (the index is 32-bit, Section III-B);
- *     0 <= nnz <= N.  N = 0 and nnz = 0 are valid and do nothing / zero-fill.
+ *     0 <= nnz <= N.  N = 0 and nnz = 0 are valid and do nothing / zero-fill;
+ *     pointers to arrays of nnz elements may be NULL when nnz == 0.
  *   - Alignment: every array pointer must be 16-byte aligned (SAMO_ERR_ALIGN).
  *   - Preconditions NOT checked on the hot path (results undefined if violated;
  *     samo_validate_index checks them): idx strictly ascending, 0 <= idx[i] < N,
@@ -97,6 +98,19 @@ samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_
 samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx,
                              int64_t idx_capacity, int32_t *d_seg_ptr, int64_t *d_nnz,
                              void *stream);
+/* The same for many layers with a handful of launches (count, scan, fill per group of up to 48
+ * jobs), so that small layers do not pay three launches each.  h_jobs is a HOST array of jobs
+ * holding DEVICE pointers; a job with idx == NULL and idx_capacity == 0 only counts.  Every job
+ * is validated before anything is enqueued. */
+typedef struct {
+    const uint8_t *mask;
+    int64_t n;
+    int32_t *idx;
+    int64_t idx_capacity;
+    int32_t *seg_ptr;
+    int64_t *nnz;
+} samo_index_job;
+samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_jobs, void *stream);
 /* seg_ptr for an index that came from elsewhere (e.g. straight from a pruner). */
 samo_status samo_build_seg_ptr(const int32_t *d_idx, int64_t nnz, int64_t n,
                                int32_t *d_seg_ptr, void *stream);

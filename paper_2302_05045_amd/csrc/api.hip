@@ -102,25 +102,57 @@ int64_t samo_seg_ptr_len(int64_t n)
     return ceil_div(n, kSeg) + 1;
 }
 
+samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_jobs, void *stream)
+{
+    if (num_jobs < 0) return SAMO_ERR_SIZE;
+    if (num_jobs > 0 && !h_jobs) return SAMO_ERR_NULL;
+    for (int32_t j = 0; j < num_jobs; ++j) {                      // validate everything before any launch
+        const samo_index_job &J = h_jobs[j];
+        if (J.n < 0 || J.n > kMaxN || J.idx_capacity < 0) return SAMO_ERR_SIZE;
+        if ((!J.mask && J.n > 0) || !J.seg_ptr || !J.nnz || (!J.idx && J.idx_capacity > 0)) return SAMO_ERR_NULL;
+        if (misaligned(J.mask) || misaligned(J.seg_ptr) || misaligned(J.idx) ||
+            (reinterpret_cast<uintptr_t>(J.nnz) & 7u))
+            return SAMO_ERR_ALIGN;
+    }
+    for (int32_t j0 = 0; j0 < num_jobs;) {
+        IndexBatch batch;
+        std::memset(&batch, 0, sizeof(batch));
+        bool fill = false;
+        int64_t wgs = 0;
+        int k = 0;
+        for (; k < kIndexBatchJobs && j0 + k < num_jobs; ++k) {
+            const samo_index_job &J = h_jobs[j0 + k];
+            const int64_t w = index_job_workgroups(J.n);
+            if (k > 0 && wgs + w > kMaxN) break;                  // keep the grid within 2^31 - 1 workgroups
+            batch.wg_start[k] = (int)wgs;
+            batch.mask[k] = J.mask;
+            batch.n[k] = J.n;
+            batch.idx[k] = J.idx;
+            batch.cap[k] = J.idx_capacity;
+            batch.seg_ptr[k] = J.seg_ptr;
+            batch.nnz[k] = J.nnz;
+            fill |= J.idx_capacity > 0;
+            wgs += w;
+        }
+        batch.num = k;
+        batch.wg_start[k] = (int)wgs;
+        if (launch_index_batch(batch, fill, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
+        j0 += k;
+    }
+    return SAMO_OK;
+}
+
 samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_ptr, int64_t *d_nnz, void *stream)
 {
-    if (n < 0 || n > kMaxN) return SAMO_ERR_SIZE;
-    if ((!d_mask && n > 0) || !d_seg_ptr || !d_nnz) return SAMO_ERR_NULL;
-    if (misaligned(d_mask) || misaligned(d_seg_ptr) || (reinterpret_cast<uintptr_t>(d_nnz) & 7u)) return SAMO_ERR_ALIGN;
-    return hip_status(launch_count(d_mask, n, d_seg_ptr, d_nnz, as_stream(stream)));
+    const samo_index_job job = {d_mask, n, nullptr, 0, d_seg_ptr, d_nnz};
+    return samo_build_index_batched(&job, 1, stream);
 }
 
 samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx, int64_t idx_capacity,
                              int32_t *d_seg_ptr, int64_t *d_nnz, void *stream)
 {
-    if (n < 0 || n > kMaxN || idx_capacity < 0) return SAMO_ERR_SIZE;
-    if ((!d_mask && n > 0) || !d_seg_ptr || !d_nnz || (!d_idx && idx_capacity > 0)) return SAMO_ERR_NULL;
-    if (misaligned(d_mask) || misaligned(d_seg_ptr) || misaligned(d_idx) ||
-        (reinterpret_cast<uintptr_t>(d_nnz) & 7u))
-        return SAMO_ERR_ALIGN;
-    hipError_t e = launch_count(d_mask, n, d_seg_ptr, d_nnz, as_stream(stream));
-    if (e != hipSuccess) return SAMO_ERR_HIP;
-    return hip_status(launch_fill(d_mask, n, d_seg_ptr, d_idx, idx_capacity, as_stream(stream)));
+    const samo_index_job job = {d_mask, n, d_idx, idx_capacity, d_seg_ptr, d_nnz};
+    return samo_build_index_batched(&job, 1, stream);
 }
 
 samo_status samo_build_seg_ptr(const int32_t *d_idx, int64_t nnz, int64_t n, int32_t *d_seg_ptr, void *stream)

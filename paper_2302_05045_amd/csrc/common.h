@@ -20,6 +20,9 @@ namespace samo {
 #ifndef SAMO_GLDS
 #define SAMO_GLDS 0
 #endif
+#ifndef SAMO_ADAM_DWORD
+#define SAMO_ADAM_DWORD 0
+#endif
 #ifndef SAMO_NT
 #define SAMO_NT 9
 #endif
@@ -55,12 +58,25 @@ struct WgRec {
     int32_t local;
 };
 
+// Up to kIndexBatchJobs index-build jobs, passed to the kernels by value (kernel argument segment).
+constexpr int kIndexBatchJobs = 48;
+struct IndexBatch {
+    int num;
+    int wg_start[kIndexBatchJobs + 1];   // exclusive prefix of workgroups per job
+    const uint8_t *mask[kIndexBatchJobs];
+    int64_t n[kIndexBatchJobs];
+    int32_t *idx[kIndexBatchJobs];
+    int64_t cap[kIndexBatchJobs];
+    int32_t *seg_ptr[kIndexBatchJobs];
+    int64_t *nnz[kIndexBatchJobs];
+};
+static_assert(sizeof(IndexBatch) <= 3072, "the job table must fit the kernel argument segment");
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) -----------------------
-hipError_t launch_count(const uint8_t *mask, int64_t n, int32_t *seg_ptr, int64_t *nnz, hipStream_t s);
-hipError_t launch_fill(const uint8_t *mask, int64_t n, const int32_t *seg_ptr, int32_t *idx,
-                       int64_t cap, hipStream_t s);
+hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s);
+int64_t index_job_workgroups(int64_t n);
 hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr,
                                    hipStream_t s);
 hipError_t launch_validate(const int32_t *idx, int64_t nnz, int64_t n, const int32_t *seg_ptr,

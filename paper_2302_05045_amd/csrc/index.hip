@@ -58,57 +58,83 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
     return x;
 }
 
-__global__ void __launch_bounds__(kThreads)
-count_kernel(const uint8_t *__restrict__ mask, int64_t n, int64_t nseg, int32_t *__restrict__ seg_cnt)
+// Workgroup -> job lookup for the batched launches: the job table travels in the kernel
+// argument segment (scalar loads, no device table to allocate or copy), wg_start is the
+// exclusive prefix of the jobs' workgroup counts.
+__device__ __forceinline__ int find_job(const IndexBatch &batch, int wg)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t seg = (int64_t)blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
-    if (seg >= nseg) return;
-    const uint32_t f = lane_flags(mask, n, seg * kSeg + lane * 16);
-    const int total = wave_sum(__popc(f));
-    if (lane == 0) seg_cnt[seg] = total;
+    int lo = 0, hi = batch.num;                 // invariant: wg_start[lo] <= wg < wg_start[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (batch.wg_start[mid] <= wg) lo = mid; else hi = mid;
+    }
+    return lo;
 }
 
-// In-place exclusive scan of a[0 .. len) where the last entry counts as 0 on input, so that
-// a[len - 1] receives the grand total; the total is also stored to *nnz as int64.
+__global__ void __launch_bounds__(kThreads)
+count_kernel(const IndexBatch batch)
+{
+    const int job = find_job(batch, blockIdx.x);
+    const int64_t n = batch.n[job];
+    const int64_t nseg = (n + kSeg - 1) / kSeg;
+    const int lane = threadIdx.x & 63;
+    const int64_t seg = (int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6);
+    if (seg >= nseg) return;
+    const uint32_t f = lane_flags(batch.mask[job], n, seg * kSeg + lane * 16);
+    const int total = wave_sum(__popc(f));
+    if (lane == 0) batch.seg_ptr[job][seg] = total;
+}
+
+// In-place exclusive scan of a job's seg_ptr[0 .. nseg] where the last entry counts as 0 on
+// input, so that seg_ptr[nseg] receives the grand total; the total is also stored to *nnz.
+// One workgroup per job: every thread owns a contiguous run of ceil(len / 1024) entries (summed
+// and rewritten serially), and one block-wide scan of the 1024 run totals links the runs.
 __global__ void __launch_bounds__(kScanThreads)
-scan_kernel(int32_t *__restrict__ a, int64_t len, int64_t *__restrict__ nnz)
+scan_kernel(const IndexBatch batch)
 {
     __shared__ int wave_tot[kScanThreads / 64];
-    __shared__ int block_tot;
+    const int job = blockIdx.x;
+    int32_t *__restrict__ a = batch.seg_ptr[job];
+    const int64_t len = (batch.n[job] + kSeg - 1) / kSeg + 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int carry = 0;
-    for (int64_t b = 0; b < len; b += kScanThreads) {
-        const int64_t i = b + tid;
-        const int x = (i < len - 1) ? a[i] : 0;
-        const int incl = wave_inclusive_scan(x, lane);
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        if (wave == 0) {
-            const int t = (lane < kScanThreads / 64) ? wave_tot[lane] : 0;
-            const int ti = wave_inclusive_scan(t, lane);
-            if (lane < kScanThreads / 64) wave_tot[lane] = ti - t;   // exclusive prefix of the waves
-            if (lane == kScanThreads / 64 - 1) block_tot = ti;
-        }
-        __syncthreads();
-        if (i < len) a[i] = carry + wave_tot[wave] + incl - x;
-        carry += block_tot;
-        __syncthreads();
+    const int64_t per = (len + kScanThreads - 1) / kScanThreads;
+    const int64_t lo = (int64_t)tid * per;
+    const int64_t hi = (lo + per < len) ? lo + per : len;
+    int sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += (i < len - 1) ? a[i] : 0;
+    const int incl = wave_inclusive_scan(sum, lane);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        const int t = (lane < kScanThreads / 64) ? wave_tot[lane] : 0;
+        const int ti = wave_inclusive_scan(t, lane);
+        if (lane < kScanThreads / 64) wave_tot[lane] = ti - t;     // exclusive prefix of the waves
+        if (lane == kScanThreads / 64 - 1) *batch.nnz[job] = (int64_t)ti;   // grand total
     }
-    if (tid == 0) *nnz = (int64_t)carry;
+    __syncthreads();
+    int run = wave_tot[wave] + incl - sum;                          // exclusive prefix of this thread's run
+    for (int64_t i = lo; i < hi; ++i) {
+        const int x = (i < len - 1) ? a[i] : 0;
+        a[i] = run;
+        run += x;
+    }
 }
 
 __global__ void __launch_bounds__(kThreads)
-fill_kernel(const uint8_t *__restrict__ mask, int64_t n, int64_t nseg, const int32_t *__restrict__ seg_ptr,
-            int32_t *__restrict__ idx, int64_t cap)
+fill_kernel(const IndexBatch batch)
 {
+    const int job = find_job(batch, blockIdx.x);
+    const int64_t n = batch.n[job];
+    const int64_t cap = batch.cap[job];
+    const int64_t nseg = (n + kSeg - 1) / kSeg;
     const int lane = threadIdx.x & 63;
-    const int64_t seg = (int64_t)blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
-    if (seg >= nseg) return;
+    const int64_t seg = (int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6);
+    if (seg >= nseg || cap <= 0) return;
+    int32_t *__restrict__ idx = batch.idx[job];
     const int64_t first = seg * kSeg + lane * 16;
-    uint32_t f = lane_flags(mask, n, first);
+    uint32_t f = lane_flags(batch.mask[job], n, first);
     const int cnt = __popc(f);
-    int64_t out = (int64_t)seg_ptr[seg] + (wave_inclusive_scan(cnt, lane) - cnt);
+    int64_t out = (int64_t)batch.seg_ptr[job][seg] + (wave_inclusive_scan(cnt, lane) - cnt);
     while (f) {
         const int b = __ffs(f) - 1;
         f &= f - 1;
@@ -158,24 +184,17 @@ validate_kernel(const int32_t *__restrict__ idx, int64_t nnz, int64_t n, int64_t
 
 }  // namespace
 
-hipError_t launch_count(const uint8_t *mask, int64_t n, int32_t *seg_ptr, int64_t *nnz, hipStream_t s)
+hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s)
 {
-    const int64_t nseg = ceil_div(n, kSeg);
-    if (nseg > 0)
-        count_kernel<<<dim3((unsigned)ceil_div(nseg, kWavesPerWg)), dim3(kThreads), 0, s>>>(mask, n, nseg, seg_ptr);
-    scan_kernel<<<dim3(1), dim3(kScanThreads), 0, s>>>(seg_ptr, nseg + 1, nnz);
+    const int wgs = batch.wg_start[batch.num];
+    if (batch.num <= 0) return hipSuccess;
+    if (wgs > 0) count_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch);
+    scan_kernel<<<dim3((unsigned)batch.num), dim3(kScanThreads), 0, s>>>(batch);
+    if (fill && wgs > 0) fill_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch);
     return hipGetLastError();
 }
 
-hipError_t launch_fill(const uint8_t *mask, int64_t n, const int32_t *seg_ptr, int32_t *idx, int64_t cap,
-                       hipStream_t s)
-{
-    const int64_t nseg = ceil_div(n, kSeg);
-    if (nseg > 0 && cap > 0)
-        fill_kernel<<<dim3((unsigned)ceil_div(nseg, kWavesPerWg)), dim3(kThreads), 0, s>>>(mask, n, nseg, seg_ptr,
-                                                                                          idx, cap);
-    return hipGetLastError();
-}
+int64_t index_job_workgroups(int64_t n) { return ceil_div(ceil_div(n, kSeg), kWavesPerWg); }
 
 hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr, hipStream_t s)
 {

@@ -333,6 +333,26 @@ adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
     float *__restrict__ M = L.m;
     float *__restrict__ V = L.v;
     const float *__restrict__ GC = L.gc;
+#if SAMO_ADAM_DWORD
+    {
+        constexpr int U = kChunk / kFlatThreads;
+        float pp[U], mm[U], vv[U], gg[U];
+        const int64_t i0 = chunk * kChunk + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * kFlatThreads;
+            if (i < nnz) { pp[u] = P[i]; mm[u] = M[i]; vv[u] = V[i]; gg[u] = GC[i]; }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * kFlatThreads;
+            if (i < nnz) {
+                adam_update(pp[u], mm[u], vv[u], gg[u], k);
+                P[i] = pp[u]; M[i] = mm[u]; V[i] = vv[u];
+            }
+        }
+    }
+#else
 #pragma unroll
     for (int it = 0; it < kChunk / (4 * kFlatThreads); ++it) {
         const int64_t i = chunk * kChunk + ((int64_t)it * kFlatThreads + threadIdx.x) * 4;
@@ -356,6 +376,7 @@ adam_kernel(const samo_layer one, const samo_layer *__restrict__ layers, const W
             }
         }
     }
+#endif
 }
 
 // ------------------------------------------------------------------ diagnostic copy

@@ -71,6 +71,14 @@ def test_size_and_null_rejection():
     assert L.samo_build_index(None, 8, FAKE, 8, FAKE, FAKE, None) == samo.SAMO_ERR_NULL
     assert L.samo_build_index(FAKE, 8, None, 8, FAKE, FAKE, None) == samo.SAMO_ERR_NULL
     assert L.samo_build_index(FAKE, 8, FAKE, -1, FAKE, FAKE, None) == samo.SAMO_ERR_SIZE
+    jobs = (samo.IndexJob * 2)()
+    jobs[0].mask, jobs[0].n, jobs[0].seg_ptr, jobs[0].nnz = FAKE, 8, FAKE, FAKE
+    jobs[1].mask, jobs[1].n, jobs[1].seg_ptr, jobs[1].nnz = FAKE, 2**31, FAKE, FAKE
+    assert L.samo_build_index_batched(jobs, 2, None) == samo.SAMO_ERR_SIZE     # second job bad: nothing launched
+    jobs[1].n, jobs[1].idx_capacity = 8, 4
+    assert L.samo_build_index_batched(jobs, 2, None) == samo.SAMO_ERR_NULL     # capacity without idx
+    assert L.samo_build_index_batched(None, 1, None) == samo.SAMO_ERR_NULL
+    assert L.samo_build_index_batched(None, 0, None) == samo.SAMO_OK
     assert L.samo_count_nonzero(FAKE, 8, None, FAKE, None) == samo.SAMO_ERR_NULL
     assert L.samo_count_nonzero(FAKE + 1, 8, FAKE, FAKE, None) == samo.SAMO_ERR_ALIGN
     assert L.samo_gather_grads(FAKE, 8, None, 4, 1.0, FAKE, None) == samo.SAMO_ERR_NULL

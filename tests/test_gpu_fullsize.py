@@ -21,29 +21,34 @@ class Model:
 
     def __init__(self, specs, with_gc=False, workers=12):
         self.specs = specs
-        self.host = []      # (spec, mask, idx, p, m, v, g16)
-        self.layers = []
+        self.host = []      # [spec, mask, idx, p, m, v, g16]
+        masks = []
 
         def consume(i, data):
             spec = data.spec
             ref_idx = oracle.build_index(data.mask)
             p_host = np.ascontiguousarray(data.w32[ref_idx])
-            if spec.mask_kind == "dense":
-                idx = seg_ptr = None
-            else:
-                ix = samo.samo_build_index(torch.from_numpy(data.mask).to(DEV))
-                assert ix.nnz == ref_idx.shape[0], spec.name
-                assert np.array_equal(ix.idx.cpu().numpy(), ref_idx), spec.name      # bit-exact index
-                idx, seg_ptr = ix.idx, ix.seg_ptr
-            p = torch.from_numpy(p_host).to(DEV)
-            g = torch.from_numpy(data.g16.view(np.int16)).to(DEV).view(torch.float16)
-            w = torch.full((spec.n,), float("nan"), dtype=torch.float16, device=DEV)
-            gc = torch.full_like(p, float("nan")) if with_gc else None
-            self.layers.append(samo.Layer(spec.n, idx, seg_ptr, p, torch.zeros_like(p), torch.zeros_like(p), w, g, gc))
-            self.host.append([spec, data.mask, ref_idx, p_host.copy(), np.zeros_like(p_host), np.zeros_like(p_host),
-                              data.g16])
+            masks.append(None if spec.mask_kind == "dense" else torch.from_numpy(data.mask).to(DEV))
+            self.host.append([spec, data.mask, ref_idx, p_host, np.zeros_like(p_host), np.zeros_like(p_host), data.g16])
 
         si.generate(specs, consume, workers=workers)
+        # same set-up as bench.py: batched index build, one layer-major allocation, one plan
+        built = iter(samo.samo_build_index_many([m for m in masks if m is not None]))
+        self.layers = samo.alloc_model([(h[0].n, h[2].shape[0], m is None) for h, m in zip(self.host, masks)], DEV,
+                                       with_gc=with_gc)
+        for L, h, m in zip(self.layers, self.host, masks):
+            if m is not None:
+                ix = next(built)
+                assert ix.nnz == h[2].shape[0], h[0].name
+                assert np.array_equal(ix.idx.cpu().numpy(), h[2]), h[0].name          # bit-exact index
+                L.idx.copy_(ix.idx)
+                L.seg_ptr.copy_(ix.seg_ptr)
+            L.p.copy_(torch.from_numpy(h[3]))
+            L.g.copy_(torch.from_numpy(h[6].view(np.int16)).view(torch.float16))
+            L.w.fill_(float("nan"))
+            if with_gc:
+                L.gc.fill_(float("nan"))
+        del masks
         self.plan = samo.Plan(self.layers)
 
     def oracle_step(self, t):

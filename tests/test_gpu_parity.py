@@ -46,6 +46,32 @@ def test_build_index_config1_and_determinism():
     assert torch.equal(a.idx, b.idx) and torch.equal(a.seg_ptr, b.seg_ptr)
 
 
+@pytest.mark.parametrize("n,keep", [(3_000_001, 0.1), (1024 * 1024 * 5 + 1, 0.5), (2_100_000, 0.999)])
+def test_build_index_many_segments(n, keep):
+    # more segments than scan threads: every thread of the scan owns a run of several entries
+    mask = si.bernoulli_mask(n, keep, n % 1000)
+    ref = oracle.build_index(mask)
+    ix = samo.samo_build_index(dev_u8(mask))
+    assert ix.nnz == ref.shape[0]
+    assert np.array_equal(ix.idx.cpu().numpy(), ref)
+    assert np.array_equal(ix.seg_ptr.cpu().numpy(), ref_seg_ptr(ref, n))
+
+
+def test_build_index_batched_many_jobs():
+    # more jobs than one launch group holds (48), with empty, tiny, ragged and multi-segment layers
+    rng = np.random.default_rng(7)
+    sizes = [0, 1, 15, 16, 1023, 1024, 1025, 4097, 70001, 300007] + [int(x) for x in rng.integers(1, 20000, 95)]
+    masks = [si.bernoulli_mask(n, float(rng.uniform(0.0, 1.0)), 900 + i) for i, n in enumerate(sizes)]
+    got = samo.samo_build_index_many([dev_u8(m) for m in masks])
+    assert len(got) == len(masks) == 105
+    for ix, mask in zip(got, masks):
+        ref = oracle.build_index(mask)
+        assert ix.nnz == ref.shape[0] and ix.n == mask.shape[0]
+        assert np.array_equal(ix.idx.cpu().numpy(), ref)
+        assert np.array_equal(ix.seg_ptr.cpu().numpy(), ref_seg_ptr(ref, mask.shape[0]))
+    assert samo.samo_build_index_many([]) == []
+
+
 def test_build_index_empty_layer():
     ix = samo.samo_build_index(torch.empty(0, dtype=torch.uint8, device=DEV))
     assert ix.nnz == 0 and ix.seg_ptr.cpu().tolist() == [0]
