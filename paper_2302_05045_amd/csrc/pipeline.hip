@@ -184,42 +184,45 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int tile, int64
     const int c1 = L.seg_ptr[s1];
     __syncthreads();
 
-    const int32_t *__restrict__ IDX = L.idx;
-    float *__restrict__ P = L.p;
-    float *__restrict__ M = L.m;
-    float *__restrict__ V = L.v;
+    // the tile's slice of the compressed arrays; at most kTile elements, so slice-relative
+    // offsets fit an int even when c0 is close to 2^31
+    const int cnt = c1 - c0;
+    const int32_t *__restrict__ IDX = L.idx + c0;
+    float *__restrict__ P = L.p + c0;
+    float *__restrict__ M = L.m + c0;
+    float *__restrict__ V = L.v + c0;
     const uint16_t *__restrict__ G = L.g;
     const int ibase = (int)base;             // a layer's flat size fits int32
 
     constexpr int U = SAMO_U;
-    for (int i0 = c0 + tid; i0 < c1; i0 += U * kTileThreads) {
+    for (int r0 = tid; r0 < cnt; r0 += U * kTileThreads) {
         int j[U];
         float pp[U], mm[U], vv[U];
         uint16_t gb[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * kTileThreads;
+            const int r = r0 + u * kTileThreads;
             j[u] = ibase; pp[u] = 0.f; mm[u] = 0.f; vv[u] = 0.f; gb[u] = 0;
-            if (i < c1) {
-                j[u] = load_stream(IDX + i);
-                pp[u] = load_stream(P + i);
-                if (MODE == kModeFused) { mm[u] = load_stream(M + i); vv[u] = load_stream(V + i); }
+            if (r < cnt) {
+                j[u] = load_stream(IDX + r);
+                pp[u] = load_stream(P + r);
+                if (MODE == kModeFused) { mm[u] = load_stream(M + r); vv[u] = load_stream(V + r); }
             }
         }
         if (MODE == kModeFused) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (i0 + u * kTileThreads < c1) gb[u] = SAMO_GLDS ? lds_g[j[u] - ibase] : G[j[u]];
+                if (r0 + u * kTileThreads < cnt) gb[u] = SAMO_GLDS ? lds_g[j[u] - ibase] : G[j[u]];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * kTileThreads;
-            if (i < c1) {
+            const int r = r0 + u * kTileThreads;
+            if (r < cnt) {
                 if (MODE == kModeFused) {
                     adam_update(pp[u], mm[u], vv[u], half_bits_to_float(gb[u]) * inv_scale, k);
-                    store_f32(P + i, pp[u]);
-                    store_f32(M + i, mm[u]);
-                    store_f32(V + i, vv[u]);
+                    store_f32(P + r, pp[u]);
+                    store_f32(M + r, mm[u]);
+                    store_f32(V + r, vv[u]);
                 }
                 lds_w[j[u] - ibase] = float_to_half_bits(pp[u]);
             }

@@ -129,3 +129,78 @@ def test_gpt6p7b_row_clustered_slice_with_dense_embedding():
     spec, mask, idx = model.host[0][0], model.host[0][1], model.host[0][2]
     per_row = mask.reshape(spec.rows, spec.cols).sum(axis=1)
     assert per_row.max() > 5 * np.median(per_row)
+
+
+def test_largest_layer_int32_index_limit():
+    """One layer of N = 2^31 - 1 elements, the largest flat size a 32-bit index allows (Section III-B):
+    index, expansion and one fused step, bit-exact / within tolerance on every element."""
+    n = 2**31 - 1
+    chunk = 1 << 26
+    mask = np.empty(n, np.uint8)
+    g16 = np.empty(n, np.uint16)
+    for c, lo in enumerate(range(0, n, chunk)):
+        hi = min(n, lo + chunk)
+        mask[lo:hi] = si.bernoulli_mask(hi - lo, 0.04, 7000 + c)
+        g16[lo:hi] = si.grads_fp16(hi - lo, 7000 + c)
+    mask[0] = mask[-1] = 1                                        # first and last position kept
+    ref_idx = oracle.build_index(mask)
+    assert ref_idx[0] == 0 and ref_idx[-1] == n - 1
+    nnz = ref_idx.shape[0]
+
+    d_mask = torch.from_numpy(mask).to(DEV)
+    ix = samo.samo_build_index(d_mask)
+    del d_mask
+    assert ix.nnz == nnz
+    assert np.array_equal(ix.idx.cpu().numpy(), ref_idx)
+    assert samo.samo_validate_index(ix.idx, n, ix.seg_ptr)
+
+    p_host = si.weights(nnz, 7100)
+    p = torch.from_numpy(p_host).to(DEV)
+    m, v = torch.zeros_like(p), torch.zeros_like(p)
+    w = torch.full((n,), float("nan"), dtype=torch.float16, device=DEV)
+    samo.samo_decompress(p, ix.idx, ix.seg_ptr, w)
+    ref_w = oracle.decompress(p_host, ref_idx, n)
+    assert np.array_equal(host_bits(w), ref_w)
+
+    g = torch.from_numpy(g16.view(np.int16)).to(DEV).view(torch.float16)
+    w.fill_(float("nan"))
+    samo.samo_fused_step(g, w, ix.idx, ix.seg_ptr, p, m, v, INV, samo.adam_cfg(1, **si.ADAM))
+    ref_m, ref_v = np.zeros_like(p_host), np.zeros_like(p_host)
+    oracle.step(g16, n, ref_idx, p_host, ref_m, ref_v, INV, OCFG, 1, ref_w)
+    got_p = p.cpu().numpy()
+    assert_close(got_p, p_host, "p")
+    assert_close(m.cpu().numpy(), ref_m, "m")
+    assert_close(v.cpu().numpy(), ref_v, "v")
+    assert np.array_equal(host_bits(w), oracle.decompress(got_p, ref_idx, n, ref_w))
+
+
+def test_fused_step_under_hip_graph_replay():
+    """The batched entry only enqueues kernels on the caller's stream, so it can be captured into a
+    HIP graph; every replay must give what the eager launch gives."""
+    specs = si.config("gpt350m", 0.9, layers=2)
+    eager, graphed = Model(specs), Model(specs)
+    cfg = samo.adam_cfg(1, **si.ADAM)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graphed.plan.samo_fused_step_batched(INV, cfg)          # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        graphed.plan.samo_fused_step_batched(INV, cfg)
+    eager.plan.samo_fused_step_batched(INV, cfg)                # eager has done 1 step, graphed 1 step
+    for rep in range(3):
+        eager.poison_w()
+        graphed.poison_w()
+        torch.cuda.synchronize()
+        eager.plan.samo_fused_step_batched(INV, cfg)
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager.layers, graphed.layers):
+            assert torch.equal(a.p, b.p) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v), rep
+            assert torch.equal(a.w.view(torch.int16), b.w.view(torch.int16)), rep
+    # and the eager side still matches the oracle after its 4 steps with a fixed step counter
+    for _ in range(4):
+        eager.oracle_step(1)
+    eager.check(1)
