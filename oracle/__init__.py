@@ -57,6 +57,20 @@ def _load():
         lib.samo_oracle_gather.argtypes = [vp, vp, i64, f32, vp]
         lib.samo_oracle_compress_f16.restype = None
         lib.samo_oracle_compress_f16.argtypes = [vp, vp, i64, vp]
+        lib.samo_oracle_f64_to_f16.restype = ctypes.c_uint16
+        lib.samo_oracle_f64_to_f16.argtypes = [ctypes.c_double]
+        lib.samo_oracle_accumulate_f16.restype = None
+        lib.samo_oracle_accumulate_f16.argtypes = [vp, vp, i64, vp]
+        lib.samo_oracle_upcast.restype = None
+        lib.samo_oracle_upcast.argtypes = [vp, i64, f32, vp]
+        lib.samo_oracle_sum_squares.restype = ctypes.c_double
+        lib.samo_oracle_sum_squares.argtypes = [vp, i64]
+        lib.samo_oracle_has_nonfinite.restype = i32
+        lib.samo_oracle_has_nonfinite.argtypes = [vp, i64]
+        lib.samo_oracle_scale.restype = None
+        lib.samo_oracle_scale.argtypes = [vp, i64, f32]
+        lib.samo_oracle_sgd.restype = None
+        lib.samo_oracle_sgd.argtypes = [vp, vp, vp, i64, f32, f32, f32]
         lib.samo_oracle_adam.restype = None
         lib.samo_oracle_adam.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32]
         lib.samo_oracle_step.restype = None
@@ -154,6 +168,62 @@ def compress_f16(dense: np.ndarray, idx: np.ndarray) -> np.ndarray:
     out = np.empty(idx.shape[0], np.uint16)
     _load().samo_oracle_compress_f16(_ptr(dense), _ptr(idx), idx.shape[0], _ptr(out))
     return out
+
+
+def f64_to_f16_bits_scalar(x: float) -> int:
+    return int(_load().samo_oracle_f64_to_f16(float(x)))
+
+
+def accumulate_f16(g: np.ndarray, idx: np.ndarray, gc16: np.ndarray) -> None:
+    """gc16[i] <- fp16(gc16[i] + g[idx[i]]), correctly rounded: one more micro-batch into the
+    stored compressed fp16 gradient (Section III-A; micro-batches, Section II-E)."""
+    g = _arr(g, np.uint16)
+    idx = _arr(idx, np.int32)
+    gc16 = _arr(gc16, np.uint16, True)
+    if gc16.shape[0] != idx.shape[0]:
+        raise ValueError("gc16 and idx differ in length")
+    _check_index(idx, g.shape[0])
+    _load().samo_oracle_accumulate_f16(_ptr(g), _ptr(idx), idx.shape[0], _ptr(gc16))
+
+
+def upcast(gc16: np.ndarray, inv_loss_scale: float) -> np.ndarray:
+    """Section III-C optimizer step, first operation: compressed fp16 -> fp32, times 1/loss scale."""
+    gc16 = _arr(gc16, np.uint16)
+    gc = np.empty(gc16.shape[0], np.float32)
+    _load().samo_oracle_upcast(_ptr(gc16), gc16.shape[0], np.float32(inv_loss_scale), _ptr(gc))
+    return gc
+
+
+def sum_squares(gc: np.ndarray) -> float:
+    gc = _arr(gc, np.float32)
+    return float(_load().samo_oracle_sum_squares(_ptr(gc), gc.shape[0]))
+
+
+def has_nonfinite(gc: np.ndarray) -> bool:
+    gc = _arr(gc, np.float32)
+    return bool(_load().samo_oracle_has_nonfinite(_ptr(gc), gc.shape[0]))
+
+
+def clip_coefficient(total_sum_squares: float, max_norm: float) -> np.float32:
+    """Gradient clipping by global norm, as torch.nn.utils.clip_grad_norm_ defines it:
+    coef = min(1, max_norm / (norm + 1e-6)), rounded to fp32."""
+    norm = float(np.sqrt(total_sum_squares))
+    return np.float32(min(1.0, max_norm / (norm + 1e-6)))
+
+
+def scale(gc: np.ndarray, coef: float) -> None:
+    gc = _arr(gc, np.float32, True)
+    _load().samo_oracle_scale(_ptr(gc), gc.shape[0], np.float32(coef))
+
+
+def sgd(p: np.ndarray, buf: np.ndarray, gc: np.ndarray, lr: float, momentum: float, weight_decay: float = 0.0) -> None:
+    """In-place SGD with momentum on the compressed fp32 tensors (one state per parameter)."""
+    p = _arr(p, np.float32, True)
+    buf = _arr(buf, np.float32, True)
+    gc = _arr(gc, np.float32)
+    if not (buf.shape[0] == gc.shape[0] == p.shape[0]):
+        raise ValueError("compressed tensors differ in length")
+    _load().samo_oracle_sgd(_ptr(p), _ptr(buf), _ptr(gc), p.shape[0], lr, momentum, weight_decay)
 
 
 def adam(p: np.ndarray, m: np.ndarray, v: np.ndarray, gc: np.ndarray, cfg: AdamCfg, step: int) -> None:

@@ -24,7 +24,9 @@
  * numpy's casts over every fp32 / fp16 bit pattern; expand = compress^-1
  * (Section III-C); dense Adam on the masked tensor via torch.optim.Adam; the
  * closed form of the first Adam step; Eq. (1)-(5) values printed in Section
- * III-D.  No function here is "parity unpinned".
+ * III-D; for the widened path (tests/test_oracle_next.py) numpy's half addition
+ * and direct double->half cast, torch's clip_grad_norm_ and torch.optim.SGD.
+ * No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -94,6 +96,38 @@ float samo_oracle_f16_to_f32(uint16_t h)
     return f32_of_bits(sign | ((uint32_t)(e + 127) << 23) | (man << 13));
 }
 
+/* IEEE 754 binary64 -> binary16, round to nearest even, directly (one rounding). */
+uint16_t samo_oracle_f64_to_f16(double x)
+{
+    uint64_t u;
+    memcpy(&u, &x, 8);
+    uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+    int bexp = (int)((u >> 52) & 0x7ffu);
+    uint64_t man = u & 0xfffffffffffffull;
+
+    if (bexp == 0x7ff)
+        return (uint16_t)(sign | (man ? 0x7e00u : 0x7c00u));
+    int e = bexp - 1023;
+    if (e > 15)
+        return (uint16_t)(sign | 0x7c00u);
+    if (e >= -14) {
+        uint32_t h = ((uint32_t)(e + 15) << 10) | (uint32_t)(man >> 42);
+        uint64_t rem = man & ((1ull << 42) - 1), half = 1ull << 41;
+        if (rem > half || (rem == half && (h & 1u)))
+            h += 1;
+        return (uint16_t)(sign | h);
+    }
+    if (e < -25 || bexp == 0)
+        return sign;
+    uint64_t full = man | (1ull << 52);          /* value = full * 2^(e-52); unit 2^-24 */
+    int shift = 28 - e;                          /* 43 (e = -15) ... 53 (e = -25) */
+    uint32_t h = (uint32_t)(full >> shift);
+    uint64_t rem = full & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    if (rem > half || (rem == half && (h & 1u)))
+        h += 1;
+    return (uint16_t)(sign | h);
+}
+
 void samo_oracle_f32_to_f16_array(const float *x, uint16_t *h, int64_t n)
 {
     for (int64_t i = 0; i < n; ++i) h[i] = samo_oracle_f32_to_f16(x[i]);
@@ -150,6 +184,74 @@ void samo_oracle_compress_f16(const uint16_t *dense, const int32_t *idx, int64_t
                               uint16_t *out)
 {
     for (int64_t i = 0; i < nnz; ++i) out[i] = dense[idx[i]];
+}
+
+/* Accumulation of one more micro-batch into the stored compressed fp16 gradient (Section III-A
+ * keeps grad theta16 compressed; Section II-E: the runtime splits a batch into micro-batches).
+ * The paper does not say how micro-batch gradients are combined; the reading taken is an fp16
+ * sum, correctly rounded once: the exact sum of two halves fits a double. */
+void samo_oracle_accumulate_f16(const uint16_t *g, const int32_t *idx, int64_t nnz, uint16_t *gc16)
+{
+    for (int64_t i = 0; i < nnz; ++i) {
+        const double a = (double)samo_oracle_f16_to_f32(gc16[i]);
+        const double b = (double)samo_oracle_f16_to_f32(g[idx[i]]);
+        gc16[i] = samo_oracle_f64_to_f16(a + b);
+    }
+}
+
+/* Optimizer step, first operation (Section III-C): up-cast of the compressed fp16 gradient to
+ * fp32 "directly on the compressed tensors", with the loss-scale division: one exact
+ * conversion, one fp32 multiply. */
+void samo_oracle_upcast(const uint16_t *gc16, int64_t nnz, float inv_loss_scale, float *gc)
+{
+    for (int64_t i = 0; i < nnz; ++i) {
+        volatile float t = samo_oracle_f16_to_f32(gc16[i]) * inv_loss_scale;
+        gc[i] = t;
+    }
+}
+
+/* Sum of squares of a compressed fp32 gradient, in double, in index order; and whether any value
+ * is NaN or infinite.  Gradient clipping by global norm (the paper trains with the original
+ * authors' hyper-parameters including gradient clipping, Section V) needs the first, mixed
+ * precision's overflow check (Micikevicius et al., cited in Section III) the second. */
+double samo_oracle_sum_squares(const float *gc, int64_t nnz)
+{
+    double s = 0.0;
+    for (int64_t i = 0; i < nnz; ++i) s += (double)gc[i] * (double)gc[i];
+    return s;
+}
+
+int32_t samo_oracle_has_nonfinite(const float *gc, int64_t nnz)
+{
+    for (int64_t i = 0; i < nnz; ++i)
+        if (isnan(gc[i]) || isinf(gc[i])) return 1;
+    return 0;
+}
+
+/* gc[i] *= coef: one fp32 multiply per element (clipping coefficient applied to the gradient). */
+void samo_oracle_scale(float *gc, int64_t nnz, float coef)
+{
+    for (int64_t i = 0; i < nnz; ++i) {
+        volatile float t = gc[i] * coef;
+        gc[i] = t;
+    }
+}
+
+/* SGD with momentum on the compressed tensors (one fp32 state per parameter; the paper's CNN
+ * runs use SGD, Section V, and Section III-D notes SAMO extends to other optimizers):
+ * buf = mu * buf + g (+ weight_decay * p in g); p = p - lr * buf.  buf starts at zero.
+ * Evaluated in fp64 from the fp32 state, one rounding per stored value. */
+void samo_oracle_sgd(float *p, float *buf, const float *gc, int64_t nnz,
+                     float lr, float momentum, float weight_decay)
+{
+    for (int64_t i = 0; i < nnz; ++i) {
+        const double theta = p[i];
+        double g = gc[i];
+        if (weight_decay != 0.0f) g += (double)weight_decay * theta;
+        const double b = (double)momentum * (double)buf[i] + g;
+        p[i] = (float)(theta - (double)lr * b);
+        buf[i] = (float)b;
+    }
 }
 
 /* Adam (Kingma & Ba, Algorithm 1; the optimizer assumed in Section III-D, with
