@@ -107,7 +107,7 @@ def main():
     # the model's buffers: one allocation, layer-major (a layer's idx/p/m/v/g/w adjacent)
     it = iter(indices)
     per_layer_index = [next(it) if st[3] is not None else None for st in staged]
-    layers = samo.alloc_model([(st[0].n, st[1].shape[0], st[3] is None) for st in staged], dev, with_gc=True)
+    layers = samo.alloc_model([(st[0].n, st[1].shape[0], st[3] is None) for st in staged], dev, with_gc=True, with_gc16=True)
     for k, L in enumerate(layers):
         spec, p_host, g16, d_mask = staged[k]
         staged[k] = None
@@ -176,6 +176,18 @@ def main():
         entry("samo_gather_batched", time_entry(lambda: plan.samo_gather_batched(inv)), move_bytes)
         entry("samo_adam_batched", time_entry(lambda: plan.samo_adam_batched(cfg(t + 1))), 28 * nnz_total)
         entry("samo_decompress_batched", time_entry(plan.samo_decompress_batched), move_bytes)
+        # the data-parallel-shaped split (compressed fp16 gradient, then Adam + expand), with the
+        # gradient statistics reduced on the way, and the other widened entries
+        stats = samo.GradStats(plan)
+        entry("samo_gather_fp16_batched(+stats)", time_entry(lambda: plan.samo_gather_fp16_batched(False, inv, stats)),
+              sum(6 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 4 * L.n for L in layers))
+        entry("samo_adam_expand_batched(clip+skip guard)",
+              time_entry(lambda: plan.samo_adam_expand_batched(inv, cfg(t + 1), stats.guard(1e9, True))),
+              sum(30 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 28 * L.n for L in layers))
+        entry("samo_grad_stats_batched(dense g)", time_entry(lambda: plan.samo_grad_stats_batched(0, inv, stats)),
+              sum(4 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 2 * L.n for L in layers))
+        entry("samo_fused_sgd_step_batched", time_entry(lambda: plan.samo_fused_sgd_step_batched(inv, samo.sgd_cfg(1e-4))),
+              sum(20 * L.p.numel() + 4 * L.n if L.seg_ptr is not None else 20 * L.n for L in layers))
         if n_indexed:
             entry("samo_build_index_batched", index_ms, index_bytes)
         nb = min(4 << 30, max(1 << 20, (fused_bytes // 2) & ~15))

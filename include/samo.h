@@ -11,6 +11,9 @@
  *   p, m, v  float[nnz]   fp32 master parameters and the two Adam states, values
  *                         at the unpruned positions only (theta32, os)
  *   gc       float[nnz]   compressed, up-cast, unscaled gradient (grad theta32)
+ *   gc16     fp16[nnz]    compressed half-precision gradient (grad theta16), still
+ *                         multiplied by the loss scale; the data-parallel
+ *                         all-reduce message of Section IV-A
  *   w        fp16[N]      dense half-precision parameters (theta16) with +0
  *                         stored explicitly at every pruned position
  *   g        fp16[N]      dense half-precision gradient as backward produced it
@@ -52,7 +55,7 @@
 extern "C" {
 #endif
 
-#define SAMO_ABI_VERSION 1
+#define SAMO_ABI_VERSION 2
 #define SAMO_SEG_ELEMS 1024 /* dense elements per seg_ptr entry */
 
 typedef int32_t samo_status;
@@ -82,6 +85,34 @@ typedef struct {
     int32_t decoupled_wd;
     int32_t step;
 } samo_adam_cfg;
+
+/* SGD with momentum (one fp32 state per parameter, held in `m`; the paper's CNN runs use SGD,
+ * Section V, and Section III-D notes that SAMO extends to other optimizers):
+ * buf = momentum * buf + g (+ weight_decay * p); p = p - lr * buf; buf starts at zero. */
+typedef struct {
+    float lr, momentum, weight_decay;
+} samo_sgd_cfg;
+
+/* Gradient statistics of a whole model, DEVICE resident: the sum of squares of the unscaled
+ * compressed gradient (for clipping by global norm; the paper trains with gradient clipping,
+ * Section V) and whether any value is NaN or infinite (the overflow check of mixed-precision
+ * training).  Written by the entry points that take a d_stats argument. */
+typedef struct {
+    double sum_squares;
+    int32_t nonfinite;
+    int32_t reserved;
+} samo_grad_stats;
+
+/* Optional guard of a batched optimizer step, evaluated on the device (no host round trip):
+ * every gradient is multiplied by min(1, max_grad_norm / (sqrt(sum_squares) + 1e-6)) when
+ * max_grad_norm > 0, and when skip_on_nonfinite != 0 and the statistics report a non-finite
+ * value the step does nothing at all (p, m, v and w keep their contents).  d_stats must have
+ * been written earlier on the same stream.  A NULL guard means no clipping and no skipping. */
+typedef struct {
+    const samo_grad_stats *d_stats;
+    float max_grad_norm;
+    int32_t skip_on_nonfinite;
+} samo_step_guard;
 
 /* ---------------------------------------------------------------- index (ind_i, Section III / III-B)
  * The pruning algorithm's output is taken as a byte mask over the flattened
@@ -133,10 +164,20 @@ samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_
 samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_idx,
                               int64_t nnz, float inv_loss_scale, float *d_gc, void *stream);
 
+/* The stored compressed half-precision gradient (Section III-A) — what a data-parallel
+ * all-reduce would send (Section IV-A).  accumulate == 0: gc16[i] = g[idx[i]] (pure movement);
+ * accumulate != 0: gc16[i] = fp16(gc16[i] + g[idx[i]]), one correctly rounded half addition
+ * (a further micro-batch, Section II-E).  The loss scale stays in the values. */
+samo_status samo_gather_grads_fp16(const uint16_t *d_g, int64_t n, const int32_t *d_idx,
+                                   int64_t nnz, uint16_t *d_gc16, int32_t accumulate, void *stream);
+
 /* ---------------------------------------------------------------- optimizer on compressed state (Section III-C, III-D)
  * One Adam step over p, m, v [0..nnz) with gradient gc, all fp32, in place. */
 samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,
                            const samo_adam_cfg *h_cfg, void *stream);
+/* One SGD-momentum step over p, buf [0..nnz) with gradient gc. */
+samo_status samo_sgd_step(float *d_p, float *d_buf, const float *d_gc, int64_t nnz,
+                          const samo_sgd_cfg *h_cfg, void *stream);
 
 /* ---------------------------------------------------------------- fused optimizer phase (Section III-C: compress + up-cast,
  * optimizer, 16-bit copy, expansion — in one pass)
@@ -147,6 +188,18 @@ samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const
                             const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m,
                             float *d_v, float inv_loss_scale, const samo_adam_cfg *h_cfg,
                             void *stream);
+
+/* The optimizer phase as it runs AFTER a gradient all-reduce (Section IV-A, Section III-C):
+ * up-cast of the compressed fp16 gradient with the loss-scale division, Adam on the compressed
+ * state, 16-bit copy and expansion.  Equals samo_fused_step when gc16 holds g at idx. */
+samo_status samo_adam_expand_step(const uint16_t *d_gc16, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                                  const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m,
+                                  float *d_v, float inv_loss_scale, const samo_adam_cfg *h_cfg,
+                                  void *stream);
+/* samo_fused_step with SGD momentum instead of Adam (state in d_buf). */
+samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                                const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_buf,
+                                float inv_loss_scale, const samo_sgd_cfg *h_cfg, void *stream);
 
 /* ---------------------------------------------------------------- whole-model (batched) forms
  * One launch covers every layer, so small layers do not pay a launch and a
@@ -165,6 +218,7 @@ typedef struct {
     uint16_t *w;
     const uint16_t *g;
     float *gc;
+    uint16_t *gc16;
 } samo_layer;
 
 typedef struct samo_plan samo_plan;
@@ -174,11 +228,37 @@ samo_status samo_plan_destroy(samo_plan *plan); /* NULL is accepted */
 /* Sum over layers, as given at creation. */
 samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *nnz_total);
 
+/* Gradient statistics need one (sum, flag) partial per workgroup: *bytes is the size of the
+ * device workspace the entry points with a d_stats argument require for this plan. */
+samo_status samo_plan_stats_workspace_bytes(const samo_plan *plan, size_t *bytes);
+
 samo_status samo_decompress_batched(const samo_plan *plan, void *stream);
-samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, void *stream);
-samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, void *stream);
+/* Gather entries: when d_stats != NULL the statistics of what was gathered (for fp16: of the
+ * values after accumulation), multiplied by inv_loss_scale, are reduced on the way — the pass
+ * over the gradient is not repeated.  d_workspace/workspace_bytes as reported above; both are
+ * ignored when d_stats == NULL.  The reduction order is fixed: results are deterministic. */
+samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, samo_grad_stats *d_stats,
+                                void *d_workspace, size_t workspace_bytes, void *stream);
+samo_status samo_gather_fp16_batched(const samo_plan *plan, int32_t accumulate, float inv_loss_scale,
+                                     samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
+                                     void *stream);
+/* Statistics only, for callers that run the fully fused step: source selects what is read —
+ * 0: the dense fp16 gradient g at idx, 1: gc16, 2: gc (fp32, already unscaled: pass 1.0f). */
+samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float inv_loss_scale,
+                                    samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
+                                    void *stream);
+/* Optimizer entries; h_guard may be NULL. */
+samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg,
+                              const samo_step_guard *h_guard, void *stream);
 samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale,
-                                    const samo_adam_cfg *h_cfg, void *stream);
+                                    const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,
+                                    void *stream);
+samo_status samo_adam_expand_batched(const samo_plan *plan, float inv_loss_scale,
+                                     const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,
+                                     void *stream);
+samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_scale,
+                                        const samo_sgd_cfg *h_cfg, const samo_step_guard *h_guard,
+                                        void *stream);
 
 /* ---------------------------------------------------------------- byte accounting (Section III-D, Eq. 1-5)  [host only]
  * paper_default = 20 * n_total; paper_samo = 24 * nnz_total + 2 * n_total;

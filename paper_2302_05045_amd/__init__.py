@@ -44,7 +44,18 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64),
                 ("idx", ctypes.c_void_p), ("seg_ptr", ctypes.c_void_p),
                 ("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
-                ("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("gc", ctypes.c_void_p)]
+                ("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("gc", ctypes.c_void_p),
+                ("gc16", ctypes.c_void_p)]
+
+
+class SgdCfg(ctypes.Structure):
+    """samo_sgd_cfg"""
+    _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float)]
+
+
+class StepGuard(ctypes.Structure):
+    """samo_step_guard"""
+    _fields_ = [("d_stats", ctypes.c_void_p), ("max_grad_norm", ctypes.c_float), ("skip_on_nonfinite", ctypes.c_int32)]
 
 
 class IndexJob(ctypes.Structure):
@@ -72,6 +83,17 @@ _SIGNATURES = {
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "samo_gather_grads": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
                                            ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_gather_grads_fp16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                                ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]),
+    "samo_sgd_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                       ctypes.POINTER(SgdCfg), ctypes.c_void_p]),
+    "samo_adam_expand_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+                                               ctypes.c_void_p]),
+    "samo_fused_sgd_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_float, ctypes.POINTER(SgdCfg), ctypes.c_void_p]),
     "samo_adam_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
     "samo_fused_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
@@ -81,11 +103,22 @@ _SIGNATURES = {
     "samo_plan_destroy": (ctypes.c_int32, [ctypes.c_void_p]),
     "samo_plan_totals": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_int64)]),
+    "samo_plan_stats_workspace_bytes": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)]),
     "samo_decompress_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p]),
-    "samo_gather_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]),
-    "samo_adam_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_gather_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_size_t, ctypes.c_void_p]),
+    "samo_gather_fp16_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "samo_grad_stats_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+                                                 ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "samo_adam_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(AdamCfg), ctypes.POINTER(StepGuard),
+                                           ctypes.c_void_p]),
     "samo_fused_step_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
-                                                 ctypes.c_void_p]),
+                                                 ctypes.POINTER(StepGuard), ctypes.c_void_p]),
+    "samo_adam_expand_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+                                                  ctypes.POINTER(StepGuard), ctypes.c_void_p]),
+    "samo_fused_sgd_step_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(SgdCfg),
+                                                     ctypes.POINTER(StepGuard), ctypes.c_void_p]),
     "samo_memory_model": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
     "samo_stream_copy": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
@@ -104,7 +137,7 @@ def lib() -> ctypes.CDLL:
             fn = getattr(handle, name)
             fn.restype = res
             fn.argtypes = args
-        if handle.samo_abi_version() != 1:
+        if handle.samo_abi_version() != 2:
             raise ImportError("libsamo.so has an unexpected ABI version")
         _lib = handle
     return _lib
@@ -253,6 +286,48 @@ def samo_gather_grads(g: torch.Tensor, idx: Optional[torch.Tensor], inv_loss_sca
            "samo_gather_grads")
 
 
+def samo_gather_grads_fp16(g: torch.Tensor, idx: Optional[torch.Tensor], gc16: torch.Tensor,
+                           accumulate: bool = False) -> None:
+    n, nnz = g.numel(), gc16.numel()
+    _check(lib().samo_gather_grads_fp16(_dev(g, _F16, "g"), n, _dev(idx, torch.int32, "idx", nnz), nnz,
+                                        _dev(gc16, _F16, "gc16"), int(bool(accumulate)), _stream()),
+           "samo_gather_grads_fp16")
+
+
+def sgd_cfg(lr: float, momentum: float = 0.9, weight_decay: float = 0.0) -> SgdCfg:
+    return SgdCfg(lr, momentum, weight_decay)
+
+
+def samo_sgd_step(p: torch.Tensor, buf: torch.Tensor, gc: torch.Tensor, cfg: SgdCfg) -> None:
+    nnz = p.numel()
+    _check(lib().samo_sgd_step(_dev(p, torch.float32, "p"), _dev(buf, torch.float32, "buf", nnz),
+                               _dev(gc, torch.float32, "gc", nnz), nnz, ctypes.byref(cfg), _stream()),
+           "samo_sgd_step")
+
+
+def samo_adam_expand_step(gc16: torch.Tensor, w: torch.Tensor, idx: Optional[torch.Tensor],
+                          seg_ptr: Optional[torch.Tensor], p: torch.Tensor, m: torch.Tensor, v: torch.Tensor,
+                          inv_loss_scale: float, cfg: AdamCfg) -> None:
+    n, nnz = w.numel(), p.numel()
+    _check(lib().samo_adam_expand_step(_dev(gc16, _F16, "gc16", nnz), _dev(w, _F16, "w"), n,
+                                       _dev(idx, torch.int32, "idx", nnz),
+                                       _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)), nnz,
+                                       _dev(p, torch.float32, "p"), _dev(m, torch.float32, "m", nnz),
+                                       _dev(v, torch.float32, "v", nnz), float(inv_loss_scale), ctypes.byref(cfg),
+                                       _stream()), "samo_adam_expand_step")
+
+
+def samo_fused_sgd_step(g: torch.Tensor, w: torch.Tensor, idx: Optional[torch.Tensor],
+                        seg_ptr: Optional[torch.Tensor], p: torch.Tensor, buf: torch.Tensor,
+                        inv_loss_scale: float, cfg: SgdCfg) -> None:
+    n, nnz = w.numel(), p.numel()
+    _check(lib().samo_fused_sgd_step(_dev(g, _F16, "g", n), _dev(w, _F16, "w"), n,
+                                     _dev(idx, torch.int32, "idx", nnz),
+                                     _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)), nnz,
+                                     _dev(p, torch.float32, "p"), _dev(buf, torch.float32, "buf", nnz),
+                                     float(inv_loss_scale), ctypes.byref(cfg), _stream()), "samo_fused_sgd_step")
+
+
 def samo_adam_step(p: torch.Tensor, m: torch.Tensor, v: torch.Tensor, gc: torch.Tensor, cfg: AdamCfg) -> None:
     nnz = p.numel()
     _check(lib().samo_adam_step(_dev(p, torch.float32, "p"), _dev(m, torch.float32, "m", nnz),
@@ -281,13 +356,36 @@ class Layer(NamedTuple):
     w: Optional[torch.Tensor] = None
     g: Optional[torch.Tensor] = None
     gc: Optional[torch.Tensor] = None
+    gc16: Optional[torch.Tensor] = None
 
 
-def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, align: int = 256) -> list:
+class GradStats:
+    """A device-resident samo_grad_stats plus the reduction workspace of a plan."""
+
+    def __init__(self, plan: "Plan"):
+        dev = plan.device
+        self.buf = torch.zeros(2, dtype=torch.float64, device=dev)          # 16 bytes: double, int32, int32
+        self.workspace = torch.empty(plan.stats_workspace_bytes(), dtype=torch.uint8, device=dev)
+
+    @property
+    def ptr(self) -> int:
+        return self.buf.data_ptr()
+
+    def read(self):
+        """(sum_squares, nonfinite) — synchronises with the device."""
+        host = self.buf.cpu()
+        return float(host[0]), bool(host[1:2].view(torch.int32)[0].item())
+
+    def guard(self, max_grad_norm: float = 0.0, skip_on_nonfinite: bool = False) -> StepGuard:
+        return StepGuard(self.ptr, float(max_grad_norm), int(bool(skip_on_nonfinite)))
+
+
+def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, with_gc16: bool = False,
+                align: int = 256) -> list:
     """Device buffers for a whole model in ONE allocation, layer-major.
 
     shapes: (n, nnz, dense) per layer.  Returns one Layer per entry whose tensors are views of a
-    single uint8 arena in the order seg_ptr, idx, p, g, m, v, w[, gc] for layer 0, then layer 1, ...
+    single uint8 arena in the order seg_ptr, idx, p, g, m, v, w[, gc][, gc16] for layer 0, then layer 1, ...
     Keeping a layer's arrays adjacent in the address space is worth ~4 % of the fused step's
     bandwidth on MI355X compared with grouping the arrays by kind across layers (measured on the
     GPT-3 2.7B shape); m and v start at zero, everything else is uninitialised.  Memory plumbing
@@ -304,6 +402,8 @@ def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, align: i
                  ("v", 4 * nnz, torch.float32), ("w", 2 * n, _F16)]
         if with_gc:
             sizes.append(("gc", 4 * nnz, torch.float32))
+        if with_gc16:
+            sizes.append(("gc16", 2 * nnz, _F16))
         offs = {}
         for name, nb, dt in sizes:
             offs[name] = (total, nb, dt)
@@ -316,7 +416,7 @@ def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, align: i
         t["m"].zero_()
         t["v"].zero_()
         layers.append(Layer(n, None if dense else t["idx"], None if dense else t["seg_ptr"], t["p"], t["m"], t["v"],
-                            t["w"], t["g"], t.get("gc")))
+                            t["w"], t["g"], t.get("gc"), t.get("gc16")))
     return layers
 
 
@@ -326,6 +426,7 @@ class Plan:
     def __init__(self, layers: Sequence[Layer]):
         self._handle = ctypes.c_void_p()
         self._layers = list(layers)          # keeps the tensors alive
+        self.device = next((L.p.device for L in self._layers), torch.device("cuda", torch.cuda.current_device()))
         descs = (LayerDesc * max(len(self._layers), 1))()
         for d, L in zip(descs, self._layers):
             nnz = L.p.numel()
@@ -338,6 +439,7 @@ class Plan:
             d.w = _dev(L.w, _F16, "w", L.n)
             d.g = _dev(L.g, _F16, "g", L.n)
             d.gc = _dev(L.gc, torch.float32, "gc", nnz)
+            d.gc16 = _dev(L.gc16, _F16, "gc16", nnz)
         _check(lib().samo_plan_create(descs, len(self._layers), ctypes.byref(self._handle)), "samo_plan_create")
 
     def close(self) -> None:
@@ -356,18 +458,53 @@ class Plan:
         _check(lib().samo_plan_totals(self._handle, ctypes.byref(n), ctypes.byref(nnz)), "samo_plan_totals")
         return n.value, nnz.value
 
+    def stats_workspace_bytes(self) -> int:
+        out = ctypes.c_size_t()
+        _check(lib().samo_plan_stats_workspace_bytes(self._handle, ctypes.byref(out)), "samo_plan_stats_workspace_bytes")
+        return out.value
+
+    @staticmethod
+    def _stats_args(stats: Optional[GradStats]):
+        if stats is None:
+            return None, None, 0
+        return stats.ptr, stats.workspace.data_ptr(), stats.workspace.numel()
+
+    @staticmethod
+    def _guard_arg(guard: Optional[StepGuard]):
+        return ctypes.byref(guard) if guard is not None else None
+
     def samo_decompress_batched(self) -> None:
         _check(lib().samo_decompress_batched(self._handle, _stream()), "samo_decompress_batched")
 
-    def samo_gather_batched(self, inv_loss_scale: float) -> None:
-        _check(lib().samo_gather_batched(self._handle, float(inv_loss_scale), _stream()), "samo_gather_batched")
+    def samo_gather_batched(self, inv_loss_scale: float, stats: Optional[GradStats] = None) -> None:
+        _check(lib().samo_gather_batched(self._handle, float(inv_loss_scale), *self._stats_args(stats), _stream()),
+               "samo_gather_batched")
 
-    def samo_adam_batched(self, cfg: AdamCfg) -> None:
-        _check(lib().samo_adam_batched(self._handle, ctypes.byref(cfg), _stream()), "samo_adam_batched")
+    def samo_gather_fp16_batched(self, accumulate: bool, inv_loss_scale: float,
+                                 stats: Optional[GradStats] = None) -> None:
+        _check(lib().samo_gather_fp16_batched(self._handle, int(bool(accumulate)), float(inv_loss_scale),
+                                              *self._stats_args(stats), _stream()), "samo_gather_fp16_batched")
 
-    def samo_fused_step_batched(self, inv_loss_scale: float, cfg: AdamCfg) -> None:
-        _check(lib().samo_fused_step_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg), _stream()),
-               "samo_fused_step_batched")
+    def samo_grad_stats_batched(self, source: int, inv_loss_scale: float, stats: GradStats) -> None:
+        _check(lib().samo_grad_stats_batched(self._handle, int(source), float(inv_loss_scale),
+                                             *self._stats_args(stats), _stream()), "samo_grad_stats_batched")
+
+    def samo_adam_batched(self, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
+        _check(lib().samo_adam_batched(self._handle, ctypes.byref(cfg), self._guard_arg(guard), _stream()),
+               "samo_adam_batched")
+
+    def samo_fused_step_batched(self, inv_loss_scale: float, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
+        _check(lib().samo_fused_step_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg),
+                                             self._guard_arg(guard), _stream()), "samo_fused_step_batched")
+
+    def samo_adam_expand_batched(self, inv_loss_scale: float, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
+        _check(lib().samo_adam_expand_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg),
+                                              self._guard_arg(guard), _stream()), "samo_adam_expand_batched")
+
+    def samo_fused_sgd_step_batched(self, inv_loss_scale: float, cfg: SgdCfg,
+                                    guard: Optional[StepGuard] = None) -> None:
+        _check(lib().samo_fused_sgd_step_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg),
+                                                 self._guard_arg(guard), _stream()), "samo_fused_sgd_step_batched")
 
 
 def samo_memory_model(n_total: int, nnz_total: int):

@@ -17,7 +17,7 @@ struct samo_plan {
     WgRec *d_chunks = nullptr;
     int64_t ntiles = 0, nchunks = 0;
     int64_t n_total = 0, nnz_total = 0;
-    bool has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true;
+    bool has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true, has_gc16 = true;
 };
 
 namespace {
@@ -172,6 +172,75 @@ samo_status samo_validate_index(const int32_t *d_idx, int64_t nnz, int64_t n, co
     return hip_status(launch_validate(d_idx, nnz, n, d_seg_ptr, d_ok, as_stream(stream)));
 }
 
+}  // extern "C"
+
+namespace {
+
+LaunchSet single(const samo_layer &L, int64_t wgs)
+{
+    LaunchSet ls;
+    ls.one = L;
+    ls.layers = nullptr;
+    ls.recs = nullptr;
+    ls.wgs = wgs;
+    ls.keep = L.n > 0 ? (float)((double)L.nnz / (double)L.n) : 1.f;
+    return ls;
+}
+
+const GuardK kNoGuard = {nullptr, 0.f, 0};
+
+samo_status make_sgd(const samo_sgd_cfg *c, OptK *k)
+{
+    if (!c) return SAMO_ERR_NULL;
+    if (!std::isfinite(c->lr)) return SAMO_ERR_ARG;
+    if (!(c->momentum >= 0.f && c->momentum < 1.f)) return SAMO_ERR_ARG;
+    if (!(std::isfinite(c->weight_decay) && c->weight_decay >= 0.f)) return SAMO_ERR_ARG;
+    std::memset(k, 0, sizeof(*k));
+    k->sgd_lr = c->lr;
+    k->sgd_mu = c->momentum;
+    k->sgd_wd = c->weight_decay;
+    return SAMO_OK;
+}
+
+samo_status make_adam_opt(const samo_adam_cfg *c, OptK *k)
+{
+    std::memset(k, 0, sizeof(*k));
+    return make_adam(c, &k->adam);
+}
+
+samo_status make_guard(const samo_step_guard *g, GuardK *out)
+{
+    *out = kNoGuard;
+    if (!g) return SAMO_OK;
+    if (!(g->max_grad_norm == g->max_grad_norm) || std::isinf(g->max_grad_norm)) return SAMO_ERR_ARG;
+    const bool used = g->max_grad_norm > 0.f || g->skip_on_nonfinite != 0;
+    if (used && !g->d_stats) return SAMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(g->d_stats) & 7u) return SAMO_ERR_ALIGN;
+    if (used) {
+        out->stats = g->d_stats;
+        out->max_norm = g->max_grad_norm;
+        out->skip = g->skip_on_nonfinite != 0;
+    }
+    return SAMO_OK;
+}
+
+// Common argument checks of the single-layer step entries (dense layers allowed).
+samo_status check_step_args(const void *grad, uint16_t *w, int64_t n, const int32_t *idx, const int32_t *seg_ptr,
+                            int64_t nnz, const float *p, const float *m, const float *v, bool need_v,
+                            float inv_loss_scale)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (samo_status s = check_index_args(idx, seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
+    if (n > 0 && !w) return SAMO_ERR_NULL;
+    if (nnz > 0 && (!grad || !p || !m || (need_v && !v))) return SAMO_ERR_NULL;
+    if (misaligned(grad) || misaligned(w) || misaligned(p) || misaligned(m) || misaligned(v)) return SAMO_ERR_ALIGN;
+    return check_scale(inv_loss_scale);
+}
+
+}  // namespace
+
+extern "C" {
+
 samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz,
                             uint16_t *d_w, int64_t n, void *stream)
 {
@@ -179,8 +248,12 @@ samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_
     if (samo_status s = check_index_args(d_idx, d_seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
     if ((!d_p && nnz > 0) || (!d_w && n > 0)) return SAMO_ERR_NULL;
     if (misaligned(d_p) || misaligned(d_w)) return SAMO_ERR_ALIGN;
-    samo_layer L = {n, nnz, d_idx, d_seg_ptr, const_cast<float *>(d_p), nullptr, nullptr, d_w, nullptr, nullptr};
-    return hip_status(launch_decompress(L, as_stream(stream)));
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, const_cast<float *>(d_p), nullptr, nullptr, d_w, nullptr, nullptr,
+                    nullptr};
+    OptK k;
+    std::memset(&k, 0, sizeof(k));
+    return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, single(L, ceil_div(n, kTile)), 1.f, k,
+                                  kNoGuard, as_stream(stream)));
 }
 
 samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_idx, int64_t nnz,
@@ -191,8 +264,21 @@ samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_i
     if (nnz > 0 && (!d_g || !d_gc)) return SAMO_ERR_NULL;
     if (misaligned(d_g) || misaligned(d_idx) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
-    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, d_gc};
-    return hip_status(launch_gather(L, inv_loss_scale, as_stream(stream)));
+    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, d_gc, nullptr};
+    return hip_status(launch_gather(kOutF32, kGradDense, single(L, ceil_div(nnz, kChunk)), inv_loss_scale, 0, nullptr,
+                                    as_stream(stream)));
+}
+
+samo_status samo_gather_grads_fp16(const uint16_t *d_g, int64_t n, const int32_t *d_idx, int64_t nnz,
+                                   uint16_t *d_gc16, int32_t accumulate, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (!d_idx && nnz > 0 && nnz != n) return SAMO_ERR_NULL;
+    if (nnz > 0 && (!d_g || !d_gc16)) return SAMO_ERR_NULL;
+    if (misaligned(d_g) || misaligned(d_idx) || misaligned(d_gc16)) return SAMO_ERR_ALIGN;
+    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, nullptr, d_gc16};
+    return hip_status(launch_gather(kOutF16, kGradDense, single(L, ceil_div(nnz, kChunk)), 1.f, accumulate != 0,
+                                    nullptr, as_stream(stream)));
 }
 
 samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,
@@ -201,27 +287,65 @@ samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc
     if (nnz < 0 || nnz > kMaxN) return SAMO_ERR_SIZE;
     if (nnz > 0 && (!d_p || !d_m || !d_v || !d_gc)) return SAMO_ERR_NULL;
     if (misaligned(d_p) || misaligned(d_m) || misaligned(d_v) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
-    AdamK k;
-    if (samo_status s = make_adam(h_cfg, &k)) return s;
-    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_m, d_v, nullptr, nullptr, const_cast<float *>(d_gc)};
-    return hip_status(launch_adam(L, k, as_stream(stream)));
+    OptK k;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_m, d_v, nullptr, nullptr, const_cast<float *>(d_gc), nullptr};
+    return hip_status(launch_flat_step(kOptAdam, single(L, ceil_div(nnz, kChunk)), k, kNoGuard, as_stream(stream)));
+}
+
+samo_status samo_sgd_step(float *d_p, float *d_buf, const float *d_gc, int64_t nnz, const samo_sgd_cfg *h_cfg,
+                          void *stream)
+{
+    if (nnz < 0 || nnz > kMaxN) return SAMO_ERR_SIZE;
+    if (nnz > 0 && (!d_p || !d_buf || !d_gc)) return SAMO_ERR_NULL;
+    if (misaligned(d_p) || misaligned(d_buf) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
+    OptK k;
+    if (samo_status s = make_sgd(h_cfg, &k)) return s;
+    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_buf, nullptr, nullptr, nullptr, const_cast<float *>(d_gc),
+                    nullptr};
+    return hip_status(launch_flat_step(kOptSgd, single(L, ceil_div(nnz, kChunk)), k, kNoGuard, as_stream(stream)));
 }
 
 samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const int32_t *d_idx,
                             const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m, float *d_v,
                             float inv_loss_scale, const samo_adam_cfg *h_cfg, void *stream)
 {
-    if (samo_status s = check_sizes(n, nnz)) return s;
-    if (samo_status s = check_index_args(d_idx, d_seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
-    if (n > 0 && (!d_g || !d_w)) return SAMO_ERR_NULL;
-    if (nnz > 0 && (!d_p || !d_m || !d_v)) return SAMO_ERR_NULL;
-    if (misaligned(d_g) || misaligned(d_w) || misaligned(d_p) || misaligned(d_m) || misaligned(d_v))
-        return SAMO_ERR_ALIGN;
-    if (samo_status s = check_scale(inv_loss_scale)) return s;
-    AdamK k;
-    if (samo_status s = make_adam(h_cfg, &k)) return s;
-    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr};
-    return hip_status(launch_fused(L, inv_loss_scale, k, as_stream(stream)));
+    if (samo_status s = check_step_args(d_g, d_w, n, d_idx, d_seg_ptr, nnz, d_p, d_m, d_v, true, inv_loss_scale))
+        return s;
+    if (n > 0 && !d_g) return SAMO_ERR_NULL;
+    OptK k;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr, nullptr};
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptAdam, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+                                  kNoGuard, as_stream(stream)));
+}
+
+samo_status samo_adam_expand_step(const uint16_t *d_gc16, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                                  const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_m, float *d_v,
+                                  float inv_loss_scale, const samo_adam_cfg *h_cfg, void *stream)
+{
+    if (samo_status s = check_step_args(d_gc16, d_w, n, d_idx, d_seg_ptr, nnz, d_p, d_m, d_v, true, inv_loss_scale))
+        return s;
+    OptK k;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, nullptr, nullptr, const_cast<uint16_t *>(d_gc16)};
+    return hip_status(launch_tile(kModeStep, kGradC16, kOptAdam, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+                                  kNoGuard, as_stream(stream)));
+}
+
+samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const int32_t *d_idx,
+                                const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_buf,
+                                float inv_loss_scale, const samo_sgd_cfg *h_cfg, void *stream)
+{
+    if (samo_status s = check_step_args(d_g, d_w, n, d_idx, d_seg_ptr, nnz, d_p, d_buf, nullptr, false,
+                                        inv_loss_scale))
+        return s;
+    if (n > 0 && !d_g) return SAMO_ERR_NULL;
+    OptK k;
+    if (samo_status s = make_sgd(h_cfg, &k)) return s;
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_buf, nullptr, d_w, d_g, nullptr, nullptr};
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+                                  kNoGuard, as_stream(stream)));
 }
 
 // ------------------------------------------------------------------------------ plan
@@ -241,13 +365,14 @@ samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, sam
         if (st == SAMO_OK) st = check_index_args(L.idx, L.seg_ptr, L.n, L.nnz, /*allow_dense=*/true);
         if (st == SAMO_OK && !L.p && L.nnz > 0) st = SAMO_ERR_NULL;
         if (st == SAMO_OK && (misaligned(L.p) || misaligned(L.m) || misaligned(L.v) || misaligned(L.w) ||
-                              misaligned(L.g) || misaligned(L.gc)))
+                              misaligned(L.g) || misaligned(L.gc) || misaligned(L.gc16)))
             st = SAMO_ERR_ALIGN;
         if (st != SAMO_OK) break;
         if (L.nnz > 0) {
             plan->has_m &= L.m != nullptr;
             plan->has_v &= L.v != nullptr;
             plan->has_gc &= L.gc != nullptr;
+            plan->has_gc16 &= L.gc16 != nullptr;
         }
         if (L.n > 0) {
             plan->has_w &= L.w != nullptr;
@@ -309,41 +434,163 @@ samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *n
     return SAMO_OK;
 }
 
+samo_status samo_plan_stats_workspace_bytes(const samo_plan *plan, size_t *bytes)
+{
+    if (!plan || !bytes) return SAMO_ERR_NULL;
+    *bytes = (size_t)(plan->nchunks > 0 ? plan->nchunks : 1) * sizeof(StatPartial);
+    return SAMO_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+LaunchSet tiles_of(const samo_plan *plan)
+{
+    LaunchSet ls;
+    std::memset(&ls, 0, sizeof(ls));
+    ls.layers = plan->d_layers;
+    ls.recs = plan->d_tiles;
+    ls.wgs = plan->ntiles;
+    ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
+    return ls;
+}
+
+LaunchSet chunks_of(const samo_plan *plan)
+{
+    LaunchSet ls;
+    std::memset(&ls, 0, sizeof(ls));
+    ls.layers = plan->d_layers;
+    ls.recs = plan->d_chunks;
+    ls.wgs = plan->nchunks;
+    ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
+    return ls;
+}
+
+// Workspace check of the entries that can reduce gradient statistics.
+samo_status check_stats_args(const samo_plan *plan, const samo_grad_stats *d_stats, const void *ws, size_t ws_bytes)
+{
+    if (!d_stats) return SAMO_OK;
+    if (!ws) return SAMO_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(d_stats) & 7u) || misaligned(ws)) return SAMO_ERR_ALIGN;
+    size_t need = 0;
+    samo_plan_stats_workspace_bytes(plan, &need);
+    return ws_bytes >= need ? SAMO_OK : SAMO_ERR_SIZE;
+}
+
+// Gather-type launch over the plan's chunks, followed by the reduction of the partials.
+samo_status run_gather(const samo_plan *plan, int out, int src, float inv_scale, int accumulate,
+                       samo_grad_stats *d_stats, void *ws, hipStream_t s)
+{
+    StatPartial *partials = d_stats ? reinterpret_cast<StatPartial *>(ws) : nullptr;
+    if (launch_gather(out, src, chunks_of(plan), inv_scale, accumulate, partials, s) != hipSuccess)
+        return SAMO_ERR_HIP;
+    if (d_stats) return hip_status(launch_stats_finalize(partials, ceil_div(plan->nchunks, kStatRecs), d_stats, s));
+    return SAMO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 samo_status samo_decompress_batched(const samo_plan *plan, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
     if (!plan->has_w) return SAMO_ERR_PLAN;
-    return hip_status(launch_decompress_batched(plan->d_layers, plan->d_tiles, plan->ntiles, as_stream(stream)));
+    OptK k;
+    std::memset(&k, 0, sizeof(k));
+    return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, tiles_of(plan), 1.f, k, kNoGuard,
+                                  as_stream(stream)));
 }
 
-samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, void *stream)
+samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, samo_grad_stats *d_stats,
+                                void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
     if (!plan->has_g || !plan->has_gc) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
-    return hip_status(launch_gather_batched(plan->d_layers, plan->d_chunks, plan->nchunks, inv_loss_scale,
-                                            as_stream(stream)));
+    if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
+    return run_gather(plan, kOutF32, kGradDense, inv_loss_scale, 0, d_stats, d_workspace, as_stream(stream));
 }
 
-samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, void *stream)
+samo_status samo_gather_fp16_batched(const samo_plan *plan, int32_t accumulate, float inv_loss_scale,
+                                     samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_g || !plan->has_gc16) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
+    return run_gather(plan, kOutF16, kGradDense, inv_loss_scale, accumulate != 0, d_stats, d_workspace,
+                      as_stream(stream));
+}
+
+samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float inv_loss_scale,
+                                    samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
+                                    void *stream)
+{
+    if (!plan || !d_stats) return SAMO_ERR_NULL;
+    if (source < 0 || source > 2) return SAMO_ERR_ARG;
+    if ((source == kGradDense && !plan->has_g) || (source == kGradC16 && !plan->has_gc16) ||
+        (source == kGradC32 && !plan->has_gc))
+        return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
+    return run_gather(plan, kOutNone, source, inv_loss_scale, 0, d_stats, d_workspace, as_stream(stream));
+}
+
+samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,
+                              void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
     if (!plan->has_m || !plan->has_v || !plan->has_gc) return SAMO_ERR_PLAN;
-    AdamK k;
-    if (samo_status s = make_adam(h_cfg, &k)) return s;
-    return hip_status(launch_adam_batched(plan->d_layers, plan->d_chunks, plan->nchunks, k, as_stream(stream)));
+    OptK k;
+    GuardK guard;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    if (samo_status s = make_guard(h_guard, &guard)) return s;
+    return hip_status(launch_flat_step(kOptAdam, chunks_of(plan), k, guard, as_stream(stream)));
 }
 
 samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale, const samo_adam_cfg *h_cfg,
-                                    void *stream)
+                                    const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
     if (!plan->has_m || !plan->has_v || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
-    AdamK k;
-    if (samo_status s = make_adam(h_cfg, &k)) return s;
-    return hip_status(launch_fused_batched(plan->d_layers, plan->d_tiles, plan->ntiles, inv_loss_scale, k,
-                                           as_stream(stream)));
+    OptK k;
+    GuardK guard;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    if (samo_status s = make_guard(h_guard, &guard)) return s;
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptAdam, tiles_of(plan), inv_loss_scale, k, guard,
+                                  as_stream(stream)));
+}
+
+samo_status samo_adam_expand_batched(const samo_plan *plan, float inv_loss_scale, const samo_adam_cfg *h_cfg,
+                                     const samo_step_guard *h_guard, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_m || !plan->has_v || !plan->has_w || !plan->has_gc16) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    OptK k;
+    GuardK guard;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    if (samo_status s = make_guard(h_guard, &guard)) return s;
+    return hip_status(launch_tile(kModeStep, kGradC16, kOptAdam, tiles_of(plan), inv_loss_scale, k, guard,
+                                  as_stream(stream)));
+}
+
+samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_scale, const samo_sgd_cfg *h_cfg,
+                                        const samo_step_guard *h_guard, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_m || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    OptK k;
+    GuardK guard;
+    if (samo_status s = make_sgd(h_cfg, &k)) return s;
+    if (samo_status s = make_guard(h_guard, &guard)) return s;
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, tiles_of(plan), inv_loss_scale, k, guard,
+                                  as_stream(stream)));
 }
 
 samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper_default, int64_t *paper_samo,

@@ -8,54 +8,57 @@
 
 namespace samo {
 
-#ifndef SAMO_TILE_THREADS
-#define SAMO_TILE_THREADS 256
-#endif
-#ifndef SAMO_TILE
-#define SAMO_TILE 4096
-#endif
-#ifndef SAMO_U
-#define SAMO_U 4
-#endif
-#ifndef SAMO_GLDS
-#define SAMO_GLDS 0
-#endif
-#ifndef SAMO_ADAM_DWORD
-#define SAMO_ADAM_DWORD 0
-#endif
-#ifndef SAMO_NT
-#define SAMO_NT 9
-#endif
-
-constexpr int kThreads = 256;           // 4 wavefronts of 64 lanes per workgroup (flat and index kernels)
-constexpr int kTileThreads = SAMO_TILE_THREADS;   // workgroup size of the tile kernels
+// Launch shapes, chosen by measurement on MI355X (GPT-3 2.7B shape, 90 % pruned): 16 dense
+// elements per thread in the tile kernels — (2048,128), (4096,256) and (8192,512) are within
+// 2 % of each other, 8 or 32 per thread lose 10-15 % — and one 64-lane wave per workgroup with
+// one float4 per array in the flat kernels.
+constexpr int kThreads = 256;           // index kernels: 4 wavefronts per workgroup
+constexpr int kTileThreads = 256;       // tile kernels
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
-constexpr int kTile = SAMO_TILE;        // dense elements owned by one workgroup
+constexpr int kTile = 4096;             // dense elements owned by one workgroup (8 KiB of fp16 in LDS)
 constexpr int kSegsPerTile = kTile / kSeg;
-#ifndef SAMO_CHUNK
-#define SAMO_CHUNK 256
-#endif
-#ifndef SAMO_FLAT_THREADS
-#define SAMO_FLAT_THREADS 64
-#endif
-constexpr int kChunk = SAMO_CHUNK;      // compressed elements per workgroup in the flat kernels
-constexpr int kFlatThreads = SAMO_FLAT_THREADS;
+constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
+constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
+constexpr int kStatRecs = 8;             // chunk records per workgroup when gradient statistics are reduced
+constexpr int kTileUnroll = 4;          // compressed elements in flight per thread in the tile kernels
 
 static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");
 static_assert(kTile % (8 * kTileThreads) == 0, "a tile is written out as whole 16-byte vectors per thread");
 static_assert(kChunk % (4 * kFlatThreads) == 0, "a chunk is whole float4 vectors per thread");
 
-// Adam constants prepared on the host in double precision, rounded once to fp32.
+// Optimizer constants prepared on the host in double precision, rounded once to fp32.
 struct AdamK {
     float lr, b1, b2, omb1, omb2, eps, wd;
     float rbc1, rbc2;   // 1 / (1 - beta^t)
     int l2, decoupled;
 };
+struct OptK {
+    AdamK adam;
+    float sgd_lr, sgd_mu, sgd_wd;
+};
+
+// Clipping / overflow guard evaluated on the device from the gradient statistics.
+struct GuardK {
+    const samo_grad_stats *stats;   // NULL: no guard
+    float max_norm;                 // <= 0: no clipping
+    int skip;                       // leave all state untouched if stats->nonfinite
+};
+
+enum { kModeDecompress = 0, kModeStep = 1 };
+enum { kGradDense = 0, kGradC16 = 1, kGradC32 = 2 };   // where a step reads its gradient
+enum { kOptAdam = 0, kOptSgd = 1 };
+enum { kOutF32 = 0, kOutF16 = 1, kOutNone = 2 };        // what the flat gather kernel writes
 
 // Workgroup -> (layer, local tile or chunk) record of the batched launches.
 struct WgRec {
     int32_t layer;
     int32_t local;
+};
+
+// One (sum of squares, non-finite flag) partial per workgroup of a flat launch.
+struct StatPartial {
+    double sum_squares;
+    int64_t nonfinite;
 };
 
 // Up to kIndexBatchJobs index-build jobs, passed to the kernels by value (kernel argument segment).
@@ -82,19 +85,20 @@ hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, i
 hipError_t launch_validate(const int32_t *idx, int64_t nnz, int64_t n, const int32_t *seg_ptr,
                            int32_t *ok, hipStream_t s);
 
-hipError_t launch_decompress(const samo_layer &layer, hipStream_t s);
-hipError_t launch_fused(const samo_layer &layer, float inv_scale, const AdamK &k, hipStream_t s);
-hipError_t launch_gather(const samo_layer &layer, float inv_scale, hipStream_t s);
-hipError_t launch_adam(const samo_layer &layer, const AdamK &k, hipStream_t s);
-
-hipError_t launch_decompress_batched(const samo_layer *d_layers, const WgRec *d_tiles, int64_t ntiles,
-                                     hipStream_t s);
-hipError_t launch_fused_batched(const samo_layer *d_layers, const WgRec *d_tiles, int64_t ntiles,
-                                float inv_scale, const AdamK &k, hipStream_t s);
-hipError_t launch_gather_batched(const samo_layer *d_layers, const WgRec *d_chunks, int64_t nchunks,
-                                 float inv_scale, hipStream_t s);
-hipError_t launch_adam_batched(const samo_layer *d_layers, const WgRec *d_chunks, int64_t nchunks,
-                               const AdamK &k, hipStream_t s);
+// `layers`/`recs` NULL: single-layer launch of `one`; else batched over the plan's tables.
+struct LaunchSet {
+    samo_layer one;
+    const samo_layer *layers;
+    const WgRec *recs;
+    int64_t wgs;
+    float keep;   // kept fraction nnz / n of the work (plan average); steers the occupancy target
+};
+hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
+                       const GuardK &guard, hipStream_t s);
+hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale, int accumulate,
+                         StatPartial *partials, hipStream_t s);
+hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const GuardK &guard, hipStream_t s);
+hipError_t launch_stats_finalize(const StatPartial *partials, int64_t count, samo_grad_stats *out, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 

@@ -75,7 +75,7 @@ class HostLayer:
 class DevLayer:
     """The same layer resident on the GPU; the index is built by the library from the mask."""
 
-    def __init__(self, h: HostLayer, with_gc=False):
+    def __init__(self, h: HostLayer, with_gc=False, with_gc16=False):
         self.h = h
         if h.dense:
             self.idx = self.seg_ptr = None
@@ -87,9 +87,10 @@ class DevLayer:
         self.w = nan_f16(h.n)
         self.g = nan_f16(h.n)
         self.gc = torch.full((h.p.shape[0],), float("nan"), device=DEV) if with_gc else None
+        self.gc16 = torch.full((h.p.shape[0],), float("nan"), dtype=torch.float16, device=DEV) if with_gc16 else None
 
     def set_grads(self, bits):
         self.g.copy_(dev_f16_bits(bits))
 
     def layer(self):
-        return samo.Layer(self.h.n, self.idx, self.seg_ptr, self.p, self.m, self.v, self.w, self.g, self.gc)
+        return samo.Layer(self.h.n, self.idx, self.seg_ptr, self.p, self.m, self.v, self.w, self.g, self.gc, self.gc16)

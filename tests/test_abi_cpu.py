@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_abi_version_and_strings():
     L = samo.lib()
-    assert L.samo_abi_version() == 1
+    assert L.samo_abi_version() == 2
     assert samo.status_string(0) == "ok"
     for s in range(-6, 0):
         assert samo.status_string(s) not in ("ok", "unknown status")
@@ -106,10 +106,31 @@ def test_bad_loss_scale(scale):
         == samo.SAMO_ERR_ARG
 
 
+def test_sgd_and_new_single_layer_entries_reject_bad_arguments():
+    L = samo.lib()
+    good = samo.sgd_cfg(0.1, 0.9, 0.0)
+    assert L.samo_sgd_step(FAKE, FAKE, FAKE, 4, None, None) == samo.SAMO_ERR_NULL
+    assert L.samo_sgd_step(FAKE, None, FAKE, 4, ctypes.byref(good), None) == samo.SAMO_ERR_NULL
+    for bad in (samo.sgd_cfg(float("nan")), samo.sgd_cfg(0.1, 1.0), samo.sgd_cfg(0.1, -0.1), samo.sgd_cfg(0.1, 0.9, -1.0)):
+        assert L.samo_sgd_step(FAKE, FAKE, FAKE, 4, ctypes.byref(bad), None) == samo.SAMO_ERR_ARG
+        assert L.samo_fused_sgd_step(FAKE, FAKE, 8, FAKE, FAKE, 4, FAKE, FAKE, 1.0, ctypes.byref(bad), None) \
+            == samo.SAMO_ERR_ARG
+    assert L.samo_gather_grads_fp16(FAKE, 8, FAKE, 4, None, 0, None) == samo.SAMO_ERR_NULL
+    assert L.samo_gather_grads_fp16(FAKE, 8, FAKE, 9, FAKE, 0, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_gather_grads_fp16(FAKE, 8, FAKE, 4, FAKE + 2, 0, None) == samo.SAMO_ERR_ALIGN
+    cfg = _cfg()
+    assert L.samo_adam_expand_step(None, FAKE, 8, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 1.0, ctypes.byref(cfg), None) \
+        == samo.SAMO_ERR_NULL
+    assert L.samo_adam_expand_step(FAKE, FAKE, 8, FAKE, FAKE, 4, FAKE, FAKE, FAKE, 0.0, ctypes.byref(cfg), None) \
+        == samo.SAMO_ERR_ARG
+    assert L.samo_grad_stats_batched(None, 0, 1.0, FAKE, FAKE, 16, None) == samo.SAMO_ERR_NULL
+    assert L.samo_plan_stats_workspace_bytes(None, None) == samo.SAMO_ERR_NULL
+
+
 def test_null_cfg_and_plan():
     L = samo.lib()
     assert L.samo_adam_step(FAKE, FAKE, FAKE, FAKE, 4, None, None) == samo.SAMO_ERR_NULL
-    assert L.samo_fused_step_batched(None, 1.0, ctypes.byref(_cfg()), None) == samo.SAMO_ERR_NULL
+    assert L.samo_fused_step_batched(None, 1.0, ctypes.byref(_cfg()), None, None) == samo.SAMO_ERR_NULL
     assert L.samo_plan_destroy(None) == samo.SAMO_OK
     out = ctypes.c_void_p()
     bad = (samo.LayerDesc * 1)()
