@@ -19,7 +19,7 @@ constexpr int kTile = 4096;             // dense elements owned by one workgroup
 constexpr int kSegsPerTile = kTile / kSeg;
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
-constexpr int kStatRecs = 8;             // chunk records per workgroup when gradient statistics are reduced
+constexpr int kStatGrid = 256 * 12 * 4;  // workgroups of a flat launch that also reduces gradient statistics
 constexpr int kTileUnroll = 4;          // compressed elements in flight per thread in the tile kernels
 
 static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");

@@ -71,6 +71,12 @@ __device__ __forceinline__ int find_job(const IndexBatch &batch, int wg)
     return lo;
 }
 
+// A wave takes kSegsPerWave consecutive segments: four independent 16-byte loads per lane are in
+// flight before anything is reduced, and the four per-lane counts travel through the wave
+// reduction (or scan) packed two to a register — a count is at most 1024, a 16-bit field is enough.
+constexpr int kSegsPerWave = 4;
+constexpr int kSegsPerWg = kSegsPerWave * kWavesPerWg;
+
 __global__ void __launch_bounds__(kThreads)
 count_kernel(const IndexBatch batch)
 {
@@ -78,11 +84,17 @@ count_kernel(const IndexBatch batch)
     const int64_t n = batch.n[job];
     const int64_t nseg = (n + kSeg - 1) / kSeg;
     const int lane = threadIdx.x & 63;
-    const int64_t seg = (int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6);
-    if (seg >= nseg) return;
-    const uint32_t f = lane_flags(batch.mask[job], n, seg * kSeg + lane * 16);
-    const int total = wave_sum(__popc(f));
-    if (lane == 0) batch.seg_ptr[job][seg] = total;
+    const int64_t seg0 = ((int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6)) * kSegsPerWave;
+    if (seg0 >= nseg) return;
+    uint32_t f[kSegsPerWave];
+#pragma unroll
+    for (int q = 0; q < kSegsPerWave; ++q) f[q] = lane_flags(batch.mask[job], n, (seg0 + q) * kSeg + lane * 16);
+    const int lo = wave_sum(__popc(f[0]) | (__popc(f[1]) << 16));
+    const int hi = wave_sum(__popc(f[2]) | (__popc(f[3]) << 16));
+    if (lane < kSegsPerWave && seg0 + lane < nseg) {
+        const int packed = (lane < 2) ? lo : hi;
+        batch.seg_ptr[job][seg0 + lane] = (lane & 1) ? (packed >> 16) : (packed & 0xffff);
+    }
 }
 
 // In-place exclusive scan of a job's seg_ptr[0 .. nseg] where the last entry counts as 0 on
@@ -128,18 +140,32 @@ fill_kernel(const IndexBatch batch)
     const int64_t cap = batch.cap[job];
     const int64_t nseg = (n + kSeg - 1) / kSeg;
     const int lane = threadIdx.x & 63;
-    const int64_t seg = (int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6);
-    if (seg >= nseg || cap <= 0) return;
+    const int64_t seg0 = ((int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6)) * kSegsPerWave;
+    if (seg0 >= nseg || cap <= 0) return;
     int32_t *__restrict__ idx = batch.idx[job];
-    const int64_t first = seg * kSeg + lane * 16;
-    uint32_t f = lane_flags(batch.mask[job], n, first);
-    const int cnt = __popc(f);
-    int64_t out = (int64_t)batch.seg_ptr[job][seg] + (wave_inclusive_scan(cnt, lane) - cnt);
-    while (f) {
-        const int b = __ffs(f) - 1;
-        f &= f - 1;
-        if (out < cap) idx[out] = (int32_t)(first + b);
-        ++out;
+    uint32_t f[kSegsPerWave];
+    int base[kSegsPerWave];
+#pragma unroll
+    for (int q = 0; q < kSegsPerWave; ++q) {
+        f[q] = lane_flags(batch.mask[job], n, (seg0 + q) * kSeg + lane * 16);
+        base[q] = (seg0 + q < nseg) ? batch.seg_ptr[job][seg0 + q] : 0;
+    }
+    const int c01 = __popc(f[0]) | (__popc(f[1]) << 16);
+    const int c23 = __popc(f[2]) | (__popc(f[3]) << 16);
+    const int e01 = wave_inclusive_scan(c01, lane) - c01;       // exclusive lane prefixes, two per register
+    const int e23 = wave_inclusive_scan(c23, lane) - c23;
+    const int excl[kSegsPerWave] = {e01 & 0xffff, e01 >> 16, e23 & 0xffff, e23 >> 16};
+#pragma unroll
+    for (int q = 0; q < kSegsPerWave; ++q) {
+        const int64_t first = (seg0 + q) * kSeg + lane * 16;
+        int64_t out = (int64_t)base[q] + excl[q];
+        uint32_t bits = f[q];
+        while (bits) {
+            const int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            if (out < cap) idx[out] = (int32_t)(first + b);
+            ++out;
+        }
     }
 }
 
@@ -194,7 +220,7 @@ hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s)
     return hipGetLastError();
 }
 
-int64_t index_job_workgroups(int64_t n) { return ceil_div(ceil_div(n, kSeg), kWavesPerWg); }
+int64_t index_job_workgroups(int64_t n) { return ceil_div(ceil_div(n, kSeg), kSegsPerWg); }
 
 hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr, hipStream_t s)
 {

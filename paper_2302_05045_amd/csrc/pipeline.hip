@@ -317,19 +317,19 @@ __device__ __forceinline__ void write_partial(double ss, int bad, StatPartial *_
 // Gradient compression.  SRC: where a value comes from (dense g at idx, gc16, gc); OUT: what is
 // written (fp32 unscaled gc, fp16 gc16 with optional accumulation, nothing).  When `partials` is
 // given, the sum of squares and the non-finite flag of the unscaled values are reduced as well.
-// A workgroup takes RECS consecutive chunk records (1 normally; kStatRecs when statistics are
-// reduced, so that the wave reduction and the partial's store are paid once per 2048 elements).
-template <int OUT, int RECS>
+// Launched with one workgroup per chunk record normally.  When statistics are reduced the grid is
+// a fixed kStatGrid workgroups that stride over the records, so that the wave reduction and the
+// partial's store are paid once per workgroup and the number (and order) of partials is fixed.
+template <int OUT, bool STRIDED>
 __global__ void __launch_bounds__(kFlatThreads)
 gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, StatPartial *__restrict__ partials)
 {
     double ss = 0.0;
     int bad = 0;
     static_assert(kChunk == 4 * kFlatThreads, "one float4 per thread and chunk record");
-#pragma unroll
-    for (int c = 0; c < RECS; ++c) {
-        const int64_t rec = (int64_t)blockIdx.x * RECS + c;
-        if (rec >= ls.wgs) break;
+    const int64_t rec_end = STRIDED ? ls.wgs : (int64_t)blockIdx.x + 1;     // straight-line code when not strided
+    const int64_t rec_step = STRIDED ? (int64_t)gridDim.x : 1;
+    for (int64_t rec = blockIdx.x; rec < rec_end; rec += rec_step) {
         samo_layer L;
         int64_t chunk;
         pick_work_at(ls, rec, &L, &chunk);
@@ -417,9 +417,21 @@ stats_finalize_kernel(const StatPartial *__restrict__ partials, int64_t count, s
     __shared__ int sh_bad[kFinalizeThreads / 64];
     double ss = 0.0;
     int bad = 0;
-    for (int64_t i = threadIdx.x; i < count; i += kFinalizeThreads) {
-        ss += partials[i].sum_squares;
-        bad |= partials[i].nonfinite != 0;
+    constexpr int kAhead = 8;                 // loads in flight per thread; the additions keep their order
+    for (int64_t i0 = threadIdx.x; i0 < count; i0 += (int64_t)kAhead * kFinalizeThreads) {
+        StatPartial part[kAhead];
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int64_t i = i0 + (int64_t)a * kFinalizeThreads;
+            part[a].sum_squares = 0.0;
+            part[a].nonfinite = 0;
+            if (i < count) part[a] = partials[i];
+        }
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            ss += part[a].sum_squares;
+            bad |= part[a].nonfinite != 0;
+        }
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     ss = wave_sum_f64(ss);
@@ -516,8 +528,9 @@ static int occ_tile_step(int gsrc, int opt, float keep)
     static const int forced = env_int("SAMO_OCC_TILE_STEP", -1);
     if (forced >= 0) return forced;
     const float per_tile = keep * kTile;               // compressed elements per workgroup, on average
-    if (gsrc == kGradDense && opt == kOptAdam) return per_tile < 300.f ? 7 : (per_tile < 600.f ? 6 : 5);
-    if (gsrc == kGradDense) return per_tile < 300.f ? 7 : 6;     // SGD: one state less in flight
+    // one workgroup too many costs 10 % (a cliff), one too few 2-3 % (a slope): lean low
+    if (gsrc == kGradDense && opt == kOptAdam) return per_tile < 600.f ? 6 : 5;
+    if (gsrc == kGradDense) return 6;                            // SGD: one state less in flight
     return per_tile < 600.f ? 0 : 6;                             // compressed gradient: no dense lines in flight
 }
 
@@ -533,7 +546,7 @@ static int occ_flat_gather(int src, float keep, bool with_stats)
 {
     static const int forced = env_int("SAMO_OCC_FLAT_GATHER", -1);
     static const int forced_stats = env_int("SAMO_OCC_FLAT_STATS", -1);
-    if (with_stats) return forced_stats >= 0 ? forced_stats : 0;   // 8 records per workgroup: uncapped is best
+    if (with_stats) return forced_stats >= 0 ? forced_stats : 0;   // strided launch: uncapped is best
     if (forced >= 0) return forced;
     if (src != kGradDense) return 12;
     const float per_wave = 1024.f + 512.f / (keep > 0.01f ? keep : 0.01f);
@@ -576,15 +589,15 @@ hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale,
     if (ls.wgs <= 0) return hipSuccess;
     const dim3 block(kFlatThreads);
     const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 64);
+    const int64_t wgs = partials ? (ls.wgs < kStatGrid ? ls.wgs : kStatGrid) : ls.wgs;
+    const dim3 grid((unsigned)wgs);
     if (partials) {
-        const dim3 grid((unsigned)ceil_div(ls.wgs, kStatRecs));
-        if (out == kOutF32) gather_kernel<kOutF32, kStatRecs><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
-        else if (out == kOutF16) gather_kernel<kOutF16, kStatRecs><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
-        else gather_kernel<kOutNone, kStatRecs><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
+        if (out == kOutF32) gather_kernel<kOutF32, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
+        else if (out == kOutF16) gather_kernel<kOutF16, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
+        else gather_kernel<kOutNone, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     } else {
-        const dim3 grid((unsigned)ls.wgs);
-        if (out == kOutF32) gather_kernel<kOutF32, 1><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
-        else if (out == kOutF16) gather_kernel<kOutF16, 1><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
+        if (out == kOutF32) gather_kernel<kOutF32, false><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
+        else if (out == kOutF16) gather_kernel<kOutF16, false><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
     }
     return hipGetLastError();
 }
