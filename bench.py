@@ -249,7 +249,7 @@ def main():
                    "resident_bytes": samo.samo_memory_model(n_total, nnz_total)[2]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "tile_kernel<fused,batched>", "kernel_ms": round(kernel_ms, 4),
+                     "kernel": "tile_kernel<1, 0, 0> (step, dense gradient, Adam)", "kernel_ms": round(kernel_ms, 4),
                      "algorithmic_bytes_per_launch": fused_bytes},
         "cpu_baseline": cpu,
         "entries": entries,
