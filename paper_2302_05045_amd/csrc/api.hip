@@ -437,7 +437,7 @@ samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *n
 samo_status samo_plan_stats_workspace_bytes(const samo_plan *plan, size_t *bytes)
 {
     if (!plan || !bytes) return SAMO_ERR_NULL;
-    *bytes = (size_t)kStatGrid * sizeof(StatPartial);
+    *bytes = (size_t)stats_workspace_partials(plan->nchunks) * sizeof(StatPartial);
     return SAMO_OK;
 }
 
@@ -485,7 +485,7 @@ samo_status run_gather(const samo_plan *plan, int out, int src, float inv_scale,
     StatPartial *partials = d_stats ? reinterpret_cast<StatPartial *>(ws) : nullptr;
     if (launch_gather(out, src, chunks_of(plan), inv_scale, accumulate, partials, s) != hipSuccess)
         return SAMO_ERR_HIP;
-    if (d_stats) return hip_status(launch_stats_finalize(partials, plan->nchunks < kStatGrid ? plan->nchunks : kStatGrid, d_stats, s));
+    if (d_stats) return hip_status(launch_stats_finalize(partials, plan->nchunks, d_stats, s));
     return SAMO_OK;
 }
 

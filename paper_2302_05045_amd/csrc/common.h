@@ -19,7 +19,7 @@ constexpr int kTile = 4096;             // dense elements owned by one workgroup
 constexpr int kSegsPerTile = kTile / kSeg;
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
-constexpr int kStatGrid = 256 * 12 * 4;  // workgroups of a flat launch that also reduces gradient statistics
+constexpr int kStatReduceGrid = 1024;    // workgroups of the first level of the gradient-statistics reduction
 constexpr int kTileUnroll = 4;          // compressed elements in flight per thread in the tile kernels
 
 static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");
@@ -98,7 +98,8 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
 hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale, int accumulate,
                          StatPartial *partials, hipStream_t s);
 hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const GuardK &guard, hipStream_t s);
-hipError_t launch_stats_finalize(const StatPartial *partials, int64_t count, samo_grad_stats *out, hipStream_t s);
+int64_t stats_workspace_partials(int64_t gather_wgs);
+hipError_t launch_stats_finalize(StatPartial *partials, int64_t gather_wgs, samo_grad_stats *out, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 

@@ -97,21 +97,16 @@ __device__ __forceinline__ float guard_coef(const GuardK &gd, bool *skip)
     return coef;
 }
 
-__device__ __forceinline__ void pick_work_at(const LaunchSet &ls, int64_t rec, samo_layer *L, int64_t *local)
+__device__ __forceinline__ void pick_work(const LaunchSet &ls, samo_layer *L, int64_t *local)
 {
     if (ls.layers) {
-        const WgRec r = ls.recs[rec];
+        const WgRec r = ls.recs[blockIdx.x];
         *L = ls.layers[r.layer];
         *local = r.local;
     } else {
         *L = ls.one;
-        *local = rec;
+        *local = blockIdx.x;
     }
-}
-
-__device__ __forceinline__ void pick_work(const LaunchSet &ls, samo_layer *L, int64_t *local)
-{
-    pick_work_at(ls, blockIdx.x, L, local);
 }
 
 // ------------------------------------------------------------------ tile kernels
@@ -294,22 +289,30 @@ __device__ __forceinline__ double wave_sum_f64(double x)
     return x;
 }
 
-// Workgroup reduction of (sum of squares, flag) into one partial; fixed order, deterministic.
+// A flat workgroup is one wave: its (sum of squares, flag) partial is a wave reduction, fixed
+// order, deterministic.  Consecutive workgroups run on different XCDs (round-robin), each with its
+// own L2; the slot permutation gives every XCD a contiguous run of the partials array, so the
+// 16-byte stores of one XCD fill whole cache lines in its L2 instead of eight L2s each holding an
+// eighth of every line.
+static_assert(kFlatThreads == 64, "write_partial assumes one wave per flat workgroup");
+// Whether slot s of a launch of `grid` workgroups was written (the last few may belong to
+// workgroups beyond the grid).
+__device__ __forceinline__ bool partial_slot_used(int64_t s, unsigned grid)
+{
+    const unsigned per_xcd = (grid + 7u) / 8u;
+    const unsigned block = (unsigned)(s % per_xcd) * 8u + (unsigned)(s / per_xcd);
+    return block < grid;
+}
+
 __device__ __forceinline__ void write_partial(double ss, int bad, StatPartial *__restrict__ partials)
 {
-    __shared__ double wave_ss[kFlatThreads / 64];
-    __shared__ int wave_bad[kFlatThreads / 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     ss = wave_sum_f64(ss);
     bad = __any(bad) ? 1 : 0;
-    if (lane == 0) { wave_ss[wave] = ss; wave_bad[wave] = bad; }
-    __syncthreads();
     if (threadIdx.x == 0) {
-        double t = 0.0;
-        int b = 0;
-        for (int w = 0; w < kFlatThreads / 64; ++w) { t += wave_ss[w]; b |= wave_bad[w]; }
-        partials[blockIdx.x].sum_squares = t;
-        partials[blockIdx.x].nonfinite = b;
+        const unsigned per_xcd = (gridDim.x + 7u) / 8u;
+        const unsigned slot = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+        partials[slot].sum_squares = ss;
+        partials[slot].nonfinite = bad;
     }
 }
 
@@ -317,101 +320,142 @@ __device__ __forceinline__ void write_partial(double ss, int bad, StatPartial *_
 // Gradient compression.  SRC: where a value comes from (dense g at idx, gc16, gc); OUT: what is
 // written (fp32 unscaled gc, fp16 gc16 with optional accumulation, nothing).  When `partials` is
 // given, the sum of squares and the non-finite flag of the unscaled values are reduced as well.
-// Launched with one workgroup per chunk record normally.  When statistics are reduced the grid is
-// a fixed kStatGrid workgroups that stride over the records, so that the wave reduction and the
-// partial's store are paid once per workgroup and the number (and order) of partials is fixed.
-template <int OUT, bool STRIDED>
+// One workgroup (a single wave) per chunk record; with statistics it leaves one partial, which
+// stats_reduce_kernel / stats_finalize_kernel sum afterwards (a grid of padded slots: see
+// launch_gather).
+template <int OUT>
 __global__ void __launch_bounds__(kFlatThreads)
 gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, StatPartial *__restrict__ partials)
 {
     double ss = 0.0;
     int bad = 0;
     static_assert(kChunk == 4 * kFlatThreads, "one float4 per thread and chunk record");
-    const int64_t rec_end = STRIDED ? ls.wgs : (int64_t)blockIdx.x + 1;     // straight-line code when not strided
-    const int64_t rec_step = STRIDED ? (int64_t)gridDim.x : 1;
-    for (int64_t rec = blockIdx.x; rec < rec_end; rec += rec_step) {
-        samo_layer L;
-        int64_t chunk;
-        pick_work_at(ls, rec, &L, &chunk);
-        const int64_t nnz = L.nnz;
-        const bool identity = (L.idx == nullptr);             // dense layer: position i is element i
-        const int64_t i = chunk * kChunk + (int64_t)threadIdx.x * 4;
-        if (i >= nnz) continue;
-        const int cnt = (nnz - i < 4) ? (int)(nnz - i) : 4;
-        uint16_t hb[4] = {0, 0, 0, 0};
-        float fv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (src == kGradC32) {
-            if (cnt == 4) {
-                const float4 q = *reinterpret_cast<const float4 *>(L.gc + i);
-                fv[0] = q.x; fv[1] = q.y; fv[2] = q.z; fv[3] = q.w;
-            } else {
-                for (int e = 0; e < cnt; ++e) fv[e] = L.gc[i + e];
-            }
-        } else if (src == kGradC16 || identity) {
-            const uint16_t *S = (src == kGradC16) ? L.gc16 : L.g;
-            if (cnt == 4) {
-                const uint2 q = *reinterpret_cast<const uint2 *>(S + i);
-                hb[0] = (uint16_t)q.x; hb[1] = (uint16_t)(q.x >> 16); hb[2] = (uint16_t)q.y; hb[3] = (uint16_t)(q.y >> 16);
-            } else {
-                for (int e = 0; e < cnt; ++e) hb[e] = S[i + e];
-            }
+    samo_layer L;
+    int64_t chunk;
+    pick_work(ls, &L, &chunk);
+    const int64_t nnz = L.nnz;
+    const bool identity = (L.idx == nullptr);             // dense layer: position i is element i
+    const int64_t i = chunk * kChunk + (int64_t)threadIdx.x * 4;
+    const int cnt = (nnz - i >= 4) ? 4 : (nnz - i > 0 ? (int)(nnz - i) : 0);
+    uint16_t hb[4] = {0, 0, 0, 0};
+    float fv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (src == kGradC32) {
+        if (cnt == 4) {
+            const float4 q = *reinterpret_cast<const float4 *>(L.gc + i);
+            fv[0] = q.x; fv[1] = q.y; fv[2] = q.z; fv[3] = q.w;
         } else {
-            if (cnt == 4) {
-                const int4 j = *reinterpret_cast<const int4 *>(L.idx + i);
-                hb[0] = L.g[j.x]; hb[1] = L.g[j.y]; hb[2] = L.g[j.z]; hb[3] = L.g[j.w];
-            } else {
-                for (int e = 0; e < cnt; ++e) hb[e] = L.g[L.idx[i + e]];
-            }
+            for (int e = 0; e < cnt; ++e) fv[e] = L.gc[i + e];
         }
-        if (OUT == kOutF16) {
-            if (accumulate) {                                  // one correctly rounded half addition
-                uint16_t old[4] = {0, 0, 0, 0};
-                if (cnt == 4) {
-                    const uint2 q = *reinterpret_cast<const uint2 *>(L.gc16 + i);
-                    old[0] = (uint16_t)q.x; old[1] = (uint16_t)(q.x >> 16); old[2] = (uint16_t)q.y; old[3] = (uint16_t)(q.y >> 16);
-                } else {
-                    for (int e = 0; e < cnt; ++e) old[e] = L.gc16[i + e];
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const _Float16 sum = __builtin_bit_cast(_Float16, old[e]) + __builtin_bit_cast(_Float16, hb[e]);
-                    hb[e] = __builtin_bit_cast(uint16_t, sum);
-                }
-            }
-            if (cnt == 4) {
-                *reinterpret_cast<uint2 *>(L.gc16 + i) =
-                    make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16), (uint32_t)hb[2] | ((uint32_t)hb[3] << 16));
-            } else {
-                for (int e = 0; e < cnt; ++e) L.gc16[i + e] = hb[e];
-            }
-        }
-        if (src != kGradC32) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) fv[e] = half_bits_to_float(hb[e]) * inv_scale;
+    } else if (src == kGradC16 || identity) {
+        const uint16_t *S = (src == kGradC16) ? L.gc16 : L.g;
+        if (cnt == 4) {
+            const uint2 q = *reinterpret_cast<const uint2 *>(S + i);
+            hb[0] = (uint16_t)q.x; hb[1] = (uint16_t)(q.x >> 16); hb[2] = (uint16_t)q.y; hb[3] = (uint16_t)(q.y >> 16);
         } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) fv[e] = fv[e] * inv_scale;
+            for (int e = 0; e < cnt; ++e) hb[e] = S[i + e];
         }
-        if (OUT == kOutF32) {
-            if (cnt == 4) store_f4_stream(L.gc + i, make_float4(fv[0], fv[1], fv[2], fv[3]));
-            else for (int e = 0; e < cnt; ++e) L.gc[i + e] = fv[e];
+    } else {
+        if (cnt == 4) {
+            const int4 j = *reinterpret_cast<const int4 *>(L.idx + i);
+            hb[0] = L.g[j.x]; hb[1] = L.g[j.y]; hb[2] = L.g[j.z]; hb[3] = L.g[j.w];
+        } else {
+            for (int e = 0; e < cnt; ++e) hb[e] = L.g[L.idx[i + e]];
         }
-        if (partials) {
-            for (int e = 0; e < cnt; ++e) {
-                ss += (double)fv[e] * (double)fv[e];
-                bad |= is_nonfinite(fv[e]) ? 1 : 0;
+    }
+    if (OUT == kOutF16) {
+        if (accumulate) {                                  // one correctly rounded half addition
+            uint16_t old[4] = {0, 0, 0, 0};
+            if (cnt == 4) {
+                const uint2 q = *reinterpret_cast<const uint2 *>(L.gc16 + i);
+                old[0] = (uint16_t)q.x; old[1] = (uint16_t)(q.x >> 16); old[2] = (uint16_t)q.y; old[3] = (uint16_t)(q.y >> 16);
+            } else {
+                for (int e = 0; e < cnt; ++e) old[e] = L.gc16[i + e];
             }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const _Float16 sum = __builtin_bit_cast(_Float16, old[e]) + __builtin_bit_cast(_Float16, hb[e]);
+                hb[e] = __builtin_bit_cast(uint16_t, sum);
+            }
+        }
+        if (cnt == 4) {
+            *reinterpret_cast<uint2 *>(L.gc16 + i) =
+                make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16), (uint32_t)hb[2] | ((uint32_t)hb[3] << 16));
+        } else {
+            for (int e = 0; e < cnt; ++e) L.gc16[i + e] = hb[e];
+        }
+    }
+    if (src != kGradC32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) fv[e] = half_bits_to_float(hb[e]) * inv_scale;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) fv[e] = fv[e] * inv_scale;
+    }
+    if (OUT == kOutF32) {
+        if (cnt == 4) store_f4_stream(L.gc + i, make_float4(fv[0], fv[1], fv[2], fv[3]));
+        else for (int e = 0; e < cnt; ++e) L.gc[i + e] = fv[e];
+    }
+    if (partials) {
+        for (int e = 0; e < cnt; ++e) {
+            ss += (double)fv[e] * (double)fv[e];
+            bad |= is_nonfinite(fv[e]) ? 1 : 0;
         }
     }
     if (partials) write_partial(ss, bad, partials);
 }
 
-// Sums the per-workgroup partials in a fixed order: thread t takes partials t, t + 1024, ...,
-// then one fixed-shape tree over the 1024 threads.
+// First level of the reduction: workgroup b sums the contiguous slice [b * per, (b + 1) * per) of
+// the partials into out[b]; thread t of it takes elements t, t + 256, ... of the slice, then a
+// fixed tree.  Every order is fixed by (count, per) alone.
+constexpr int kReduceThreads = 256;
+
+__global__ void __launch_bounds__(kReduceThreads)
+stats_reduce_kernel(const StatPartial *__restrict__ partials, int64_t count, unsigned gather_grid, int64_t per,
+                    StatPartial *__restrict__ out)
+{
+    __shared__ double sh_ss[kReduceThreads / 64];
+    __shared__ int sh_bad[kReduceThreads / 64];
+    const int64_t lo = (int64_t)blockIdx.x * per;
+    const int64_t hi = (lo + per < count) ? lo + per : count;
+    double ss = 0.0;
+    int bad = 0;
+    constexpr int kAhead = 4;                 // loads in flight per thread; the additions keep their order
+    for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += (int64_t)kAhead * kReduceThreads) {
+        StatPartial part[kAhead];
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int64_t i = i0 + (int64_t)a * kReduceThreads;
+            part[a].sum_squares = 0.0;
+            part[a].nonfinite = 0;
+            if (i < hi && partial_slot_used(i, gather_grid)) part[a] = partials[i];
+        }
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            ss += part[a].sum_squares;
+            bad |= part[a].nonfinite != 0;
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    ss = wave_sum_f64(ss);
+    bad = __any(bad) ? 1 : 0;
+    if (lane == 0) { sh_ss[wave] = ss; sh_bad[wave] = bad; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        int b = 0;
+        for (int w = 0; w < kReduceThreads / 64; ++w) { t += sh_ss[w]; b |= sh_bad[w]; }
+        out[blockIdx.x].sum_squares = t;
+        out[blockIdx.x].nonfinite = b;
+    }
+}
+
+// Last level: sums up to a few thousand partials in a fixed order: thread t takes partials
+// t, t + 1024, ..., then one fixed-shape tree over the 1024 threads.
 constexpr int kFinalizeThreads = 1024;
 
 __global__ void __launch_bounds__(kFinalizeThreads)
-stats_finalize_kernel(const StatPartial *__restrict__ partials, int64_t count, samo_grad_stats *__restrict__ out)
+stats_finalize_kernel(const StatPartial *__restrict__ partials, int64_t count, unsigned gather_grid,
+                      samo_grad_stats *__restrict__ out)
 {
     __shared__ double sh_ss[kFinalizeThreads / 64];
     __shared__ int sh_bad[kFinalizeThreads / 64];
@@ -425,7 +469,8 @@ stats_finalize_kernel(const StatPartial *__restrict__ partials, int64_t count, s
             const int64_t i = i0 + (int64_t)a * kFinalizeThreads;
             part[a].sum_squares = 0.0;
             part[a].nonfinite = 0;
-            if (i < count) part[a] = partials[i];
+            // gather_grid != 0: the partials come straight from a gather launch of that many workgroups
+            if (i < count && (gather_grid == 0 || partial_slot_used(i, gather_grid))) part[a] = partials[i];
         }
 #pragma unroll
         for (int a = 0; a < kAhead; ++a) {
@@ -546,12 +591,16 @@ static int occ_flat_gather(int src, float keep, bool with_stats)
 {
     static const int forced = env_int("SAMO_OCC_FLAT_GATHER", -1);
     static const int forced_stats = env_int("SAMO_OCC_FLAT_STATS", -1);
-    if (with_stats) return forced_stats >= 0 ? forced_stats : 0;   // strided launch: uncapped is best
-    if (forced >= 0) return forced;
-    if (src != kGradDense) return 12;
+    if (with_stats && forced_stats >= 0) return forced_stats;
+    if (!with_stats && forced >= 0) return forced;
+    if (src != kGradDense) return with_stats ? 20 : 12;
     const float per_wave = 1024.f + 512.f / (keep > 0.01f ? keep : 0.01f);
-    int t = (int)(75.f * 1024.f / per_wave + 0.5f);
-    return t < 11 ? 11 : (t > 32 ? 0 : t);
+    float t = 75.f * 1024.f / per_wave;
+    if (t < 13.f) t = 13.f;
+    // the statistics add an arithmetic tail during which a wave has no memory traffic in flight:
+    // more waves have to be resident for the same traffic in flight
+    if (with_stats) t *= 1.6f;
+    return t > 32.f ? 0 : (int)(t + 0.5f);
 }
 
 static int occ_flat_step()
@@ -587,18 +636,11 @@ hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale,
                          StatPartial *partials, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    const dim3 block(kFlatThreads);
+    const dim3 grid((unsigned)ls.wgs), block(kFlatThreads);
     const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 64);
-    const int64_t wgs = partials ? (ls.wgs < kStatGrid ? ls.wgs : kStatGrid) : ls.wgs;
-    const dim3 grid((unsigned)wgs);
-    if (partials) {
-        if (out == kOutF32) gather_kernel<kOutF32, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
-        else if (out == kOutF16) gather_kernel<kOutF16, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
-        else gather_kernel<kOutNone, true><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
-    } else {
-        if (out == kOutF32) gather_kernel<kOutF32, false><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
-        else if (out == kOutF16) gather_kernel<kOutF16, false><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, nullptr);
-    }
+    if (out == kOutF32) gather_kernel<kOutF32><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
+    else if (out == kOutF16) gather_kernel<kOutF16><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
+    else gather_kernel<kOutNone><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     return hipGetLastError();
 }
 
@@ -612,9 +654,26 @@ hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const G
     return hipGetLastError();
 }
 
-hipError_t launch_stats_finalize(const StatPartial *partials, int64_t count, samo_grad_stats *out, hipStream_t s)
+int64_t stats_workspace_partials(int64_t gather_wgs)
 {
-    stats_finalize_kernel<<<dim3(1), dim3(kFinalizeThreads), 0, s>>>(partials, count, out);
+    return ceil_div(gather_wgs, 8) * 8 + kStatReduceGrid;
+}
+
+// Sums the partials a gather launch of `gather_wgs` workgroups left in `partials` (which must hold
+// stats_workspace_partials(gather_wgs) entries) into *out: one level when there are few, else a
+// first level of kStatReduceGrid workgroups that writes behind the partials.
+hipError_t launch_stats_finalize(StatPartial *partials, int64_t gather_wgs, samo_grad_stats *out, hipStream_t s)
+{
+    const int64_t slots = ceil_div(gather_wgs, 8) * 8;
+    if (slots <= 4 * kStatReduceGrid) {
+        stats_finalize_kernel<<<dim3(1), dim3(kFinalizeThreads), 0, s>>>(partials, slots, (unsigned)gather_wgs, out);
+    } else {
+        const int64_t per = ceil_div(slots, (int64_t)kStatReduceGrid);
+        const int64_t grid = ceil_div(slots, per);
+        stats_reduce_kernel<<<dim3((unsigned)grid), dim3(kReduceThreads), 0, s>>>(partials, slots, (unsigned)gather_wgs,
+                                                                                 per, partials + slots);
+        stats_finalize_kernel<<<dim3(1), dim3(kFinalizeThreads), 0, s>>>(partials + slots, grid, 0u, out);
+    }
     return hipGetLastError();
 }
 

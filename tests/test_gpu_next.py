@@ -168,6 +168,41 @@ def test_dp_split_batched_with_statistics():
             assert np.array_equal(host_bits(d.w), oracle.decompress(got_p, h.idx, h.n))
 
 
+@pytest.mark.parametrize("n,keep", [(11_000_003, 0.25), (9_000_001, 0.13)])
+def test_statistics_of_many_chunks(n, keep):
+    """More chunk records than one reduction level takes, with a count that is not a multiple of
+    eight (slots of the partials array stay unused), and a non-finite value in the last chunk."""
+    mask = si.bernoulli_mask(n, keep, 4242)
+    kept = np.flatnonzero(mask)
+    chunks = -(-kept.shape[0] // 256)
+    target = (chunks - 8) // 8 * 8 + 3                       # a count of chunk records that is 3 mod 8
+    mask[kept[target * 256 - 100:]] = 0                      # ... the last of them ragged
+    h = HostLayer(n, mask, si.weights(n, 4242), 4242)
+    assert h.idx.shape[0] > 4 * 1024 * 256 and (-(-h.idx.shape[0] // 256)) % 8 == 3
+    d = DevLayer(h, with_gc=True, with_gc16=True)
+    plan = samo.Plan([d.layer()])
+    stats = samo.GradStats(plan)
+    g = h.grads(1)
+    d.set_grads(g)
+    gc = oracle.gather(g, h.idx, INV)
+    ref_ss = oracle.sum_squares(gc)
+    plan.samo_gather_fp16_batched(False, INV, stats)
+    ss, bad = stats.read()
+    # two fp64 summations of the same non-negative terms in different orders: each is within
+    # (terms - 1) * 2^-53 relative of the exact sum
+    assert abs(ss - ref_ss) <= 2 * gc.shape[0] * 2.0 ** -53 * ref_ss and not bad
+    assert np.array_equal(host_bits(d.gc16), oracle.compress_f16(g, h.idx))
+    again = samo.GradStats(plan)
+    plan.samo_gather_batched(INV, again)
+    assert again.read() == (ss, bad)
+    assert np.array_equal(d.gc.cpu().numpy(), gc)
+    g2 = g.copy()
+    g2[h.idx[-1]] = 0x7C00                                   # +inf at the last kept position
+    d.set_grads(g2)
+    plan.samo_grad_stats_batched(0, INV, stats)
+    assert stats.read()[1] is True
+
+
 def test_micro_batch_accumulation_batched():
     hosts, devs, plan = _model()
     refs = [None] * len(hosts)
