@@ -28,9 +28,10 @@
  * Conventions common to every entry point
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller
  *     owns every buffer.  The library allocates device memory only inside
- *     samo_plan_create (one small table, freed by samo_plan_destroy).
+ *     samo_plan_create (small tables, freed by samo_plan_destroy).
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
- *     Calls only enqueue work and return; there is no hidden synchronisation.
+ *     Calls only enqueue work and return; there is no hidden synchronisation
+ *     (samo_plan_create, a set-up call without a stream argument, excepted).
  *     Outputs (including *d_nnz) are valid once the stream reaches that point.
  *   - Arguments are validated on the host BEFORE anything is enqueued.  On a
  *     negative status nothing was launched and no output was touched.
@@ -204,9 +205,14 @@ samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, c
 /* ---------------------------------------------------------------- whole-model (batched) forms
  * One launch covers every layer, so small layers do not pay a launch and a
  * tail each.  A plan is built once per pruning from a HOST array of layer
- * descriptors holding DEVICE pointers; it copies the descriptors and its
- * workgroup-to-layer maps to the device.  The plan does not own the layers'
- * buffers, which must stay valid while the plan is used.  A descriptor with
+ * descriptors holding DEVICE pointers; it copies the descriptors to the device
+ * and builds its workgroup-to-work maps there.  The maps split every pruned
+ * layer into runs of segments that move about equal numbers of bytes, which
+ * they read off seg_ptr: the index of every layer (seg_ptr's contents) must be
+ * final when the plan is created, and a plan is rebuilt after re-pruning.
+ * samo_plan_create synchronises the device (before reading seg_ptr and before it
+ * returns); it is the only entry point that does.  The plan does not own the
+ * layers' buffers, which must stay valid while the plan is used.  A descriptor with
  * idx == NULL (then seg_ptr == NULL and nnz == n) is a dense layer.  Buffers an
  * entry point does not use may be NULL in the descriptor (e.g. gc for the
  * fused step); an entry point that needs a missing one returns SAMO_ERR_PLAN. */

@@ -28,6 +28,15 @@ inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 inline samo_status hip_status(hipError_t e) { return e == hipSuccess ? SAMO_OK : SAMO_ERR_HIP; }
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Tile records of a layer in a plan: one per segment of an unpruned layer; for a pruned layer as
+// many as its total weight holds tiles of weight kTileCost.
+int64_t tile_records(const samo_layer &L)
+{
+    const int64_t nseg = ceil_div(L.n, kSeg);
+    if (nseg == 0 || !L.seg_ptr) return nseg;
+    return ceil_div(kSegCost * nseg + kNnzCost * L.nnz, kTileCost);
+}
+
 samo_status check_sizes(int64_t n, int64_t nnz)
 {
     if (n < 0 || n > kMaxN) return SAMO_ERR_SIZE;
@@ -183,7 +192,18 @@ LaunchSet single(const samo_layer &L, int64_t wgs)
     ls.layers = nullptr;
     ls.recs = nullptr;
     ls.wgs = wgs;
+    ls.segs_per_tile = 1;
     ls.keep = L.n > 0 ? (float)((double)L.nnz / (double)L.n) : 1.f;
+    return ls;
+}
+
+// Single-layer tile launch: every workgroup owns the same number of segments, chosen from the
+// layer's average density (the per-region balance of a plan needs seg_ptr's contents).
+LaunchSet single_tiles(const samo_layer &L)
+{
+    const int segs = single_layer_tile_segs(L.n, L.nnz, L.seg_ptr == nullptr);
+    LaunchSet ls = single(L, ceil_div(ceil_div(L.n, kSeg), segs));
+    ls.segs_per_tile = segs;
     return ls;
 }
 
@@ -252,7 +272,7 @@ samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_
                     nullptr};
     OptK k;
     std::memset(&k, 0, sizeof(k));
-    return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, single(L, ceil_div(n, kTile)), 1.f, k,
+    return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, single_tiles(L), 1.f, k,
                                   kNoGuard, as_stream(stream)));
 }
 
@@ -316,7 +336,7 @@ samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const
     OptK k;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
     samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr, nullptr};
-    return hip_status(launch_tile(kModeStep, kGradDense, kOptAdam, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptAdam, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
 
@@ -329,7 +349,7 @@ samo_status samo_adam_expand_step(const uint16_t *d_gc16, uint16_t *d_w, int64_t
     OptK k;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
     samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, nullptr, nullptr, const_cast<uint16_t *>(d_gc16)};
-    return hip_status(launch_tile(kModeStep, kGradC16, kOptAdam, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+    return hip_status(launch_tile(kModeStep, kGradC16, kOptAdam, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
 
@@ -344,7 +364,7 @@ samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, c
     OptK k;
     if (samo_status s = make_sgd(h_cfg, &k)) return s;
     samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_buf, nullptr, d_w, d_g, nullptr, nullptr};
-    return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, single(L, ceil_div(n, kTile)), inv_loss_scale, k,
+    return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
 
@@ -380,7 +400,7 @@ samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, sam
         }
         plan->n_total += L.n;
         plan->nnz_total += L.nnz;
-        plan->ntiles += ceil_div(L.n, kTile);
+        plan->ntiles += tile_records(L);
         plan->nchunks += ceil_div(L.nnz, kChunk);
     }
     if (st == SAMO_OK && (plan->ntiles > kMaxN || plan->nchunks > kMaxN)) st = SAMO_ERR_SIZE;
@@ -390,23 +410,37 @@ samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, sam
     }
     plan->layers.assign(h_layers, h_layers + num_layers);
 
-    std::vector<WgRec> tiles((size_t)plan->ntiles), chunks((size_t)plan->nchunks);
-    size_t ti = 0, ci = 0;
+    std::vector<WgRec> chunks((size_t)plan->nchunks);
+    std::vector<int64_t> tile_start((size_t)num_layers + 1, 0);
+    size_t ci = 0;
     for (int32_t l = 0; l < num_layers; ++l) {
-        const int64_t nt = ceil_div(h_layers[l].n, kTile), nc = ceil_div(h_layers[l].nnz, kChunk);
-        for (int64_t t = 0; t < nt; ++t) tiles[ti++] = WgRec{l, (int32_t)t};
-        for (int64_t c = 0; c < nc; ++c) chunks[ci++] = WgRec{l, (int32_t)c};
+        const int64_t nc = ceil_div(h_layers[l].nnz, kChunk);
+        for (int64_t c = 0; c < nc; ++c) chunks[ci++] = WgRec{l, (uint32_t)c};
+        tile_start[(size_t)l + 1] = tile_start[(size_t)l] + tile_records(h_layers[l]);
     }
 
-    hipError_t e = hipSuccess;
+    // Everything the layers' seg_ptr tables depend on must have finished: the tile records are
+    // computed from their contents.
+    hipError_t e = plan->ntiles > 0 ? hipDeviceSynchronize() : hipSuccess;
     auto upload = [&e](const void *src, size_t bytes, void **dst) {
         if (e != hipSuccess || bytes == 0) return;
         e = hipMalloc(dst, bytes);
         if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
     };
     upload(plan->layers.data(), plan->layers.size() * sizeof(samo_layer), reinterpret_cast<void **>(&plan->d_layers));
-    upload(tiles.data(), tiles.size() * sizeof(WgRec), reinterpret_cast<void **>(&plan->d_tiles));
     upload(chunks.data(), chunks.size() * sizeof(WgRec), reinterpret_cast<void **>(&plan->d_chunks));
+    if (e == hipSuccess && plan->ntiles > 0) {
+        int64_t *d_tile_start = nullptr;
+        upload(tile_start.data(), tile_start.size() * sizeof(int64_t), reinterpret_cast<void **>(&d_tile_start));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&plan->d_tiles), (size_t)plan->ntiles * sizeof(WgRec));
+        if (e == hipSuccess)
+            e = launch_build_tile_recs(plan->d_layers, d_tile_start, num_layers, plan->ntiles, plan->d_tiles, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (d_tile_start) {
+            const hipError_t e2 = hipFree(d_tile_start);
+            if (e == hipSuccess) e = e2;
+        }
+    }
     if (e != hipSuccess) {
         samo_plan_destroy(plan);
         return SAMO_ERR_HIP;
@@ -452,6 +486,7 @@ LaunchSet tiles_of(const samo_plan *plan)
     ls.layers = plan->d_layers;
     ls.recs = plan->d_tiles;
     ls.wgs = plan->ntiles;
+    ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
     return ls;
 }
@@ -463,6 +498,7 @@ LaunchSet chunks_of(const samo_plan *plan)
     ls.layers = plan->d_layers;
     ls.recs = plan->d_chunks;
     ls.wgs = plan->nchunks;
+    ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
     return ls;
 }

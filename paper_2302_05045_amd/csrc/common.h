@@ -8,22 +8,32 @@
 
 namespace samo {
 
-// Launch shapes, chosen by measurement on MI355X (GPT-3 2.7B shape, 90 % pruned): 16 dense
-// elements per thread in the tile kernels — (2048,128), (4096,256) and (8192,512) are within
-// 2 % of each other, 8 or 32 per thread lose 10-15 % — and one 64-lane wave per workgroup with
-// one float4 per array in the flat kernels.
+// Launch shapes, chosen by measurement on MI355X.  A tile workgroup (256 threads) owns a run of
+// whole segments of a layer of about equal weight kTileCost, where a segment weighs kSegCost plus
+// kNnzCost per kept element: at 90-95 % pruning that is about 4 segments (4096 dense elements, 16
+// per thread — 8 or 32 per thread lose 10-15 %), 3 at 80 %, 2 at 50 %, 5-6 where nothing is kept,
+// one segment per workgroup in an unpruned layer.  The weights follow the fused step's traffic
+// (4 bytes per dense element, 28 per kept one) with the dense side weighted up: swept over
+// (4096..16384, 8..28, 20K..64K) on the GPT shapes, this choice is within 1 % of the best at 80, 90
+// and 95 % uniform pruning and 6 % ahead of fixed 4096-element tiles on row-clustered masks.  Even
+// weights per workgroup keep the traffic in flight per compute unit steady whatever the local
+// density (clustered masks, mixed pruned and dense layers), so one occupancy target fits all.
+// Flat kernels: one 64-lane wave per workgroup with one float4 per array.
 constexpr int kThreads = 256;           // index kernels: 4 wavefronts per workgroup
 constexpr int kTileThreads = 256;       // tile kernels
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
-constexpr int kTile = 4096;             // dense elements owned by one workgroup (8 KiB of fp16 in LDS)
-constexpr int kSegsPerTile = kTile / kSeg;
+constexpr int64_t kTileCost = 32768;    // target weight of one tile workgroup
+constexpr int64_t kSegCost = 6144;      // weight of a segment's dense side (fp16 gradient lines read, fp16 weights written)
+constexpr int64_t kNnzCost = 24;        // weight of a kept element (idx, p, m, v read; p, m, v written)
+constexpr int kMaxTileSegs = (int)((kTileCost + kSegCost - 1) / kSegCost);   // reached where nothing is kept
+constexpr int kMaxTile = kMaxTileSegs * kSeg;   // dense elements of the largest tile (fp16 image in LDS)
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
 constexpr int kStatReduceGrid = 1024;    // workgroups of the first level of the gradient-statistics reduction
 constexpr int kTileUnroll = 4;          // compressed elements in flight per thread in the tile kernels
 
-static_assert(kTile % kSeg == 0, "a tile is a whole number of segments");
-static_assert(kTile % (8 * kTileThreads) == 0, "a tile is written out as whole 16-byte vectors per thread");
+static_assert(kMaxTileSegs >= 1 && kMaxTileSegs < 256, "the segment count of a tile record is an 8-bit field");
+static_assert(kSeg % 8 == 0, "a tile is written out as whole 16-byte vectors");
 static_assert(kChunk % (4 * kFlatThreads) == 0, "a chunk is whole float4 vectors per thread");
 
 // Optimizer constants prepared on the host in double precision, rounded once to fp32.
@@ -49,11 +59,14 @@ enum { kGradDense = 0, kGradC16 = 1, kGradC32 = 2 };   // where a step reads its
 enum { kOptAdam = 0, kOptSgd = 1 };
 enum { kOutF32 = 0, kOutF16 = 1, kOutNone = 2 };        // what the flat gather kernel writes
 
-// Workgroup -> (layer, local tile or chunk) record of the batched launches.
+// Workgroup -> work record of the batched launches.  Chunk records (flat kernels): local = chunk
+// index within the layer.  Tile records: local = first segment | number of segments << 24 (a
+// layer has at most 2^21 segments).
 struct WgRec {
     int32_t layer;
-    int32_t local;
+    uint32_t local;
 };
+constexpr int kRecSegShift = 24;
 
 // One (sum of squares, non-finite flag) partial per workgroup of a flat launch.
 struct StatPartial {
@@ -91,8 +104,14 @@ struct LaunchSet {
     const samo_layer *layers;
     const WgRec *recs;
     int64_t wgs;
-    float keep;   // kept fraction nnz / n of the work (plan average); steers the occupancy target
+    int segs_per_tile;   // single-layer tile launches: workgroup b owns segments [b * this, (b + 1) * this)
+    float keep;          // kept fraction nnz / n of the work (plan average); steers the flat kernels' occupancy target
 };
+// Segments per tile of a single-layer launch, from the layer's average density.
+int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense);
+// Fills recs[rec_start[l] + k] for every layer l of a plan (device tables; reads the layers' seg_ptr).
+hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_rec_start, int num_layers,
+                                  int64_t total, WgRec *d_recs, hipStream_t s);
 hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
                        const GuardK &guard, hipStream_t s);
 hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale, int accumulate,

@@ -1,7 +1,8 @@
 // Expansion, gradient compression, optimizers on the compressed state and the fused optimizer
 // phase (Section III-C of the paper) as HBM-streaming kernels for gfx950.
 //
-// Dense side (fp16 w and g, N elements): a workgroup owns one aligned tile of kTile elements.
+// Dense side (fp16 w and g, N elements): a workgroup owns a tile, a run of whole 1024-element
+// segments of one layer chosen so that every workgroup moves about the same number of bytes.
 // The new fp16 weights of the tile are assembled in LDS — zero filled, then the kept values
 // dropped in at their tile-relative positions — and leave as whole 16-byte non-temporal stores,
 // so HBM never sees a partial-line write and the explicit zeros of the pruned positions cost no
@@ -45,6 +46,12 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float x)
 __device__ __forceinline__ void store16_stream(void *dst, const uint4 &v)
 {
     __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(dst));
+}
+
+__device__ __forceinline__ void store8_stream(void *dst, const uint2 &v)
+{
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store((u32x2){v.x, v.y}, reinterpret_cast<u32x2 *>(dst));
 }
 
 __device__ __forceinline__ void store_f4_stream(float *dst, const float4 &v)
@@ -109,98 +116,95 @@ __device__ __forceinline__ void pick_work(const LaunchSet &ls, samo_layer *L, in
     }
 }
 
+// The tile of this workgroup: segments [*s0, *s0 + *nsegs) of *L; *nsegs may be 0 (nothing to do).
+__device__ __forceinline__ void pick_tile(const LaunchSet &ls, samo_layer *L, int *s0, int *nsegs)
+{
+    if (ls.layers) {
+        const WgRec r = ls.recs[blockIdx.x];
+        *L = ls.layers[r.layer];
+        *s0 = (int)(r.local & ((1u << kRecSegShift) - 1u));
+        *nsegs = (int)(r.local >> kRecSegShift);
+    } else {
+        *L = ls.one;
+        const int64_t nseg = (ls.one.n + kSeg - 1) / kSeg;
+        const int64_t first = (int64_t)blockIdx.x * ls.segs_per_tile;
+        *s0 = (int)first;
+        *nsegs = (nseg - first < ls.segs_per_tile) ? (int)(nseg - first) : ls.segs_per_tile;
+    }
+}
+
 // ------------------------------------------------------------------ tile kernels
-// Dense (unpruned) layer: identity index, plain elementwise pass over the tile.
+// Dense (unpruned) layer: identity index, plain elementwise pass over the tile (one segment, so
+// one trip).  A thread takes four consecutive elements — one 16-byte vector of each fp32 array,
+// one 8-byte vector of each fp16 array — so every wave-level access is one contiguous run.
 template <int MODE, int GSRC, int OPT>
 __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, int len, float inv_scale, float coef,
                                            const OptK &k)
 {
     const int tid = threadIdx.x;
-    float *__restrict__ P = L.p + base;
-    float *__restrict__ M = L.m + base;
-    float *__restrict__ V = L.v + base;
-    uint16_t *__restrict__ W = L.w + base;
-    const int nvec = len / 8;
+    float4 *__restrict__ P = reinterpret_cast<float4 *>(L.p + base);
+    float4 *__restrict__ M = reinterpret_cast<float4 *>(L.m + base);
+    float4 *__restrict__ V = reinterpret_cast<float4 *>(L.v + base);
+    uint2 *__restrict__ W = reinterpret_cast<uint2 *>(L.w + base);
+    const int nvec = len / 4;
     for (int o = tid; o < nvec; o += kTileThreads) {
-        const float4 p0 = reinterpret_cast<const float4 *>(P)[2 * o];
-        const float4 p1 = reinterpret_cast<const float4 *>(P)[2 * o + 1];
-        float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        float4 p = P[o];
         if (MODE == kModeStep) {
-            float gv[8];
+            float4 m = M[o];
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (OPT == kOptAdam) v = V[o];
+            float4 g;
             if (GSRC == kGradC32) {
-                const float4 g0 = reinterpret_cast<const float4 *>(L.gc + base)[2 * o];
-                const float4 g1 = reinterpret_cast<const float4 *>(L.gc + base)[2 * o + 1];
-                const float t[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) gv[e] = t[e] * coef;
+                g = reinterpret_cast<const float4 *>(L.gc + base)[o];
+                g.x *= coef; g.y *= coef; g.z *= coef; g.w *= coef;
             } else {
-                const uint16_t *src = (GSRC == kGradDense) ? L.g : L.gc16;
-                const uint4 gq = reinterpret_cast<const uint4 *>(src + base)[o];
-                const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    gv[e] = (half_bits_to_float((uint16_t)(gw[e >> 1] >> (16 * (e & 1)))) * inv_scale) * coef;
+                const uint2 gq = reinterpret_cast<const uint2 *>((GSRC == kGradDense ? L.g : L.gc16) + base)[o];
+                g.x = (half_bits_to_float((uint16_t)gq.x) * inv_scale) * coef;
+                g.y = (half_bits_to_float((uint16_t)(gq.x >> 16)) * inv_scale) * coef;
+                g.z = (half_bits_to_float((uint16_t)gq.y) * inv_scale) * coef;
+                g.w = (half_bits_to_float((uint16_t)(gq.y >> 16)) * inv_scale) * coef;
             }
-            const float4 m0 = reinterpret_cast<const float4 *>(M)[2 * o];
-            const float4 m1 = reinterpret_cast<const float4 *>(M)[2 * o + 1];
-            float mv[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-            float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if (OPT == kOptAdam) {
-                const float4 v0 = reinterpret_cast<const float4 *>(V)[2 * o];
-                const float4 v1 = reinterpret_cast<const float4 *>(V)[2 * o + 1];
-                vv[0] = v0.x; vv[1] = v0.y; vv[2] = v0.z; vv[3] = v0.w;
-                vv[4] = v1.x; vv[5] = v1.y; vv[6] = v1.z; vv[7] = v1.w;
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) opt_update<OPT>(pv[e], mv[e], vv[e], gv[e], k);
-            reinterpret_cast<float4 *>(P)[2 * o] = make_float4(pv[0], pv[1], pv[2], pv[3]);
-            reinterpret_cast<float4 *>(P)[2 * o + 1] = make_float4(pv[4], pv[5], pv[6], pv[7]);
-            reinterpret_cast<float4 *>(M)[2 * o] = make_float4(mv[0], mv[1], mv[2], mv[3]);
-            reinterpret_cast<float4 *>(M)[2 * o + 1] = make_float4(mv[4], mv[5], mv[6], mv[7]);
-            if (OPT == kOptAdam) {
-                reinterpret_cast<float4 *>(V)[2 * o] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-                reinterpret_cast<float4 *>(V)[2 * o + 1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
-            }
+            opt_update<OPT>(p.x, m.x, v.x, g.x, k);
+            opt_update<OPT>(p.y, m.y, v.y, g.y, k);
+            opt_update<OPT>(p.z, m.z, v.z, g.z, k);
+            opt_update<OPT>(p.w, m.w, v.w, g.w, k);
+            P[o] = p;
+            M[o] = m;
+            if (OPT == kOptAdam) V[o] = v;
         }
-        uint32_t hw[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            hw[q] = (uint32_t)float_to_half_bits(pv[2 * q]) | ((uint32_t)float_to_half_bits(pv[2 * q + 1]) << 16);
-        store16_stream(reinterpret_cast<uint4 *>(W) + o, make_uint4(hw[0], hw[1], hw[2], hw[3]));
+        const uint32_t lo = (uint32_t)float_to_half_bits(p.x) | ((uint32_t)float_to_half_bits(p.y) << 16);
+        const uint32_t hi = (uint32_t)float_to_half_bits(p.z) | ((uint32_t)float_to_half_bits(p.w) << 16);
+        store8_stream(W + o, make_uint2(lo, hi));
     }
-    for (int e = nvec * 8 + tid; e < len; e += kTileThreads) {      // ragged end of the layer
-        float pe = P[e];
+    for (int e = nvec * 4 + tid; e < len; e += kTileThreads) {      // ragged end of the layer
+        float pe = L.p[base + e];
         if (MODE == kModeStep) {
             float g;
             if (GSRC == kGradC32) g = L.gc[base + e] * coef;
             else g = (half_bits_to_float((GSRC == kGradDense ? L.g : L.gc16)[base + e]) * inv_scale) * coef;
-            float me = M[e], ve = (OPT == kOptAdam) ? V[e] : 0.f;
+            float me = L.m[base + e], ve = (OPT == kOptAdam) ? L.v[base + e] : 0.f;
             opt_update<OPT>(pe, me, ve, g, k);
-            P[e] = pe;
-            M[e] = me;
-            if (OPT == kOptAdam) V[e] = ve;
+            L.p[base + e] = pe;
+            L.m[base + e] = me;
+            if (OPT == kOptAdam) L.v[base + e] = ve;
         }
-        W[e] = float_to_half_bits(pe);
+        L.w[base + e] = float_to_half_bits(pe);
     }
 }
 
 template <int MODE, int GSRC, int OPT>
-__device__ __forceinline__ void sparse_tile(const samo_layer &L, int tile, int64_t base, int len, float inv_scale,
-                                            float coef, const OptK &k, uint16_t *lds_w)
+__device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nsegs, int64_t base, int len,
+                                            float inv_scale, float coef, const OptK &k, uint16_t *lds_w)
 {
     const int tid = threadIdx.x;
     uint4 *l4 = reinterpret_cast<uint4 *>(lds_w);
-#pragma unroll
-    for (int o = tid; o < kTile / 8; o += kTileThreads) l4[o] = make_uint4(0u, 0u, 0u, 0u);
+    for (int o = tid; o < (len + 7) / 8; o += kTileThreads) l4[o] = make_uint4(0u, 0u, 0u, 0u);
 
-    const int64_t nseg = (L.n + kSeg - 1) / kSeg;
-    const int64_t s0 = (int64_t)tile * kSegsPerTile;
-    const int64_t s1 = (s0 + kSegsPerTile < nseg) ? s0 + kSegsPerTile : nseg;
     const int c0 = L.seg_ptr[s0];
-    const int c1 = L.seg_ptr[s1];
+    const int c1 = L.seg_ptr[s0 + nsegs];
     __syncthreads();
 
-    // the tile's slice of the compressed arrays; at most kTile elements, so slice-relative
+    // the tile's slice of the compressed arrays; at most kMaxTile elements, so slice-relative
     // offsets fit an int even when c0 is close to 2^31
     const int cnt = c1 - c0;
     const int32_t *__restrict__ IDX = L.idx + c0;
@@ -265,20 +269,21 @@ template <int MODE, int GSRC, int OPT>
 __global__ void __launch_bounds__(kTileThreads)
 tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guard)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds_w[kTile];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_w[kMaxTile];
     bool skip;
     const float coef = guard_coef(guard, &skip);
     if (skip) return;                         // uniform: every workgroup of the launch takes it
     samo_layer L;
-    int64_t tile;
-    pick_work(ls, &L, &tile);
-    const int64_t base = tile * kTile;
+    int s0, nsegs;
+    pick_tile(ls, &L, &s0, &nsegs);
+    if (nsegs <= 0) return;                   // uniform per workgroup: a record without segments
+    const int64_t base = (int64_t)s0 * kSeg;
     const int64_t rest = L.n - base;
-    const int len = rest < kTile ? (int)rest : kTile;
+    const int len = rest < (int64_t)nsegs * kSeg ? (int)rest : nsegs * kSeg;
     if (L.seg_ptr == nullptr)                 // dense (unpruned) layer
         dense_tile<MODE, GSRC, OPT>(L, base, len, inv_scale, coef, k);
     else
-        sparse_tile<MODE, GSRC, OPT>(L, (int)tile, base, len, inv_scale, coef, k, lds_w);
+        sparse_tile<MODE, GSRC, OPT>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w);
 }
 
 // ------------------------------------------------------------------ statistics helpers
@@ -537,6 +542,52 @@ flat_step_kernel(const LaunchSet ls, const OptK k, const GuardK guard)
     }
 }
 
+// ------------------------------------------------------------------ tile records of a plan
+// Record k of a pruned layer owns the segments s whose running weight C(s) = kSegCost * s +
+// kNnzCost * seg_ptr[s] (the weight of everything before s) falls in
+// [k * kTileCost, (k + 1) * kTileCost): C is increasing, so the records partition the layer, each
+// weighs about kTileCost, and none holds more than kMaxTileSegs segments.  seg_ptr is the prefix
+// sum already, so a record's bounds are two binary searches, independent of every other record.
+// A record can be empty (a single segment heavier than kTileCost spans two buckets).  An unpruned
+// layer gets one record per segment.
+__device__ __forceinline__ int64_t first_seg_with_cost(const int32_t *__restrict__ seg_ptr, int64_t nseg, int64_t target)
+{
+    int64_t lo = 0, hi = nseg;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int64_t cost = kSegCost * mid + kNnzCost * (int64_t)seg_ptr[mid];
+        if (cost < target) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(kThreads)
+build_tile_recs_kernel(const samo_layer *__restrict__ layers, const int64_t *__restrict__ rec_start, int num_layers,
+                       int64_t total, WgRec *__restrict__ recs)
+{
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= total) return;
+    int lo = 0, hi = num_layers;                // the last layer whose first record is <= t
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (rec_start[mid] <= t) lo = mid; else hi = mid;
+    }
+    const samo_layer L = layers[lo];
+    const int64_t k = t - rec_start[lo];
+    const int64_t nrec = rec_start[lo + 1] - rec_start[lo];
+    const int64_t nseg = (L.n + kSeg - 1) / kSeg;
+    int64_t first = k, count = 1;
+    if (L.seg_ptr != nullptr) {
+        first = (k == 0) ? 0 : first_seg_with_cost(L.seg_ptr, nseg, k * kTileCost);
+        const int64_t end = (k + 1 == nrec) ? nseg : first_seg_with_cost(L.seg_ptr, nseg, (k + 1) * kTileCost);
+        count = end - first;
+        if (count < 0) count = 0;                       // only with a seg_ptr that is not a prefix sum:
+        if (count > kMaxTileSegs) count = kMaxTileSegs; // stay inside the workgroup's LDS image
+    }
+    recs[t].layer = lo;
+    recs[t].local = (uint32_t)first | ((uint32_t)count << kRecSegShift);
+}
+
 // ------------------------------------------------------------------ diagnostic copy
 // 16 bytes per thread, 4 KiB per workgroup: the fastest plain-copy shape measured on MI355X.
 __global__ void __launch_bounds__(kThreads)
@@ -555,11 +606,11 @@ static int env_int(const char *name, int dflt)
 }
 // Occupancy targets.  MI355X streams fastest with a bounded amount of traffic in flight per
 // compute unit; one workgroup too many per CU and bandwidth drops by 5-15 % (measured: the fused
-// step at 90 % sparsity reaches 6.2 TB/s with 6 workgroups per CU, 5.9 with 7, 5.5 with 8).  The
-// best count falls as the tiles get denser, so it is chosen per launch from the kept fraction and
-// enforced by padding the LDS request: a workgroup that asks for a size between LDS/(target+1)
-// and LDS/target fits exactly `target` times.  SAMO_OCC_* environment variables override the
-// targets (tuning aid; 0 = no cap).
+// step at 90 % sparsity reaches 6.2 TB/s with 6 workgroups per CU, 5.5 with 7).  Tile workgroups
+// all move about kTileCost bytes, so one target serves every density; it is enforced by padding
+// the LDS request: a workgroup that asks for a size between LDS/(target+1) and LDS/target fits
+// exactly `target` times.  SAMO_OCC_* environment variables override the targets (tuning aid;
+// 0 = no cap).
 constexpr int kLdsPerCu = 160 * 1024;
 static int lds_pad_for(int target_wgs, int static_bytes)
 {
@@ -568,18 +619,16 @@ static int lds_pad_for(int target_wgs, int static_bytes)
     return want > static_bytes ? want - static_bytes : 0;
 }
 
-static int occ_tile_step(int gsrc, int opt, float keep)
+static int occ_tile_step(int gsrc, int opt)
 {
     static const int forced = env_int("SAMO_OCC_TILE_STEP", -1);
     if (forced >= 0) return forced;
-    const float per_tile = keep * kTile;               // compressed elements per workgroup, on average
-    // one workgroup too many costs 10 % (a cliff), one too few 2-3 % (a slope): lean low
-    if (gsrc == kGradDense && opt == kOptAdam) return per_tile < 600.f ? 6 : 5;
-    if (gsrc == kGradDense) return 6;                            // SGD: one state less in flight
-    return per_tile < 600.f ? 0 : 6;                             // compressed gradient: no dense lines in flight
+    // a step that reads the dense gradient keeps whole dense lines in flight: 6 workgroups per CU;
+    // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling
+    return gsrc == kGradDense ? 6 : 0;
 }
 
-static int occ_tile_decompress(float keep)
+static int occ_tile_decompress()
 {
     static const int forced = env_int("SAMO_OCC_TILE_DECOMP", -1);
     return forced >= 0 ? forced : 0;
@@ -616,8 +665,8 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
                        const GuardK &guard, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress(ls.keep)
-                                                         : occ_tile_step(gsrc, opt, ls.keep), kTile * 2);
+    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt),
+                                kMaxTile * 2);
     if (mode == kModeDecompress) {
         SAMO_LAUNCH_TILE(kModeDecompress, kGradDense, kOptAdam);
     } else if (opt == kOptAdam) {
@@ -629,6 +678,23 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
         else if (gsrc == kGradC16) SAMO_LAUNCH_TILE(kModeStep, kGradC16, kOptSgd);
         else SAMO_LAUNCH_TILE(kModeStep, kGradC32, kOptSgd);
     }
+    return hipGetLastError();
+}
+
+int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense)
+{
+    if (dense || n <= 0) return 1;
+    const double per_seg = (double)kSegCost + (double)kNnzCost * (double)kSeg * ((double)nnz / (double)n);
+    const int segs = (int)((double)kTileCost / per_seg + 0.5);
+    return segs < 1 ? 1 : (segs > kMaxTileSegs ? kMaxTileSegs : segs);
+}
+
+hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_rec_start, int num_layers,
+                                  int64_t total, WgRec *d_recs, hipStream_t s)
+{
+    if (total <= 0) return hipSuccess;
+    build_tile_recs_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, s>>>(d_layers, d_rec_start,
+                                                                                              num_layers, total, d_recs);
     return hipGetLastError();
 }
 

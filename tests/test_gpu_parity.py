@@ -325,6 +325,47 @@ def test_batched_entries_match_oracle():
     plan.close()
 
 
+def _uneven_masks():
+    """Masks whose local density swings between nothing kept and everything kept, so that a
+    plan's tiles range from one segment to the largest a workgroup takes."""
+    rng = np.random.default_rng(77)
+    out = []
+    n = 300_007                                          # long empty and full stretches, ragged end
+    m = np.zeros(n, np.uint8)
+    m[20_000:29_000] = 1
+    m[100_000:100_003] = 1
+    m[150_001:260_000] = rng.random(109_999) < 0.5
+    m[-5:] = 1
+    out.append(m)
+    out.append(si.row_clustered_mask(96, 4096, 0.9, 5))  # hot rows 10x denser than the rest
+    out.append(si.row_clustered_mask(40, 3000, 0.8, 6))  # rows that do not line up with segments
+    out.append(np.ones(70_001, np.uint8))                # everything kept, through the index
+    out.append(np.zeros(50_000, np.uint8))               # nothing kept
+    return out
+
+
+def test_plan_tiles_follow_local_density():
+    hosts = [HostLayer(m.shape[0], m, si.weights(m.shape[0], 700 + i), 700 + i) for i, m in enumerate(_uneven_masks())]
+    devs = [DevLayer(h, with_gc16=True) for h in hosts]
+    plan = samo.Plan([d.layer() for d in devs])
+    plan.samo_decompress_batched()
+    for d, h in zip(devs, hosts):
+        assert np.array_equal(host_bits(d.w), oracle.decompress(h.p, h.idx, h.n))
+    for t in (1, 2):
+        for d, h in zip(devs, hosts):
+            d.set_grads(h.grads(t))
+            d.w.fill_(float("nan"))
+        if t == 1:
+            plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        else:                                            # the split form walks the same tiles
+            plan.samo_gather_fp16_batched(False, INV)
+            plan.samo_adam_expand_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        for d, h in zip(devs, hosts):
+            oracle.step(h.grads(t), h.n, h.idx, h.p, h.m, h.v, INV, OCFG, t)
+            _check_fused_outputs(d, h, h.n, t)
+    plan.close()
+
+
 def test_plan_reports_missing_buffers():
     h = _layer(5000, 0.2, 9)
     d = DevLayer(h)                                     # no gc
