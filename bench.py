@@ -91,8 +91,8 @@ def main():
     si.generate(specs, consume, workers=args.gen_workers)
     torch.cuda.synchronize()
 
-    # a0: index of every pruned matrix, batched (count -> size -> count + scan + fill); the second
-    # call is the one timed (it redoes the count, so it is the whole construction)
+    # a0: index of every pruned matrix, batched (a counting call to size the buffers, then the build);
+    # the second call is the one timed (it is the whole construction on its own)
     masks = [m for _, _, _, m in staged if m is not None]
     indices = samo.samo_build_index_many(masks)
     nnz_out = torch.empty(max(len(masks), 1), dtype=torch.int64, device=dev)
@@ -102,7 +102,7 @@ def main():
     e1.record(stream)
     e1.synchronize()
     index_ms = e0.elapsed_time(e1)
-    index_bytes = sum(2 * ix.n + 4 * ix.nnz for ix in indices)
+    index_bytes = sum(ix.n + 4 * ix.nnz for ix in indices)          # the mask is read once, the positions written once
     del masks
     # the model's buffers: one allocation, layer-major (a layer's idx/p/m/v/g/w adjacent)
     it = iter(indices)

@@ -124,14 +124,20 @@ typedef struct {
  *   If nnz > idx_capacity only the first idx_capacity positions are stored;
  *   *d_nnz still holds the true count, so the caller can detect it.
  *   d_idx may be NULL only if idx_capacity == 0.
- * Typical use: count, read *d_nnz, allocate idx, build; or build with capacity n. */
+ * Typical use: count, read *d_nnz, allocate idx, build; or build with capacity n.
+ * The mask is read once: workgroups pass the running count along a chain kept in
+ * d_seg_ptr, waiting for their predecessors for a bounded time.  Should that wait
+ * ever run out (it cannot unless the device stops scheduling running workgroups)
+ * *d_nnz is set to -1 and d_seg_ptr / d_idx are incomplete.  While the call is in
+ * flight d_seg_ptr and *d_nnz hold intermediate values; the outputs of different
+ * jobs of one call must not overlap. */
 samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_ptr,
                                int64_t *d_nnz, void *stream);
 samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx,
                              int64_t idx_capacity, int32_t *d_seg_ptr, int64_t *d_nnz,
                              void *stream);
-/* The same for many layers with a handful of launches (count, scan, fill per group of up to 48
- * jobs), so that small layers do not pay three launches each.  h_jobs is a HOST array of jobs
+/* The same for many layers with a handful of launches (two per group of up to 48 jobs), so
+ * that small layers do not pay their own launches.  h_jobs is a HOST array of jobs
  * holding DEVICE pointers; a job with idx == NULL and idx_capacity == 0 only counts.  Every job
  * is validated before anything is enqueued. */
 typedef struct {

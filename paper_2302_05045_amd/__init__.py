@@ -208,6 +208,8 @@ def samo_build_index(mask: torch.Tensor) -> Index:
     nnz_out = torch.empty(1, dtype=torch.int64, device=mask.device)
     samo_count_nonzero(mask, seg_ptr, nnz_out)
     nnz = int(nnz_out.item())
+    if nnz < 0:
+        raise SamoError(SAMO_ERR_HIP, "samo_count_nonzero (the device-side scan gave up)")
     idx = torch.empty(nnz, dtype=torch.int32, device=mask.device)
     samo_build_index_into(mask, idx, seg_ptr, nnz_out)
     return Index(idx, seg_ptr, nnz, n)
@@ -251,6 +253,8 @@ def samo_build_index_many(masks: Sequence[torch.Tensor]) -> list:
     nnz_out = torch.empty(len(masks), dtype=torch.int64, device=dev)
     samo_build_index_batched(masks, [None] * len(masks), seg_ptrs, nnz_out)
     counts = nnz_out.cpu().tolist()
+    if any(c < 0 for c in counts):
+        raise SamoError(SAMO_ERR_HIP, "samo_build_index_batched (the device-side scan gave up)")
     idxs = [torch.empty(c, dtype=torch.int32, device=dev) for c in counts]
     samo_build_index_batched(masks, idxs, seg_ptrs, nnz_out)
     return [Index(i, s, c, m.numel()) for i, s, c, m in zip(idxs, seg_ptrs, counts, masks)]

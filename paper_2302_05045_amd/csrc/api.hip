@@ -141,6 +141,7 @@ samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_j
             batch.seg_ptr[k] = J.seg_ptr;
             batch.nnz[k] = J.nnz;
             fill |= J.idx_capacity > 0;
+            if (w > 0) batch.ticket = J.nnz;
             wgs += w;
         }
         batch.num = k;

@@ -85,6 +85,8 @@ struct IndexBatch {
     int64_t cap[kIndexBatchJobs];
     int32_t *seg_ptr[kIndexBatchJobs];
     int64_t *nnz[kIndexBatchJobs];
+    int64_t *ticket;                     // the nnz of the job that owns the last workgroup: zero before the
+                                         // launch, counts the workgroups as they start, final once that one ends
 };
 static_assert(sizeof(IndexBatch) <= 3072, "the job table must fit the kernel argument segment");
 

@@ -1,19 +1,29 @@
 // Mask -> index construction (the paper's ind_i, Section III and III-B) for gfx950.
 //
-// The pruner's output arrives as a byte mask over the flattened layer.  One
-// 64-lane wavefront owns one segment of SAMO_SEG_ELEMS = 1024 mask bytes: every
-// lane loads 16 bytes, so a wave reads its segment with one coalesced 1 KiB
-// access.  Pass 1 counts the kept bytes per segment, a single-workgroup scan
-// turns the counts into seg_ptr (exclusive prefix), pass 2 re-reads the mask and
-// writes the ascending int32 positions using a wave-level exclusive scan of the
-// lanes' counts.  All integer work; bound by the two mask reads.
+// The pruner's output arrives as a byte mask over the flattened layer.  The mask is read ONCE.
+// A workgroup of four wavefronts owns 64 consecutive segments of SAMO_SEG_ELEMS = 1024 mask
+// bytes; a wavefront takes sixteen of them, every lane loading 16 bytes of each, so a segment is
+// one coalesced 1 KiB access and sixteen are in flight per lane.  The kept bytes are counted per segment
+// (popcount + wave reduction); the number of kept elements in front of the workgroup then comes
+// from a chained scan across workgroups (each publishes its own count at once and the running
+// total as soon as it knows it; a successor sums the counts back to the nearest running total);
+// finally the ascending int32 positions are written from the flag words still held in registers,
+// using a wave-level exclusive scan of the lanes' counts.  All integer work, bound by one read of
+// the mask plus the write of the index.
+//
+// The chain lives in seg_ptr itself: seg_ptr[e], e the end of a workgroup's block of segments, is
+// the number of kept elements up to there — exactly the running total the next workgroup needs.
+// While unknown it holds kEmpty, then -1 - (own count), then the final value.  Workgroups take
+// their blocks in the order of a ticket drawn at start, so every predecessor of a running
+// workgroup is itself running or done and the wait for it ends; the wait is bounded all the same,
+// and a workgroup that gives up marks its block kPoison, which its successors pass on and the
+// last block of the job reports as *nnz = -1.
 #include "common.h"
 
 namespace samo {
 namespace {
 
 constexpr int kWavesPerWg = kThreads / 64;
-constexpr int kScanThreads = 1024;
 
 // bit (8*b + 7) set for every non-zero byte b of x
 __device__ __forceinline__ uint32_t nonzero_byte_flags(uint32_t x)
@@ -71,100 +81,180 @@ __device__ __forceinline__ int find_job(const IndexBatch &batch, int wg)
     return lo;
 }
 
-// A wave takes kSegsPerWave consecutive segments: four independent 16-byte loads per lane are in
-// flight before anything is reduced, and the four per-lane counts travel through the wave
-// reduction (or scan) packed two to a register — a count is at most 1024, a 16-bit field is enough.
-constexpr int kSegsPerWave = 4;
+// A wave takes kSegsPerWave consecutive segments, kSegsPerLoad at a time: all its 16-byte loads are
+// in flight before anything is reduced, and the per-lane counts travel through the wave scans
+// packed two to a register — a count is at most 1024, a 16-bit field is enough.
+constexpr int kSegsPerLoad = 4;
+constexpr int kRounds = 4;                // rounds of four segments a wave takes: 64 KiB of mask per workgroup
+                                          // (measured: 16 KiB blocks are twice as slow — the chain is per block)
+constexpr int kSegsPerWave = kSegsPerLoad * kRounds;
 constexpr int kSegsPerWg = kSegsPerWave * kWavesPerWg;
+static_assert(kSegsPerWg <= 64, "the block's segment counts are scanned by one wave");
 
-__global__ void __launch_bounds__(kThreads)
-count_kernel(const IndexBatch batch)
+// States of a chain entry other than a final running total (which is >= 0).
+constexpr int kEmpty = INT32_MIN;         // nothing published yet
+constexpr int kPoison = INT32_MIN + 1;    // a predecessor gave up
+constexpr int kSpinLimit = 1 << 20;       // polls of a missing predecessor before giving up (seconds)
+__device__ __forceinline__ int encode_count(int c) { return -1 - c; }
+__device__ __forceinline__ int decode_count(int v) { return -1 - v; }
+
+__device__ __forceinline__ int chain_load(const int32_t *p)
 {
-    const int job = find_job(batch, blockIdx.x);
-    const int64_t n = batch.n[job];
-    const int64_t nseg = (n + kSeg - 1) / kSeg;
-    const int lane = threadIdx.x & 63;
-    const int64_t seg0 = ((int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6)) * kSegsPerWave;
-    if (seg0 >= nseg) return;
-    uint32_t f[kSegsPerWave];
-#pragma unroll
-    for (int q = 0; q < kSegsPerWave; ++q) f[q] = lane_flags(batch.mask[job], n, (seg0 + q) * kSeg + lane * 16);
-    const int lo = wave_sum(__popc(f[0]) | (__popc(f[1]) << 16));
-    const int hi = wave_sum(__popc(f[2]) | (__popc(f[3]) << 16));
-    if (lane < kSegsPerWave && seg0 + lane < nseg) {
-        const int packed = (lane < 2) ? lo : hi;
-        batch.seg_ptr[job][seg0 + lane] = (lane & 1) ? (packed >> 16) : (packed & 0xffff);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void chain_store(int32_t *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// seg_ptr position of the chain entry of block b: the end of its segments.
+__device__ __forceinline__ int64_t chain_slot(int64_t b, int64_t nseg)
+{
+    const int64_t e = (b + 1) * kSegsPerWg;
+    return e < nseg ? e : nseg;
+}
+
+// Prepares a batch: every job's seg_ptr[0] = 0 and *nnz = 0 (the ticket counter is one of these),
+// every block's chain entry = kEmpty.
+__global__ void __launch_bounds__(kThreads)
+index_init_kernel(const IndexBatch batch)
+{
+    const int t = blockIdx.x * kThreads + threadIdx.x;
+    if (t < batch.num) {
+        batch.seg_ptr[t][0] = 0;
+        *batch.nnz[t] = 0;
+    }
+    if (t < batch.wg_start[batch.num]) {
+        const int job = find_job(batch, t);
+        const int64_t nseg = (batch.n[job] + kSeg - 1) / kSeg;
+        batch.seg_ptr[job][chain_slot(t - batch.wg_start[job], nseg)] = kEmpty;
     }
 }
 
-// In-place exclusive scan of a job's seg_ptr[0 .. nseg] where the last entry counts as 0 on
-// input, so that seg_ptr[nseg] receives the grand total; the total is also stored to *nnz.
-// One workgroup per job: every thread owns a contiguous run of ceil(len / 1024) entries (summed
-// and rewritten serially), and one block-wide scan of the 1024 run totals links the runs.
-__global__ void __launch_bounds__(kScanThreads)
-scan_kernel(const IndexBatch batch)
+// Number of kept elements in front of block `blk` of a job (wave 0 of the workgroup, all lanes):
+// sums the published counts of the predecessors back to the nearest running total, 64 chain
+// entries per look (more per look did not pay: measured).  Returns kPoison if a predecessor gave
+// up or never shows.
+__device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t nseg, int blk, int lane)
 {
-    __shared__ int wave_tot[kScanThreads / 64];
-    const int job = blockIdx.x;
-    int32_t *__restrict__ a = batch.seg_ptr[job];
-    const int64_t len = (batch.n[job] + kSeg - 1) / kSeg + 1;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t per = (len + kScanThreads - 1) / kScanThreads;
-    const int64_t lo = (int64_t)tid * per;
-    const int64_t hi = (lo + per < len) ? lo + per : len;
-    int sum = 0;
-    for (int64_t i = lo; i < hi; ++i) sum += (i < len - 1) ? a[i] : 0;
-    const int incl = wave_inclusive_scan(sum, lane);
-    if (lane == 63) wave_tot[wave] = incl;
+    int prefix = 0;
+    int back = blk - 1;                       // nearest predecessor not yet accounted for
+    int spins = 0;
+    while (back >= 0) {
+        const int b = back - lane;            // lane i looks at block back - i
+        int v = kEmpty;
+        if (b >= 0) v = chain_load(seg_ptr + chain_slot(b, nseg));
+        const unsigned long long m_total = __ballot(b >= 0 && v >= 0);
+        const int first_total = m_total ? __ffsll((long long)m_total) - 1 : 64;
+        // the lanes in front of the first running total must all hold counts
+        const bool wanted = lane <= first_total && b >= 0;
+        if (__any(wanted && v == kPoison)) return kPoison;
+        if (__any(wanted && v == kEmpty)) {
+            if (++spins > kSpinLimit) return kPoison;
+            __builtin_amdgcn_s_sleep(2);
+            continue;
+        }
+        int part = 0;
+        if (wanted) part = (lane == first_total) ? v : decode_count(v);
+        prefix += wave_sum(part);
+        if (first_total < 64) break;
+        back -= 64;
+    }
+    return prefix;
+}
+
+__global__ void __launch_bounds__(kThreads)
+index_kernel(const IndexBatch batch, int fill)
+{
+    __shared__ int sh_ticket;
+    __shared__ int sh_seg[kSegsPerWg];        // kept elements per segment, then in front of it within the block
+    __shared__ int sh_base;                   // kept elements in front of the block, or kPoison
+    __shared__ int32_t sh_stage[kWavesPerWg][kSeg];   // positions of one segment per wave, on their way out
+    if (threadIdx.x == 0) sh_ticket = (int)atomicAdd(reinterpret_cast<unsigned long long *>(batch.ticket), 1ull);
     __syncthreads();
+    const int ticket = sh_ticket;
+    const int job = find_job(batch, ticket);
+    const int blk = ticket - batch.wg_start[job];
+    const int64_t n = batch.n[job];
+    const int64_t nseg = (n + kSeg - 1) / kSeg;
+    int32_t *__restrict__ seg_ptr = batch.seg_ptr[job];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t seg0 = ((int64_t)blk * kWavesPerWg + wave) * kSegsPerWave;     // segments beyond nseg read as empty
+
+    uint32_t f[kRounds][kSegsPerLoad];
+    int c01[kRounds], c23[kRounds], i01[kRounds], i23[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int q = 0; q < kSegsPerLoad; ++q)
+            f[r][q] = lane_flags(batch.mask[job], n, (seg0 + r * kSegsPerLoad + q) * kSeg + lane * 16);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        c01[r] = __popc(f[r][0]) | (__popc(f[r][1]) << 16);
+        c23[r] = __popc(f[r][2]) | (__popc(f[r][3]) << 16);
+        i01[r] = wave_inclusive_scan(c01[r], lane);
+        i23[r] = wave_inclusive_scan(c23[r], lane);
+        if (lane == 63) {                      // the last lane's inclusive prefixes are the segment totals
+            int *dst = sh_seg + wave * kSegsPerWave + r * kSegsPerLoad;
+            dst[0] = i01[r] & 0xffff;
+            dst[1] = i01[r] >> 16;
+            dst[2] = i23[r] & 0xffff;
+            dst[3] = i23[r] >> 16;
+        }
+    }
+    __syncthreads();
+
+    const int64_t slot = chain_slot(blk, nseg);
+    const bool last_block = (blk + 1 == batch.wg_start[job + 1] - batch.wg_start[job]);
     if (wave == 0) {
-        const int t = (lane < kScanThreads / 64) ? wave_tot[lane] : 0;
-        const int ti = wave_inclusive_scan(t, lane);
-        if (lane < kScanThreads / 64) wave_tot[lane] = ti - t;     // exclusive prefix of the waves
-        if (lane == kScanThreads / 64 - 1) *batch.nnz[job] = (int64_t)ti;   // grand total
+        const int c = lane < kSegsPerWg ? sh_seg[lane] : 0;
+        const int incl = wave_inclusive_scan(c, lane);
+        const int total = __shfl(incl, kSegsPerWg - 1, 64);
+        if (blk > 0 && lane == 0) chain_store(seg_ptr + slot, encode_count(total));
+        const int before = kept_before_block(seg_ptr, nseg, blk, lane);
+        if (lane == 0) {
+            chain_store(seg_ptr + slot, before == kPoison ? kPoison : before + total);
+            sh_base = before;
+            if (last_block) *batch.nnz[job] = (before == kPoison) ? -1 : (int64_t)before + total;
+        }
+        if (lane < kSegsPerWg) sh_seg[lane] = incl - c;
     }
     __syncthreads();
-    int run = wave_tot[wave] + incl - sum;                          // exclusive prefix of this thread's run
-    for (int64_t i = lo; i < hi; ++i) {
-        const int x = (i < len - 1) ? a[i] : 0;
-        a[i] = run;
-        run += x;
-    }
-}
+    const int base = sh_base;
+    if (base == kPoison) return;
 
-__global__ void __launch_bounds__(kThreads)
-fill_kernel(const IndexBatch batch)
-{
-    const int job = find_job(batch, blockIdx.x);
-    const int64_t n = batch.n[job];
+    // seg_ptr entries strictly inside the block (its first is the predecessor's chain entry)
+    const int64_t first_seg = (int64_t)blk * kSegsPerWg;
+    if (threadIdx.x >= 1 && threadIdx.x < kSegsPerWg && first_seg + threadIdx.x < slot)
+        seg_ptr[first_seg + threadIdx.x] = base + sh_seg[threadIdx.x];
+
     const int64_t cap = batch.cap[job];
-    const int64_t nseg = (n + kSeg - 1) / kSeg;
-    const int lane = threadIdx.x & 63;
-    const int64_t seg0 = ((int64_t)(blockIdx.x - batch.wg_start[job]) * kWavesPerWg + (threadIdx.x >> 6)) * kSegsPerWave;
-    if (seg0 >= nseg || cap <= 0) return;
+    if (!fill || cap <= 0 || seg0 >= nseg) return;
     int32_t *__restrict__ idx = batch.idx[job];
-    uint32_t f[kSegsPerWave];
-    int base[kSegsPerWave];
+    int32_t *stage = sh_stage[wave];           // this wave's own staging area: no workgroup barrier needed
 #pragma unroll
-    for (int q = 0; q < kSegsPerWave; ++q) {
-        f[q] = lane_flags(batch.mask[job], n, (seg0 + q) * kSeg + lane * 16);
-        base[q] = (seg0 + q < nseg) ? batch.seg_ptr[job][seg0 + q] : 0;
-    }
-    const int c01 = __popc(f[0]) | (__popc(f[1]) << 16);
-    const int c23 = __popc(f[2]) | (__popc(f[3]) << 16);
-    const int e01 = wave_inclusive_scan(c01, lane) - c01;       // exclusive lane prefixes, two per register
-    const int e23 = wave_inclusive_scan(c23, lane) - c23;
-    const int excl[kSegsPerWave] = {e01 & 0xffff, e01 >> 16, e23 & 0xffff, e23 >> 16};
+    for (int r = 0; r < kRounds; ++r) {
+        const int e01 = i01[r] - c01[r], e23 = i23[r] - c23[r];     // exclusive lane prefixes, two per register
+        const int excl[kSegsPerLoad] = {e01 & 0xffff, e01 >> 16, e23 & 0xffff, e23 >> 16};
+        const int t01 = __builtin_amdgcn_readlane(i01[r], 63), t23 = __builtin_amdgcn_readlane(i23[r], 63);
+        const int tot[kSegsPerLoad] = {t01 & 0xffff, t01 >> 16, t23 & 0xffff, t23 >> 16};
 #pragma unroll
-    for (int q = 0; q < kSegsPerWave; ++q) {
-        const int64_t first = (seg0 + q) * kSeg + lane * 16;
-        int64_t out = (int64_t)base[q] + excl[q];
-        uint32_t bits = f[q];
-        while (bits) {
-            const int b = __ffs(bits) - 1;
-            bits &= bits - 1;
-            if (out < cap) idx[out] = (int32_t)(first + b);
-            ++out;
+        for (int q = 0; q < kSegsPerLoad; ++q) {
+            // the segment's positions go to LDS in order, then leave as contiguous 256-byte stores
+            const int sq = r * kSegsPerLoad + q;
+            const int first = (int)((seg0 + sq) * kSeg) + lane * 16;     // a layer's flat size fits int32
+            int at = excl[q];
+            uint32_t bits = f[r][q];
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                stage[at++] = first + b;
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int64_t out0 = (int64_t)base + sh_seg[wave * kSegsPerWave + sq];
+            for (int o = lane; o < tot[q]; o += 64)
+                if (out0 + o < cap) idx[out0 + o] = stage[o];
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -212,11 +302,11 @@ validate_kernel(const int32_t *__restrict__ idx, int64_t nnz, int64_t n, int64_t
 
 hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s)
 {
-    const int wgs = batch.wg_start[batch.num];
     if (batch.num <= 0) return hipSuccess;
-    if (wgs > 0) count_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch);
-    scan_kernel<<<dim3((unsigned)batch.num), dim3(kScanThreads), 0, s>>>(batch);
-    if (fill && wgs > 0) fill_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch);
+    const int wgs = batch.wg_start[batch.num];
+    const int init_threads = wgs > batch.num ? wgs : batch.num;
+    index_init_kernel<<<dim3((unsigned)ceil_div(init_threads, kThreads)), dim3(kThreads), 0, s>>>(batch);
+    if (wgs > 0) index_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch, fill ? 1 : 0);
     return hipGetLastError();
 }
 
