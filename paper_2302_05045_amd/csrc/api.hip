@@ -2,6 +2,7 @@
 // Every entry point validates on the host first and enqueues only if all
 // arguments are acceptable, so the error paths can be exercised without a GPU.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -126,6 +127,9 @@ samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_j
     for (int32_t j0 = 0; j0 < num_jobs;) {
         IndexBatch batch;
         std::memset(&batch, 0, sizeof(batch));
+        // testing aid: a tiny limit makes the give-up path (nnz = -1) reachable from the host
+        const char *limit = std::getenv("SAMO_INDEX_SPIN_LIMIT");
+        batch.spin_limit = limit ? std::atoi(limit) : kIndexSpinLimit;
         bool fill = false;
         int64_t wgs = 0;
         int k = 0;

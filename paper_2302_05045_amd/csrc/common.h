@@ -76,6 +76,7 @@ struct StatPartial {
 
 // Up to kIndexBatchJobs index-build jobs, passed to the kernels by value (kernel argument segment).
 constexpr int kIndexBatchJobs = 48;
+constexpr int kIndexSpinLimit = 1 << 20;   // about a second of polling
 struct IndexBatch {
     int num;
     int wg_start[kIndexBatchJobs + 1];   // exclusive prefix of workgroups per job
@@ -85,6 +86,7 @@ struct IndexBatch {
     int64_t cap[kIndexBatchJobs];
     int32_t *seg_ptr[kIndexBatchJobs];
     int64_t *nnz[kIndexBatchJobs];
+    int spin_limit;                      // polls of a missing predecessor before a workgroup gives up
     int64_t *ticket;                     // the nnz of the job that owns the last workgroup: zero before the
                                          // launch, counts the workgroups as they start, final once that one ends
 };

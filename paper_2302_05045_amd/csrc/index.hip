@@ -94,7 +94,6 @@ static_assert(kSegsPerWg <= 64, "the block's segment counts are scanned by one w
 // States of a chain entry other than a final running total (which is >= 0).
 constexpr int kEmpty = INT32_MIN;         // nothing published yet
 constexpr int kPoison = INT32_MIN + 1;    // a predecessor gave up
-constexpr int kSpinLimit = 1 << 20;       // polls of a missing predecessor before giving up (seconds)
 __device__ __forceinline__ int encode_count(int c) { return -1 - c; }
 __device__ __forceinline__ int decode_count(int v) { return -1 - v; }
 
@@ -135,7 +134,7 @@ index_init_kernel(const IndexBatch batch)
 // sums the published counts of the predecessors back to the nearest running total, 64 chain
 // entries per look (more per look did not pay: measured).  Returns kPoison if a predecessor gave
 // up or never shows.
-__device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t nseg, int blk, int lane)
+__device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t nseg, int blk, int lane, int spin_limit)
 {
     int prefix = 0;
     int back = blk - 1;                       // nearest predecessor not yet accounted for
@@ -150,7 +149,7 @@ __device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t
         const bool wanted = lane <= first_total && b >= 0;
         if (__any(wanted && v == kPoison)) return kPoison;
         if (__any(wanted && v == kEmpty)) {
-            if (++spins > kSpinLimit) return kPoison;
+            if (++spins > spin_limit) return kPoison;
             __builtin_amdgcn_s_sleep(2);
             continue;
         }
@@ -211,7 +210,7 @@ index_kernel(const IndexBatch batch, int fill)
         const int incl = wave_inclusive_scan(c, lane);
         const int total = __shfl(incl, kSegsPerWg - 1, 64);
         if (blk > 0 && lane == 0) chain_store(seg_ptr + slot, encode_count(total));
-        const int before = kept_before_block(seg_ptr, nseg, blk, lane);
+        const int before = kept_before_block(seg_ptr, nseg, blk, lane, batch.spin_limit);
         if (lane == 0) {
             chain_store(seg_ptr + slot, before == kPoison ? kPoison : before + total);
             sh_base = before;
