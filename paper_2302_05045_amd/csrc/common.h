@@ -20,7 +20,9 @@ namespace samo {
 // density (clustered masks, mixed pruned and dense layers), so one occupancy target fits all.
 // Flat kernels: one 64-lane wave per workgroup with one float4 per array.
 constexpr int kThreads = 256;           // index kernels: 4 wavefronts per workgroup
-constexpr int kTileThreads = 256;       // tile kernels
+constexpr int kTileThreads = 256;       // tile kernels that run an optimizer step
+constexpr int kExpandThreads = 128;     // expansion only: little read traffic per tile, so more, smaller workgroups
+                                        // per compute unit (+15 % over 256 threads; the step kernels lose with 128)
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
 constexpr int64_t kTileCost = 32768;    // target weight of one tile workgroup
 constexpr int64_t kSegCost = 6144;      // weight of a segment's dense side (fp16 gradient lines read, fp16 weights written)

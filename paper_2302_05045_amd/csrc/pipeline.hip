@@ -137,7 +137,7 @@ __device__ __forceinline__ void pick_tile(const LaunchSet &ls, samo_layer *L, in
 // Dense (unpruned) layer: identity index, plain elementwise pass over the tile (one segment, so
 // one trip).  A thread takes four consecutive elements — one 16-byte vector of each fp32 array,
 // one 8-byte vector of each fp16 array — so every wave-level access is one contiguous run.
-template <int MODE, int GSRC, int OPT>
+template <int MODE, int GSRC, int OPT, int T>
 __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, int len, float inv_scale, float coef,
                                            const OptK &k)
 {
@@ -147,7 +147,7 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
     float4 *__restrict__ V = reinterpret_cast<float4 *>(L.v + base);
     uint2 *__restrict__ W = reinterpret_cast<uint2 *>(L.w + base);
     const int nvec = len / 4;
-    for (int o = tid; o < nvec; o += kTileThreads) {
+    for (int o = tid; o < nvec; o += T) {
         float4 p = P[o];
         if (MODE == kModeStep) {
             float4 m = M[o];
@@ -176,7 +176,7 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
         const uint32_t hi = (uint32_t)float_to_half_bits(p.z) | ((uint32_t)float_to_half_bits(p.w) << 16);
         store8_stream(W + o, make_uint2(lo, hi));
     }
-    for (int e = nvec * 4 + tid; e < len; e += kTileThreads) {      // ragged end of the layer
+    for (int e = nvec * 4 + tid; e < len; e += T) {      // ragged end of the layer
         float pe = L.p[base + e];
         if (MODE == kModeStep) {
             float g;
@@ -192,13 +192,13 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
     }
 }
 
-template <int MODE, int GSRC, int OPT>
+template <int MODE, int GSRC, int OPT, int T>
 __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nsegs, int64_t base, int len,
                                             float inv_scale, float coef, const OptK &k, uint16_t *lds_w)
 {
     const int tid = threadIdx.x;
     uint4 *l4 = reinterpret_cast<uint4 *>(lds_w);
-    for (int o = tid; o < (len + 7) / 8; o += kTileThreads) l4[o] = make_uint4(0u, 0u, 0u, 0u);
+    for (int o = tid; o < (len + 7) / 8; o += T) l4[o] = make_uint4(0u, 0u, 0u, 0u);
 
     const int c0 = L.seg_ptr[s0];
     const int c1 = L.seg_ptr[s0 + nsegs];
@@ -217,13 +217,13 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nse
     const int ibase = (int)base;             // a layer's flat size fits int32
 
     constexpr int U = kTileUnroll;
-    for (int r0 = tid; r0 < cnt; r0 += U * kTileThreads) {
+    for (int r0 = tid; r0 < cnt; r0 += U * T) {
         int j[U];
         float pp[U], mm[U], vv[U], gg[U];
         uint16_t gb[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * kTileThreads;
+            const int r = r0 + u * T;
             j[u] = ibase; pp[u] = 0.f; mm[u] = 0.f; vv[u] = 0.f; gg[u] = 0.f; gb[u] = 0;
             if (r < cnt) {
                 j[u] = IDX[r];
@@ -239,11 +239,11 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nse
         if (MODE == kModeStep && GSRC == kGradDense) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (r0 + u * kTileThreads < cnt) gb[u] = G[j[u]];
+                if (r0 + u * T < cnt) gb[u] = G[j[u]];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * kTileThreads;
+            const int r = r0 + u * T;
             if (r < cnt) {
                 if (MODE == kModeStep) {
                     const float g = (GSRC == kGradC32) ? gg[u] * coef
@@ -261,12 +261,12 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nse
 
     uint16_t *__restrict__ W = L.w + base;
     const int nvec = len / 8;
-    for (int o = tid; o < nvec; o += kTileThreads) store16_stream(reinterpret_cast<uint4 *>(W) + o, l4[o]);
-    for (int e = nvec * 8 + tid; e < len; e += kTileThreads) W[e] = lds_w[e];
+    for (int o = tid; o < nvec; o += T) store16_stream(reinterpret_cast<uint4 *>(W) + o, l4[o]);
+    for (int e = nvec * 8 + tid; e < len; e += T) W[e] = lds_w[e];
 }
 
-template <int MODE, int GSRC, int OPT>
-__global__ void __launch_bounds__(kTileThreads)
+template <int MODE, int GSRC, int OPT, int T>
+__global__ void __launch_bounds__(T)
 tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guard)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[kMaxTile];
@@ -281,9 +281,9 @@ tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guar
     const int64_t rest = L.n - base;
     const int len = rest < (int64_t)nsegs * kSeg ? (int)rest : nsegs * kSeg;
     if (L.seg_ptr == nullptr)                 // dense (unpruned) layer
-        dense_tile<MODE, GSRC, OPT>(L, base, len, inv_scale, coef, k);
+        dense_tile<MODE, GSRC, OPT, T>(L, base, len, inv_scale, coef, k);
     else
-        sparse_tile<MODE, GSRC, OPT>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w);
+        sparse_tile<MODE, GSRC, OPT, T>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w);
 }
 
 // ------------------------------------------------------------------ statistics helpers
@@ -659,7 +659,7 @@ static int occ_flat_step()
 }
 
 #define SAMO_LAUNCH_TILE(M, G, O)                                                                          \
-    tile_kernel<M, G, O><<<dim3((unsigned)ls.wgs), dim3(kTileThreads), pad, s>>>(ls, inv_scale, k, guard)
+    tile_kernel<M, G, O, kTileThreads><<<dim3((unsigned)ls.wgs), dim3(kTileThreads), pad, s>>>(ls, inv_scale, k, guard)
 
 hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
                        const GuardK &guard, hipStream_t s)
@@ -668,7 +668,8 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
     const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt),
                                 kMaxTile * 2);
     if (mode == kModeDecompress) {
-        SAMO_LAUNCH_TILE(kModeDecompress, kGradDense, kOptAdam);
+        tile_kernel<kModeDecompress, kGradDense, kOptAdam, kExpandThreads><<<dim3((unsigned)ls.wgs), dim3(kExpandThreads), pad, s>>>(ls, inv_scale, k,
+                                                                                                                          guard);
     } else if (opt == kOptAdam) {
         if (gsrc == kGradDense) SAMO_LAUNCH_TILE(kModeStep, kGradDense, kOptAdam);
         else if (gsrc == kGradC16) SAMO_LAUNCH_TILE(kModeStep, kGradC16, kOptAdam);
