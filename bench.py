@@ -213,19 +213,20 @@ def main():
             idx = oracle.build_index(mask)
             state.append((spec, idx, p_host.copy(), np.zeros_like(p_host), np.zeros_like(p_host), g16,
                           np.empty(spec.n, np.uint16)))
-        best = None
-        for rep in (1, 2):
+        best, spent = None, 0.0
+        for rep in (1, 2, 3, 4):                  # about 10-30 s of CPU work in all
             t0 = time.perf_counter()
             for spec, idx, p, m, v, g16, w in state:
                 oracle.step(g16, spec.n, idx, p, m, v, inv, ocfg, rep, w)
             dt = time.perf_counter() - t0
             best = dt if best is None else min(best, dt)
-            if dt > 20:
+            spent += dt
+            if spent + dt > 30:
                 break
         cpu_nnz = sum(s[1].shape[0] for s in state)
         cpu = {"value": round(cpu_nnz / best, 1), "unit": "nonzero params/s", "cores": 1, "kind": "oracle",
                "sample": "%d of %d weight matrices of the workload (%d nonzeros), one gather+Adam+expand step, "
-                         "best of <=2, single thread" % (len(state), len(specs), cpu_nnz),
+                         "best of <=4, single thread" % (len(state), len(specs), cpu_nnz),
                "seconds": round(best, 3), "host_cpus": os.cpu_count()}
 
     out = {
@@ -249,7 +250,7 @@ def main():
                    "resident_bytes": samo.samo_memory_model(n_total, nnz_total)[2]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "tile_kernel<1, 0, 0> (step, dense gradient, Adam)", "kernel_ms": round(kernel_ms, 4),
+                     "kernel": "tile_kernel<1, 0, 0, 256> (step, dense gradient, Adam, 256 threads)", "kernel_ms": round(kernel_ms, 4),
                      "algorithmic_bytes_per_launch": fused_bytes},
         "cpu_baseline": cpu,
         "entries": entries,
