@@ -204,3 +204,81 @@ def test_fused_step_under_hip_graph_replay():
     for _ in range(4):
         eager.oracle_step(1)
     eager.check(1)
+
+
+def test_index_build_statistics_and_guarded_split_step_under_hip_graph_replay():
+    """Index construction (init + chained kernel), the compressed fp16 gather with gradient
+    statistics (gather, two-level reduction) and the clipped Adam+expand step are kernels only —
+    no memset, no allocation — so they replay from a HIP graph; every replay is checked against
+    the eager result, with eager work and synchronisations between replays."""
+    specs = si.config("gpt350m", 0.9, layers=1)
+    n_masks = len(specs)
+    host = [si.make_layer(s) for s in specs]
+    masks = [torch.from_numpy(h.mask).to(DEV) for h in host]
+    first = samo.samo_build_index_many(masks)                       # sizes the buffers (eager)
+    layers = samo.alloc_model([(ix.n, ix.nnz, False) for ix in first], DEV, with_gc16=True)
+    ref = samo.alloc_model([(ix.n, ix.nnz, False) for ix in first], DEV, with_gc16=True)
+    for group in (layers, ref):
+        for L, ix, h in zip(group, first, host):
+            L.idx.copy_(ix.idx)
+            L.seg_ptr.copy_(ix.seg_ptr)
+            L.p.copy_(torch.from_numpy(np.ascontiguousarray(h.w32[h.mask != 0])))
+            L.g.copy_(torch.from_numpy(h.g16.view(np.int16)).view(torch.float16))
+    plan, ref_plan = samo.Plan(layers), samo.Plan(ref)
+    stats, ref_stats = samo.GradStats(plan), samo.GradStats(ref_plan)
+    cfg = samo.adam_cfg(1, **si.ADAM)
+    nnz_out = torch.zeros(n_masks, dtype=torch.int64, device=DEV)
+    max_norm = 0.5                                                 # well below the gradient's norm: clipping acts
+
+    def work(pl, st, group):
+        samo.samo_build_index_batched(masks, [L.idx for L in group], [L.seg_ptr for L in group], nnz_out)
+        pl.samo_gather_fp16_batched(False, INV, st)
+        pl.samo_adam_expand_batched(INV, cfg, st.guard(max_norm, True))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work(plan, stats, layers)                                   # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work(plan, stats, layers)
+    work(ref_plan, ref_stats, ref)                                  # both sides have done one step
+    for rep in range(3):
+        for group in (layers, ref):
+            for L in group:
+                L.w.fill_(float("nan"))
+                L.idx.fill_(-1)                                     # the replay has to rebuild these
+                L.seg_ptr.fill_(-7)
+        nnz_out.fill_(-3)
+        torch.cuda.synchronize()
+        work(ref_plan, ref_stats, ref)
+        expect_nnz = nnz_out.clone()
+        nnz_out.fill_(-3)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(nnz_out, expect_nnz) and nnz_out.tolist() == [ix.nnz for ix in first], rep
+        assert stats.read() == ref_stats.read(), rep
+        for a, b, ix in zip(layers, ref, first):
+            assert torch.equal(a.idx, ix.idx) and torch.equal(a.seg_ptr, ix.seg_ptr), rep
+            assert torch.equal(a.idx, b.idx) and torch.equal(a.seg_ptr, b.seg_ptr), rep
+            assert torch.equal(a.gc16.view(torch.int16), b.gc16.view(torch.int16)), rep
+            assert torch.equal(a.p, b.p) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v), rep
+            assert torch.equal(a.w.view(torch.int16), b.w.view(torch.int16)), rep
+    ss, bad = stats.read()
+    assert not bad and ss ** 0.5 > max_norm
+    # the eager side against the oracle: four identical clipped steps with t = 1
+    total = sum(oracle.sum_squares(oracle.gather(h.g16, np.flatnonzero(h.mask).astype(np.int32), INV)) for h in host)
+    coef = oracle.clip_coefficient(total, max_norm)
+    for L, h in zip(ref, host):
+        idx = oracle.build_index(h.mask)
+        p = np.ascontiguousarray(h.w32[idx])
+        m, v = np.zeros_like(p), np.zeros_like(p)
+        for _ in range(4):
+            gc = oracle.gather(h.g16, idx, INV)
+            oracle.scale(gc, coef)
+            oracle.adam(p, m, v, gc, OCFG, 1)
+        assert_close(L.p.cpu().numpy(), p, "p")
+        assert_close(L.m.cpu().numpy(), m, "m")
+        assert_close(L.v.cpu().numpy(), v, "v")
