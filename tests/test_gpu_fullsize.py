@@ -19,7 +19,7 @@ class Model:
     """All layers of a configuration on the GPU (index built by the library) and on the host
     (index built by the oracle)."""
 
-    def __init__(self, specs, with_gc=False, workers=12):
+    def __init__(self, specs, with_gc=False, workers=12, with_gc16=False):
         self.specs = specs
         self.host = []      # [spec, mask, idx, p, m, v, g16]
         masks = []
@@ -35,7 +35,7 @@ class Model:
         # same set-up as bench.py: batched index build, one layer-major allocation, one plan
         built = iter(samo.samo_build_index_many([m for m in masks if m is not None]))
         self.layers = samo.alloc_model([(h[0].n, h[2].shape[0], m is None) for h, m in zip(self.host, masks)], DEV,
-                                       with_gc=with_gc)
+                                       with_gc=with_gc, with_gc16=with_gc16)
         for L, h, m in zip(self.layers, self.host, masks):
             if m is not None:
                 ix = next(built)
@@ -69,9 +69,9 @@ class Model:
             L.w.fill_(float("nan"))
 
 
-def test_gpt2p7b_90pct_fused_batched_two_steps():
+def test_gpt2p7b_90pct_every_batched_entry_at_full_size():
     """The configuration bench.py times: 128 matrices, N = 2,516,582,400, one launch per step."""
-    model = Model(si.config("gpt2.7b", 0.9))
+    model = Model(si.config("gpt2.7b", 0.9), with_gc=True, with_gc16=True)
     n_total, nnz_total = model.plan.totals()
     assert n_total == 2_516_582_400 and nnz_total == 251_658_240
     for t in (1, 2):
@@ -79,6 +79,25 @@ def test_gpt2p7b_90pct_fused_batched_two_steps():
         model.plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
         model.oracle_step(t)
         model.check(t)
+    # step 3 as the separate passes of the paper, step 4 as the split around an all-reduce with the
+    # gradient statistics reduced on the way (the other entries bench.py times, same launch shapes)
+    model.poison_w()
+    model.plan.samo_gather_batched(INV)
+    model.plan.samo_adam_batched(samo.adam_cfg(3, **si.ADAM))
+    model.plan.samo_decompress_batched()
+    model.oracle_step(3)
+    model.check(3)
+    model.poison_w()
+    stats = samo.GradStats(model.plan)
+    model.plan.samo_gather_fp16_batched(False, INV, stats)
+    model.plan.samo_adam_expand_batched(INV, samo.adam_cfg(4, **si.ADAM), stats.guard(0.0, True))
+    ref_ss = sum(oracle.sum_squares(oracle.gather(h[6], h[2], INV)) for h in model.host)
+    ss, bad = stats.read()
+    assert not bad and abs(ss - ref_ss) <= 2 * nnz_total * 2.0 ** -53 * ref_ss
+    for L, h in zip(model.layers[:8], model.host[:8]):
+        assert np.array_equal(host_bits(L.gc16), oracle.compress_f16(h[6], h[2])), h[0].name
+    model.oracle_step(4)
+    model.check(4)
 
 
 def test_gpt350m_unfused_then_fused():
