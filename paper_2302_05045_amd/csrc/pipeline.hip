@@ -287,11 +287,31 @@ tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guar
 }
 
 // ------------------------------------------------------------------ statistics helpers
+// Sum over the 64 lanes of a wave, the same value returned to every lane.  Data-parallel
+// primitives move the operands between lanes inside the vector ALU (row shifts within 16 lanes,
+// then two row broadcasts), which is a handful of cycles per step where a shuffle through the LDS
+// crossbar costs a round trip; the order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add_f64(double x)
+{
+    const int lo = __double2loint(x), hi = __double2hiint(x);
+    // lanes the pattern does not feed read 0.0 (bound_ctrl), rows outside ROW_MASK keep x + 0.0
+    const int lo2 = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, true);
+    const int hi2 = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, true);
+    return x + __hiloint2double(hi2, lo2);
+}
+
 __device__ __forceinline__ double wave_sum_f64(double x)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
-    return x;
+    x = dpp_add_f64<0x111, 0xf>(x);           // row_shr:1  (inclusive scan within each row of 16 lanes)
+    x = dpp_add_f64<0x112, 0xf>(x);           // row_shr:2
+    x = dpp_add_f64<0x114, 0xf>(x);           // row_shr:4
+    x = dpp_add_f64<0x118, 0xf>(x);           // row_shr:8
+    x = dpp_add_f64<0x142, 0xa>(x);           // row_bcast:15 into rows 1 and 3
+    x = dpp_add_f64<0x143, 0xc>(x);           // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+    return __hiloint2double(hi, lo);
 }
 
 // A flat workgroup is one wave: its (sum of squares, flag) partial is a wave reduction, fixed
