@@ -58,13 +58,25 @@ __device__ __forceinline__ int wave_sum(int x)
     return x;
 }
 
+// Inclusive scan over the 64 lanes with data-parallel primitives: a shifted add within each row of
+// 16 lanes (four steps), then lane 15 of a row added to the whole next row and lane 31 to the upper
+// half — the operands move inside the vector ALU, no trip through the LDS crossbar.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_add(int x)
+{
+    // lanes the pattern does not feed read 0 (bound_ctrl); rows outside ROW_MASK add 0
+    return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, true);
+}
+
 __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int y = __shfl_up(x, d, 64);
-        if (lane >= d) x += y;
-    }
+    (void)lane;
+    x = dpp_add<0x111, 0xf>(x);               // row_shr:1
+    x = dpp_add<0x112, 0xf>(x);               // row_shr:2
+    x = dpp_add<0x114, 0xf>(x);               // row_shr:4
+    x = dpp_add<0x118, 0xf>(x);               // row_shr:8
+    x = dpp_add<0x142, 0xa>(x);               // row_bcast:15 into rows 1 and 3
+    x = dpp_add<0x143, 0xc>(x);               // row_bcast:31 into rows 2 and 3
     return x;
 }
 
