@@ -286,6 +286,15 @@ samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper
  * rate and calibrates hardware byte counters.  Not part of the method. */
 samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void *stream);
 
+/* ---------------------------------------------------------------- environment (tuning and testing aids)
+ * Read by the library, never required:
+ *   SAMO_OCC_TILE_STEP, SAMO_OCC_TILE_DECOMP, SAMO_OCC_FLAT_GATHER, SAMO_OCC_FLAT_STATS,
+ *   SAMO_OCC_FLAT_STEP   workgroups (waves for the flat kernels) resident per compute unit that a
+ *                        launch of that kind aims at, overriding the built-in target; 0 = no cap.
+ *                        Read once per process.
+ *   SAMO_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it gives
+ *                        up (default 2^20); 0 makes the give-up path reachable in tests.  Read per call. */
+
 #ifdef __cplusplus
 }
 #endif
