@@ -388,6 +388,37 @@ def test_plan_tiles_follow_local_density():
     plan.close()
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_plan_tiles_cover_random_piecewise_masks(seed):
+    """Many layers of random size whose density jumps between stretches (nothing, a few, half, all
+    kept): whatever the cut into tiles, every segment must be expanded and updated exactly once."""
+    rng = np.random.default_rng(1000 + seed)
+    hosts = []
+    for i in range(24):
+        n = int(rng.choice([1, 7, 1023, 1024, 1025, 5000, 33_333, 70_000, 200_001]))
+        mask = np.zeros(n, np.uint8)
+        lo = 0
+        while lo < n:
+            hi = min(n, lo + int(rng.integers(1, 20_000)))
+            d = float(rng.choice([0.0, 0.003, 0.05, 0.5, 1.0]))
+            mask[lo:hi] = rng.random(hi - lo) < d
+            lo = hi
+        hosts.append(HostLayer(n, mask, si.weights(n, 3000 + 100 * seed + i), 3000 + 100 * seed + i))
+    devs = [DevLayer(h) for h in hosts]
+    plan = samo.Plan([d.layer() for d in devs])
+    plan.samo_decompress_batched()
+    for d, h in zip(devs, hosts):
+        assert np.array_equal(host_bits(d.w), oracle.decompress(h.p, h.idx, h.n))
+    for d, h in zip(devs, hosts):
+        d.set_grads(h.grads(1))
+        d.w.fill_(float("nan"))
+    plan.samo_fused_step_batched(INV, samo.adam_cfg(1, **si.ADAM))
+    for d, h in zip(devs, hosts):
+        oracle.step(h.grads(1), h.n, h.idx, h.p, h.m, h.v, INV, OCFG, 1)
+        _check_fused_outputs(d, h, h.n, 1)
+    plan.close()
+
+
 def test_plan_reports_missing_buffers():
     h = _layer(5000, 0.2, 9)
     d = DevLayer(h)                                     # no gc
