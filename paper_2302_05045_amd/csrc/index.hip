@@ -36,7 +36,8 @@ __device__ __forceinline__ uint32_t lane_flags(const uint8_t *__restrict__ mask,
 {
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     if (first + 16 <= n) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(mask + first);
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(mask + first));   // read once
         w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
     } else {
         for (int b = 0; b < 16; ++b)

@@ -412,8 +412,8 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
             }
         }
         if (cnt == 4) {
-            *reinterpret_cast<uint2 *>(L.gc16 + i) =
-                make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16), (uint32_t)hb[2] | ((uint32_t)hb[3] << 16));
+            store8_stream(L.gc16 + i, make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16),
+                                                 (uint32_t)hb[2] | ((uint32_t)hb[3] << 16)));   // +4 % over a plain store
         } else {
             for (int e = 0; e < cnt; ++e) L.gc16[i + e] = hb[e];
         }
