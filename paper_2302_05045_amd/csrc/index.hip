@@ -3,13 +3,14 @@
 // The pruner's output arrives as a byte mask over the flattened layer.  The mask is read ONCE.
 // A workgroup of four wavefronts owns 64 consecutive segments of SAMO_SEG_ELEMS = 1024 mask
 // bytes; a wavefront takes sixteen of them, every lane loading 16 bytes of each, so a segment is
-// one coalesced 1 KiB access and sixteen are in flight per lane.  The kept bytes are counted per segment
-// (popcount + wave reduction); the number of kept elements in front of the workgroup then comes
-// from a chained scan across workgroups (each publishes its own count at once and the running
-// total as soon as it knows it; a successor sums the counts back to the nearest running total);
-// finally the ascending int32 positions are written from the flag words still held in registers,
-// using a wave-level exclusive scan of the lanes' counts.  All integer work, bound by one read of
-// the mask plus the write of the index.
+// one coalesced 1 KiB access and sixteen are in flight per lane.  The kept bytes are counted per
+// lane (popcount of a 16-bit flag word) and scanned across the wave, which gives every lane its
+// offset within the segment and the segment its total; the number of kept elements in front of
+// the workgroup then comes from a chained scan across workgroups (each publishes its own count at
+// once and the running total as soon as it knows it; a successor sums the counts back to the
+// nearest running total); finally the ascending int32 positions are produced from the flag words
+// still held in registers, collected per segment in LDS and stored as contiguous runs.  All
+// integer work, bound by one read of the mask plus the write of the index.
 //
 // The chain lives in seg_ptr itself: seg_ptr[e], e the end of a workgroup's block of segments, is
 // the number of kept elements up to there — exactly the running total the next workgroup needs.
