@@ -162,3 +162,25 @@ def test_binding_refuses_cpu_tensors():
     with pytest.raises(TypeError):
         samo.samo_decompress(torch.zeros(4), torch.zeros(4, dtype=torch.int32), torch.zeros(2, dtype=torch.int32),
                              torch.zeros(8, dtype=torch.float16))
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/samo.h is a C header: it compiles on its own as C99 and as C++17, pedantically,
+    and a C translation unit can name every type and take the address of every entry point."""
+    import re
+    import subprocess
+    header = os.path.join(ROOT, "include", "samo.h")
+    names = sorted(set(re.findall(r"\b(samo_[a-z0-9_]+)\s*\(", open(header).read())))
+    assert "samo_fused_step_batched" in names and "samo_build_index" in names
+    src = tmp_path / "use_samo.c"
+    body = "\n".join("    p[%d] = (void (*)(void))%s;" % (i, n) for i, n in enumerate(names))
+    src.write_text('#include "samo.h"\n'
+                   "void (*p[%d])(void);\n" % len(names) +
+                   "int use(void) {\n"
+                   "    samo_adam_cfg a; samo_sgd_cfg s; samo_grad_stats g; samo_step_guard q; samo_index_job j; samo_layer l;\n"
+                   "    (void)a; (void)s; (void)g; (void)q; (void)j; (void)l;\n" + body + "\n    return SAMO_OK;\n}\n")
+    inc = "-I" + os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", inc, "-c", str(src),
+                           "-o", str(tmp_path / "use_samo.o")])
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-pedantic", inc, "-x", "c++", "-c",
+                           str(src), "-o", str(tmp_path / "use_samo_cpp.o")])
