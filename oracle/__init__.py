@@ -76,6 +76,13 @@ def _load():
         lib.samo_oracle_step.restype = None
         lib.samo_oracle_step.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, f32,
                                          f32, f32, f32, f32, f32, i32, i32]
+        lib.samo_oracle_compress_f32.restype = None
+        lib.samo_oracle_compress_f32.argtypes = [vp, vp, i64, f32, vp]
+        lib.samo_oracle_expand_f32.restype = None
+        lib.samo_oracle_expand_f32.argtypes = [vp, vp, i64, vp, i64]
+        lib.samo_oracle_step_fp32.restype = None
+        lib.samo_oracle_step_fp32.argtypes = [vp, vp, i64, vp, i64, vp, vp, vp, vp, f32,
+                                              f32, f32, f32, f32, f32, i32, i32]
         _lib = lib
     return _lib
 
@@ -265,6 +272,51 @@ def step(g: np.ndarray, n: int, idx: np.ndarray, p: np.ndarray, m: np.ndarray, v
                              cfg.lr, cfg.beta1, cfg.beta2, cfg.eps,
                              cfg.weight_decay, int(cfg.decoupled_wd), int(t))
     return w
+
+
+# ----------------------------------------------------------------- single-precision SAMO
+def compress_f32(dense: np.ndarray, idx: np.ndarray, factor: float = 1.0) -> np.ndarray:
+    """Values of a dense fp32 tensor at idx, times `factor` (one fp32 multiply)."""
+    dense = _arr(dense, np.float32)
+    idx = _arr(idx, np.int32)
+    _check_index(idx, dense.shape[0])
+    out = np.empty(idx.shape[0], np.float32)
+    _load().samo_oracle_compress_f32(_ptr(dense), _ptr(idx), idx.shape[0], np.float32(factor), _ptr(out))
+    return out
+
+
+def expand_f32(c: np.ndarray, idx: np.ndarray, n: int) -> np.ndarray:
+    """Dense fp32 tensor of n elements: c at idx, +0 elsewhere."""
+    c = _arr(c, np.float32)
+    idx = _arr(idx, np.int32)
+    if c.shape[0] != idx.shape[0]:
+        raise ValueError("shape mismatch")
+    _check_index(idx, n)
+    dense = np.empty(n, np.float32)
+    _load().samo_oracle_expand_f32(_ptr(c), _ptr(idx), idx.shape[0], _ptr(dense), n)
+    return dense
+
+
+def step_fp32(g32: np.ndarray, w32: np.ndarray, idx: np.ndarray, m: np.ndarray, v: np.ndarray,
+              grad_factor: float, cfg: AdamCfg, t: int) -> None:
+    """One single-precision optimizer phase of a layer: updates the dense w32 (kept positions
+    stepped, every other position +0) and the compressed m, v in place."""
+    g32 = _arr(g32, np.float32)
+    w32 = _arr(w32, np.float32, True)
+    idx = _arr(idx, np.int32)
+    m = _arr(m, np.float32, True)
+    v = _arr(v, np.float32, True)
+    n, nnz = w32.shape[0], idx.shape[0]
+    if g32.shape[0] != n or not (m.shape[0] == v.shape[0] == nnz):
+        raise ValueError("shape mismatch")
+    if t < 1:
+        raise ValueError("Adam's step counter starts at 1")
+    _check_index(idx, n)
+    gc = np.empty(nnz, np.float32)
+    pc = np.empty(nnz, np.float32)
+    _load().samo_oracle_step_fp32(_ptr(g32), _ptr(w32), n, _ptr(idx), nnz, _ptr(m), _ptr(v), _ptr(gc), _ptr(pc),
+                                  np.float32(grad_factor), cfg.lr, cfg.beta1, cfg.beta2, cfg.eps,
+                                  cfg.weight_decay, int(cfg.decoupled_wd), int(t))
 
 
 def _check_index(idx: np.ndarray, n: int) -> None:

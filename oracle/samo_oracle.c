@@ -25,7 +25,9 @@
  * (Section III-C); dense Adam on the masked tensor via torch.optim.Adam; the
  * closed form of the first Adam step; Eq. (1)-(5) values printed in Section
  * III-D; for the widened path (tests/test_oracle_next.py) numpy's half addition
- * and direct double->half cast, torch's clip_grad_norm_ and torch.optim.SGD.
+ * and direct double->half cast, torch's clip_grad_norm_ and torch.optim.SGD;
+ * for single precision (tests/test_oracle_fp32.py) torch.optim.Adam on the dense
+ * masked fp32 problem, numpy's fp32 multiply and the expand/compress identity.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -300,3 +302,43 @@ void samo_oracle_step(const uint16_t *g, uint16_t *w, int64_t n,
     samo_oracle_adam(p, m, v, gc, nnz, lr, beta1, beta2, eps, weight_decay, decoupled_wd, step);
     samo_oracle_decompress(p, idx, nnz, w, n);
 }
+
+/* ---- single-precision SAMO ------------------------------------------------------------------
+ * Section III notes that the optimizations also apply to single-precision training.  The paper
+ * gives no details; the reading taken: theta32 is the only copy of the parameters and stays dense
+ * with explicit zeros (it is what forward and backward use, Section III-C), the dense fp32
+ * gradient is compressed at ind, the optimizer state is compressed; there are no 16-bit copies
+ * and no loss scale (a gradient factor is kept for clipping).  One optimizer phase in the paper's
+ * order: compress the gradient, compress theta32, run the optimizer on the compressed tensors,
+ * expand theta32. */
+
+/* values at ind of a dense fp32 tensor, times `factor`: one fp32 multiply (exact for 1.0f) */
+void samo_oracle_compress_f32(const float *dense, const int32_t *idx, int64_t nnz, float factor, float *out)
+{
+    for (int64_t i = 0; i < nnz; ++i) {
+        volatile float t = dense[idx[i]] * factor;
+        out[i] = t;
+    }
+}
+
+/* inverse of compression for fp32: +0 everywhere, then the values at ind */
+void samo_oracle_expand_f32(const float *c, const int32_t *idx, int64_t nnz, float *dense, int64_t n)
+{
+    for (int64_t j = 0; j < n; ++j) dense[j] = 0.0f;
+    for (int64_t i = 0; i < nnz; ++i) dense[idx[i]] = c[i];
+}
+
+/* gc and pc are caller-provided scratch of nnz floats */
+void samo_oracle_step_fp32(const float *g32, float *w32, int64_t n,
+                           const int32_t *idx, int64_t nnz,
+                           float *m, float *v, float *gc, float *pc,
+                           float grad_factor,
+                           float lr, float beta1, float beta2, float eps,
+                           float weight_decay, int32_t decoupled_wd, int32_t step)
+{
+    samo_oracle_compress_f32(g32, idx, nnz, grad_factor, gc);
+    samo_oracle_compress_f32(w32, idx, nnz, 1.0f, pc);
+    samo_oracle_adam(pc, m, v, gc, nnz, lr, beta1, beta2, eps, weight_decay, decoupled_wd, step);
+    samo_oracle_expand_f32(pc, idx, nnz, w32, n);
+}
+
