@@ -191,6 +191,20 @@ def main():
               sum(4 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 2 * L.n for L in layers))
         entry("samo_fused_sgd_step_batched", time_entry(lambda: plan.samo_fused_sgd_step_batched(inv, samo.sgd_cfg(1e-4))),
               sum(20 * L.p.numel() + 4 * L.n if L.seg_ptr is not None else 20 * L.n for L in layers))
+        # single-precision SAMO on the same shapes and masks (its own arena: dense fp32 parameters and
+        # gradient, compressed m and v): 20 bytes per kept element + 12 per dense one, 28 per element of a dense layer
+        layers32 = samo.alloc_model_fp32([(L.n, L.p.numel(), L.seg_ptr is None) for L in layers], dev)
+        for L32, L in zip(layers32, layers):
+            if L.seg_ptr is not None:
+                L32.idx.copy_(L.idx)
+                L32.seg_ptr.copy_(L.seg_ptr)
+            L32.w32.zero_()
+            L32.g32.normal_(0.0, 1e-3)
+        plan32 = samo.Plan(layers32)
+        entry("samo_fused_step_fp32_batched", time_entry(lambda: plan32.samo_fused_step_fp32_batched(1.0, cfg(t + 1))),
+              sum(20 * L.p.numel() + 12 * L.n if L.seg_ptr is not None else 28 * L.n for L in layers))
+        plan32.close()
+        del plan32, layers32
         if n_indexed:
             entry("samo_build_index_batched", index_ms, index_bytes)
         nb = min(4 << 30, max(1 << 20, (fused_bytes // 2) & ~15))

@@ -17,6 +17,8 @@
  *   w        fp16[N]      dense half-precision parameters (theta16) with +0
  *                         stored explicitly at every pruned position
  *   g        fp16[N]      dense half-precision gradient as backward produced it
+ *   w32, g32 float[N]     single-precision SAMO only: dense fp32 parameters (zeros stored
+ *                         explicitly) and dense fp32 gradient
  *   seg_ptr  int32[ceil(N / SAMO_SEG_ELEMS) + 1]
  *                         seg_ptr[s] = #{ i : idx[i] < s * SAMO_SEG_ELEMS };
  *                         seg_ptr[last] = nnz.  Not in the paper: a small table
@@ -56,7 +58,7 @@
 extern "C" {
 #endif
 
-#define SAMO_ABI_VERSION 2
+#define SAMO_ABI_VERSION 3
 #define SAMO_SEG_ELEMS 1024 /* dense elements per seg_ptr entry */
 
 typedef int32_t samo_status;
@@ -208,6 +210,19 @@ samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, c
                                 const int32_t *d_seg_ptr, int64_t nnz, float *d_p, float *d_buf,
                                 float inv_loss_scale, const samo_sgd_cfg *h_cfg, void *stream);
 
+/* ---------------------------------------------------------------- single-precision SAMO
+ * Section III notes that the optimizations apply to single-precision training as well.  There
+ * theta32 is the only copy of the parameters and stays dense with explicit zeros (w32, n floats:
+ * what forward and backward use); the dense fp32 gradient g32 is read at the kept positions; the
+ * optimizer state m, v is compressed; there are no 16-bit copies and no loss scale.  One optimizer
+ * phase: for every kept position j = idx[i]:  g = g32[j] * grad_factor (one fp32 multiply; 1.0f
+ * unless the gradient is to be scaled), one Adam step on (w32[j], m[i], v[i]).  Every other
+ * element of w32[0..n) is +0 on exit, whatever it held.  grad_factor must be finite and > 0.
+ * Dense (unpruned) layer: d_idx == NULL, d_seg_ptr == NULL and nnz == n. */
+samo_status samo_fused_step_fp32(const float *d_g32, float *d_w32, int64_t n, const int32_t *d_idx,
+                                 const int32_t *d_seg_ptr, int64_t nnz, float *d_m, float *d_v,
+                                 float grad_factor, const samo_adam_cfg *h_cfg, void *stream);
+
 /* ---------------------------------------------------------------- whole-model (batched) forms
  * One launch covers every layer, so small layers do not pay a launch and a
  * tail each.  A plan is built once per pruning from a HOST array of layer
@@ -231,6 +246,8 @@ typedef struct {
     const uint16_t *g;
     float *gc;
     uint16_t *gc16;
+    float *w32;        /* single-precision SAMO: dense fp32 parameters (theta32 with explicit zeros) */
+    const float *g32;  /* single-precision SAMO: dense fp32 gradient */
 } samo_layer;
 
 typedef struct samo_plan samo_plan;
@@ -255,7 +272,8 @@ samo_status samo_gather_fp16_batched(const samo_plan *plan, int32_t accumulate, 
                                      samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
                                      void *stream);
 /* Statistics only, for callers that run the fully fused step: source selects what is read —
- * 0: the dense fp16 gradient g at idx, 1: gc16, 2: gc (fp32, already unscaled: pass 1.0f). */
+ * 0: the dense fp16 gradient g at idx, 1: gc16, 2: gc (fp32, already unscaled: pass 1.0f),
+ * 3: the dense fp32 gradient g32 at idx (single-precision SAMO; the factor plays grad_factor). */
 samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float inv_loss_scale,
                                     samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
                                     void *stream);
@@ -271,6 +289,11 @@ samo_status samo_adam_expand_batched(const samo_plan *plan, float inv_loss_scale
 samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_scale,
                                         const samo_sgd_cfg *h_cfg, const samo_step_guard *h_guard,
                                         void *stream);
+/* samo_fused_step_fp32 over every layer of the plan (descriptors with w32, g32, m, v; p is not used
+ * and may be NULL in a plan that serves only this entry). */
+samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_factor,
+                                         const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,
+                                         void *stream);
 
 /* ---------------------------------------------------------------- byte accounting (Section III-D, Eq. 1-5)  [host only]
  * paper_default = 20 * n_total; paper_samo = 24 * nnz_total + 2 * n_total;
@@ -288,8 +311,9 @@ samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void
 
 /* ---------------------------------------------------------------- environment (tuning and testing aids)
  * Read by the library, never required:
- *   SAMO_OCC_TILE_STEP, SAMO_OCC_TILE_DECOMP, SAMO_OCC_FLAT_GATHER, SAMO_OCC_FLAT_STATS,
- *   SAMO_OCC_FLAT_STEP   workgroups (waves for the flat kernels) resident per compute unit that a
+ *   SAMO_OCC_TILE_STEP, SAMO_OCC_TILE_STEP32, SAMO_OCC_TILE_DECOMP, SAMO_OCC_FLAT_GATHER,
+ *   SAMO_OCC_FLAT_STATS, SAMO_OCC_FLAT_STEP
+ *                        workgroups (waves for the flat kernels) resident per compute unit that a
  *                        launch of that kind aims at, overriding the built-in target; 0 = no cap.
  *                        Read once per process.
  *   SAMO_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it gives

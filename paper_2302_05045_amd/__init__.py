@@ -45,7 +45,7 @@ class LayerDesc(ctypes.Structure):
                 ("idx", ctypes.c_void_p), ("seg_ptr", ctypes.c_void_p),
                 ("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("gc", ctypes.c_void_p),
-                ("gc16", ctypes.c_void_p)]
+                ("gc16", ctypes.c_void_p), ("w32", ctypes.c_void_p), ("g32", ctypes.c_void_p)]
 
 
 class SgdCfg(ctypes.Structure):
@@ -99,6 +99,11 @@ _SIGNATURES = {
     "samo_fused_step": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_fused_step_fp32": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_float, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
+    "samo_fused_step_fp32_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+                                                      ctypes.POINTER(StepGuard), ctypes.c_void_p]),
     "samo_plan_create": (ctypes.c_int32, [ctypes.POINTER(LayerDesc), ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]),
     "samo_plan_destroy": (ctypes.c_int32, [ctypes.c_void_p]),
     "samo_plan_totals": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
@@ -137,7 +142,7 @@ def lib() -> ctypes.CDLL:
             fn = getattr(handle, name)
             fn.restype = res
             fn.argtypes = args
-        if handle.samo_abi_version() != 2:
+        if handle.samo_abi_version() != 3:
             raise ImportError("libsamo.so has an unexpected ABI version")
         _lib = handle
     return _lib
@@ -349,18 +354,31 @@ def samo_fused_step(g: torch.Tensor, w: torch.Tensor, idx: Optional[torch.Tensor
                                  _stream()), "samo_fused_step")
 
 
+def samo_fused_step_fp32(g32: torch.Tensor, w32: torch.Tensor, idx: Optional[torch.Tensor],
+                         seg_ptr: Optional[torch.Tensor], m: torch.Tensor, v: torch.Tensor, grad_factor: float,
+                         cfg: AdamCfg) -> None:
+    n, nnz = w32.numel(), m.numel()
+    _check(lib().samo_fused_step_fp32(_dev(g32, torch.float32, "g32", n), _dev(w32, torch.float32, "w32"), n,
+                                      _dev(idx, torch.int32, "idx", nnz),
+                                      _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)), nnz,
+                                      _dev(m, torch.float32, "m"), _dev(v, torch.float32, "v", nnz),
+                                      float(grad_factor), ctypes.byref(cfg), _stream()), "samo_fused_step_fp32")
+
+
 class Layer(NamedTuple):
     """Device tensors of one layer for the batched entry points (None where unused)."""
     n: int
     idx: Optional[torch.Tensor]
     seg_ptr: Optional[torch.Tensor]
-    p: torch.Tensor
+    p: Optional[torch.Tensor]
     m: Optional[torch.Tensor] = None
     v: Optional[torch.Tensor] = None
     w: Optional[torch.Tensor] = None
     g: Optional[torch.Tensor] = None
     gc: Optional[torch.Tensor] = None
     gc16: Optional[torch.Tensor] = None
+    w32: Optional[torch.Tensor] = None      # single-precision SAMO: dense fp32 parameters
+    g32: Optional[torch.Tensor] = None      # single-precision SAMO: dense fp32 gradient
 
 
 class GradStats:
@@ -424,16 +442,45 @@ def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, with_gc1
     return layers
 
 
+def alloc_model_fp32(shapes: Sequence[tuple], device, align: int = 256) -> list:
+    """The same for single-precision SAMO: per layer seg_ptr, idx, g32, m, v, w32 in one arena
+    (no compressed p, no 16-bit buffers); m and v start at zero."""
+    def rnd(x):
+        return (x + align - 1) // align * align
+    plan, total = [], 0
+    for n, nnz, dense in shapes:
+        if dense and nnz != n:
+            raise ValueError("a dense layer has nnz == n")
+        sizes = [("seg_ptr", 0 if dense else 4 * samo_seg_ptr_len(n), torch.int32),
+                 ("idx", 0 if dense else 4 * nnz, torch.int32), ("g32", 4 * n, torch.float32),
+                 ("m", 4 * nnz, torch.float32), ("v", 4 * nnz, torch.float32), ("w32", 4 * n, torch.float32)]
+        offs = {}
+        for name, nb, dt in sizes:
+            offs[name] = (total, nb, dt)
+            total += rnd(nb)
+        plan.append((n, dense, offs))
+    arena = torch.empty(max(total, 1), dtype=torch.uint8, device=device)
+    layers = []
+    for n, dense, offs in plan:
+        t = {name: arena[o:o + nb].view(dt) for name, (o, nb, dt) in offs.items()}
+        t["m"].zero_()
+        t["v"].zero_()
+        layers.append(Layer(n, None if dense else t["idx"], None if dense else t["seg_ptr"], None, t["m"], t["v"],
+                            w32=t["w32"], g32=t["g32"]))
+    return layers
+
+
 class Plan:
     """samo_plan: one launch per entry point over all layers of a model."""
 
     def __init__(self, layers: Sequence[Layer]):
         self._handle = ctypes.c_void_p()
         self._layers = list(layers)          # keeps the tensors alive
-        self.device = next((L.p.device for L in self._layers), torch.device("cuda", torch.cuda.current_device()))
+        self.device = next(((L.p if L.p is not None else L.m).device for L in self._layers),
+                           torch.device("cuda", torch.cuda.current_device()))
         descs = (LayerDesc * max(len(self._layers), 1))()
         for d, L in zip(descs, self._layers):
-            nnz = L.p.numel()
+            nnz = (L.p if L.p is not None else L.m).numel()      # a single-precision layer has no compressed p
             d.n, d.nnz = int(L.n), nnz
             d.idx = _dev(L.idx, torch.int32, "idx", nnz)
             d.seg_ptr = _dev(L.seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(L.n))
@@ -444,6 +491,8 @@ class Plan:
             d.g = _dev(L.g, _F16, "g", L.n)
             d.gc = _dev(L.gc, torch.float32, "gc", nnz)
             d.gc16 = _dev(L.gc16, _F16, "gc16", nnz)
+            d.w32 = _dev(L.w32, torch.float32, "w32", L.n)
+            d.g32 = _dev(L.g32, torch.float32, "g32", L.n)
         _check(lib().samo_plan_create(descs, len(self._layers), ctypes.byref(self._handle)), "samo_plan_create")
 
     def close(self) -> None:
@@ -500,6 +549,10 @@ class Plan:
     def samo_fused_step_batched(self, inv_loss_scale: float, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
         _check(lib().samo_fused_step_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg),
                                              self._guard_arg(guard), _stream()), "samo_fused_step_batched")
+
+    def samo_fused_step_fp32_batched(self, grad_factor: float, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
+        _check(lib().samo_fused_step_fp32_batched(self._handle, float(grad_factor), ctypes.byref(cfg),
+                                                  self._guard_arg(guard), _stream()), "samo_fused_step_fp32_batched")
 
     def samo_adam_expand_batched(self, inv_loss_scale: float, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
         _check(lib().samo_adam_expand_batched(self._handle, float(inv_loss_scale), ctypes.byref(cfg),

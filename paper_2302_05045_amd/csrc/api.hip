@@ -18,7 +18,8 @@ struct samo_plan {
     WgRec *d_chunks = nullptr;
     int64_t ntiles = 0, nchunks = 0;
     int64_t n_total = 0, nnz_total = 0;
-    bool has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true, has_gc16 = true;
+    bool has_p = true, has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true, has_gc16 = true;
+    bool has_w32 = true, has_g32 = true;
 };
 
 namespace {
@@ -274,7 +275,7 @@ samo_status samo_decompress(const float *d_p, const int32_t *d_idx, const int32_
     if ((!d_p && nnz > 0) || (!d_w && n > 0)) return SAMO_ERR_NULL;
     if (misaligned(d_p) || misaligned(d_w)) return SAMO_ERR_ALIGN;
     samo_layer L = {n, nnz, d_idx, d_seg_ptr, const_cast<float *>(d_p), nullptr, nullptr, d_w, nullptr, nullptr,
-                    nullptr};
+                    nullptr, nullptr, nullptr};
     OptK k;
     std::memset(&k, 0, sizeof(k));
     return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, single_tiles(L), 1.f, k,
@@ -289,7 +290,7 @@ samo_status samo_gather_grads(const uint16_t *d_g, int64_t n, const int32_t *d_i
     if (nnz > 0 && (!d_g || !d_gc)) return SAMO_ERR_NULL;
     if (misaligned(d_g) || misaligned(d_idx) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
-    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, d_gc, nullptr};
+    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, d_gc, nullptr, nullptr, nullptr};
     return hip_status(launch_gather(kOutF32, kGradDense, single(L, ceil_div(nnz, kChunk)), inv_loss_scale, 0, nullptr,
                                     as_stream(stream)));
 }
@@ -301,7 +302,7 @@ samo_status samo_gather_grads_fp16(const uint16_t *d_g, int64_t n, const int32_t
     if (!d_idx && nnz > 0 && nnz != n) return SAMO_ERR_NULL;
     if (nnz > 0 && (!d_g || !d_gc16)) return SAMO_ERR_NULL;
     if (misaligned(d_g) || misaligned(d_idx) || misaligned(d_gc16)) return SAMO_ERR_ALIGN;
-    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, nullptr, d_gc16};
+    samo_layer L = {n, nnz, d_idx, nullptr, nullptr, nullptr, nullptr, nullptr, d_g, nullptr, d_gc16, nullptr, nullptr};
     return hip_status(launch_gather(kOutF16, kGradDense, single(L, ceil_div(nnz, kChunk)), 1.f, accumulate != 0,
                                     nullptr, as_stream(stream)));
 }
@@ -314,7 +315,7 @@ samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc
     if (misaligned(d_p) || misaligned(d_m) || misaligned(d_v) || misaligned(d_gc)) return SAMO_ERR_ALIGN;
     OptK k;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
-    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_m, d_v, nullptr, nullptr, const_cast<float *>(d_gc), nullptr};
+    samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_m, d_v, nullptr, nullptr, const_cast<float *>(d_gc), nullptr, nullptr, nullptr};
     return hip_status(launch_flat_step(kOptAdam, single(L, ceil_div(nnz, kChunk)), k, kNoGuard, as_stream(stream)));
 }
 
@@ -327,7 +328,7 @@ samo_status samo_sgd_step(float *d_p, float *d_buf, const float *d_gc, int64_t n
     OptK k;
     if (samo_status s = make_sgd(h_cfg, &k)) return s;
     samo_layer L = {nnz, nnz, nullptr, nullptr, d_p, d_buf, nullptr, nullptr, nullptr, const_cast<float *>(d_gc),
-                    nullptr};
+                    nullptr, nullptr, nullptr};
     return hip_status(launch_flat_step(kOptSgd, single(L, ceil_div(nnz, kChunk)), k, kNoGuard, as_stream(stream)));
 }
 
@@ -340,7 +341,7 @@ samo_status samo_fused_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, const
     if (n > 0 && !d_g) return SAMO_ERR_NULL;
     OptK k;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
-    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr, nullptr};
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, d_g, nullptr, nullptr, nullptr, nullptr};
     return hip_status(launch_tile(kModeStep, kGradDense, kOptAdam, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
@@ -353,7 +354,7 @@ samo_status samo_adam_expand_step(const uint16_t *d_gc16, uint16_t *d_w, int64_t
         return s;
     OptK k;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
-    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, nullptr, nullptr, const_cast<uint16_t *>(d_gc16)};
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_m, d_v, d_w, nullptr, nullptr, const_cast<uint16_t *>(d_gc16), nullptr, nullptr};
     return hip_status(launch_tile(kModeStep, kGradC16, kOptAdam, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
@@ -368,7 +369,7 @@ samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, c
     if (n > 0 && !d_g) return SAMO_ERR_NULL;
     OptK k;
     if (samo_status s = make_sgd(h_cfg, &k)) return s;
-    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_buf, nullptr, d_w, d_g, nullptr, nullptr};
+    samo_layer L = {n, nnz, d_idx, d_seg_ptr, d_p, d_buf, nullptr, d_w, d_g, nullptr, nullptr, nullptr, nullptr};
     return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, single_tiles(L), inv_loss_scale, k,
                                   kNoGuard, as_stream(stream)));
 }
@@ -388,12 +389,14 @@ samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, sam
         const samo_layer &L = h_layers[l];
         st = check_sizes(L.n, L.nnz);
         if (st == SAMO_OK) st = check_index_args(L.idx, L.seg_ptr, L.n, L.nnz, /*allow_dense=*/true);
-        if (st == SAMO_OK && !L.p && L.nnz > 0) st = SAMO_ERR_NULL;
+        if (st == SAMO_OK && !L.p && !L.w32 && L.nnz > 0) st = SAMO_ERR_NULL;      // parameters in one form at least
         if (st == SAMO_OK && (misaligned(L.p) || misaligned(L.m) || misaligned(L.v) || misaligned(L.w) ||
-                              misaligned(L.g) || misaligned(L.gc) || misaligned(L.gc16)))
+                              misaligned(L.g) || misaligned(L.gc) || misaligned(L.gc16) || misaligned(L.w32) ||
+                              misaligned(L.g32)))
             st = SAMO_ERR_ALIGN;
         if (st != SAMO_OK) break;
         if (L.nnz > 0) {
+            plan->has_p &= L.p != nullptr;
             plan->has_m &= L.m != nullptr;
             plan->has_v &= L.v != nullptr;
             plan->has_gc &= L.gc != nullptr;
@@ -402,6 +405,8 @@ samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, sam
         if (L.n > 0) {
             plan->has_w &= L.w != nullptr;
             plan->has_g &= L.g != nullptr;
+            plan->has_w32 &= L.w32 != nullptr;
+            plan->has_g32 &= L.g32 != nullptr;
         }
         plan->n_total += L.n;
         plan->nnz_total += L.nnz;
@@ -537,7 +542,7 @@ extern "C" {
 samo_status samo_decompress_batched(const samo_plan *plan, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_w) return SAMO_ERR_PLAN;
+    if (!plan->has_w || !plan->has_p) return SAMO_ERR_PLAN;
     OptK k;
     std::memset(&k, 0, sizeof(k));
     return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, tiles_of(plan), 1.f, k, kNoGuard,
@@ -571,9 +576,9 @@ samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float
                                     void *stream)
 {
     if (!plan || !d_stats) return SAMO_ERR_NULL;
-    if (source < 0 || source > 2) return SAMO_ERR_ARG;
+    if (source < 0 || source > 3) return SAMO_ERR_ARG;
     if ((source == kGradDense && !plan->has_g) || (source == kGradC16 && !plan->has_gc16) ||
-        (source == kGradC32 && !plan->has_gc))
+        (source == kGradC32 && !plan->has_gc) || (source == kGradDense32 && !plan->has_g32))
         return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
@@ -584,7 +589,7 @@ samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg,
                               void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_m || !plan->has_v || !plan->has_gc) return SAMO_ERR_PLAN;
+    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_gc) return SAMO_ERR_PLAN;
     OptK k;
     GuardK guard;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
@@ -596,7 +601,7 @@ samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale,
                                     const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_m || !plan->has_v || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -610,7 +615,7 @@ samo_status samo_adam_expand_batched(const samo_plan *plan, float inv_loss_scale
                                      const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_m || !plan->has_v || !plan->has_w || !plan->has_gc16) return SAMO_ERR_PLAN;
+    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_w || !plan->has_gc16) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -624,7 +629,7 @@ samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_sc
                                         const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_m || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (!plan->has_p || !plan->has_m || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -632,6 +637,44 @@ samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_sc
     if (samo_status s = make_guard(h_guard, &guard)) return s;
     return hip_status(launch_tile(kModeStep, kGradDense, kOptSgd, tiles_of(plan), inv_loss_scale, k, guard,
                                   as_stream(stream)));
+}
+
+samo_status samo_fused_step_fp32(const float *d_g32, float *d_w32, int64_t n, const int32_t *d_idx,
+                                 const int32_t *d_seg_ptr, int64_t nnz, float *d_m, float *d_v, float grad_factor,
+                                 const samo_adam_cfg *h_cfg, void *stream)
+{
+    if (samo_status s = check_sizes(n, nnz)) return s;
+    if (samo_status s = check_index_args(d_idx, d_seg_ptr, n, nnz, /*allow_dense=*/true)) return s;
+    if (n > 0 && (!d_w32 || !d_g32)) return SAMO_ERR_NULL;
+    if (nnz > 0 && (!d_m || !d_v)) return SAMO_ERR_NULL;
+    if (misaligned(d_g32) || misaligned(d_w32) || misaligned(d_m) || misaligned(d_v)) return SAMO_ERR_ALIGN;
+    if (samo_status s = check_scale(grad_factor)) return s;
+    OptK k;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    samo_layer L;
+    std::memset(&L, 0, sizeof(L));
+    L.n = n;
+    L.nnz = nnz;
+    L.idx = d_idx;
+    L.seg_ptr = d_seg_ptr;
+    L.m = d_m;
+    L.v = d_v;
+    L.w32 = d_w32;
+    L.g32 = d_g32;
+    return hip_status(launch_tile_fp32(single_tiles(L), grad_factor, k, kNoGuard, as_stream(stream)));
+}
+
+samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_factor, const samo_adam_cfg *h_cfg,
+                                         const samo_step_guard *h_guard, void *stream)
+{
+    if (!plan) return SAMO_ERR_NULL;
+    if (!plan->has_m || !plan->has_v || !plan->has_w32 || !plan->has_g32) return SAMO_ERR_PLAN;
+    if (samo_status s = check_scale(grad_factor)) return s;
+    OptK k;
+    GuardK guard;
+    if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
+    if (samo_status s = make_guard(h_guard, &guard)) return s;
+    return hip_status(launch_tile_fp32(tiles_of(plan), grad_factor, k, guard, as_stream(stream)));
 }
 
 samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper_default, int64_t *paper_samo,

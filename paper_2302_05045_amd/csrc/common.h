@@ -32,6 +32,7 @@ constexpr int kMaxTile = kMaxTileSegs * kSeg;   // dense elements of the largest
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
 constexpr int kStatReduceGrid = 1024;    // workgroups of the first level of the gradient-statistics reduction
+constexpr int kTileUnrollFp32 = 4;      // the same for the single-precision tile kernel
 constexpr int kTileUnroll = 6;          // compressed elements in flight per thread in the tile kernels (4 and 6 tie on
                                         // uniform masks, 6 is 1 % ahead where dense stretches make long slices, 8 loses)
 
@@ -58,7 +59,7 @@ struct GuardK {
 };
 
 enum { kModeDecompress = 0, kModeStep = 1 };
-enum { kGradDense = 0, kGradC16 = 1, kGradC32 = 2 };   // where a step reads its gradient
+enum { kGradDense = 0, kGradC16 = 1, kGradC32 = 2, kGradDense32 = 3 };   // where a step / the statistics read the gradient
 enum { kOptAdam = 0, kOptSgd = 1 };
 enum { kOutF32 = 0, kOutF16 = 1, kOutNone = 2 };        // what the flat gather kernel writes
 
@@ -121,6 +122,7 @@ hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_r
                                   int64_t total, WgRec *d_recs, hipStream_t s);
 hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
                        const GuardK &guard, hipStream_t s);
+hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s);
 hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale, int accumulate,
                          StatPartial *partials, hipStream_t s);
 hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const GuardK &guard, hipStream_t s);

@@ -289,6 +289,121 @@ tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guar
         sparse_tile<MODE, GSRC, OPT, T>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w);
 }
 
+// ------------------------------------------------------------------ single-precision tile kernel
+// The same tile scheme with theta32 as the dense side: the kept values of the tile are read from
+// the dense fp32 parameters themselves, stepped, and dropped into a zero-filled fp32 image of the
+// tile in LDS, which leaves as whole 16-byte non-temporal stores — pruned positions come out +0,
+// the optimizer state m, v is the only compressed fp32 traffic.
+template <int T>
+__device__ __forceinline__ void dense_tile_fp32(const samo_layer &L, int64_t base, int len, float factor, float coef,
+                                                const OptK &k)
+{
+    const int tid = threadIdx.x;
+    float4 *__restrict__ W = reinterpret_cast<float4 *>(L.w32 + base);
+    float4 *__restrict__ M = reinterpret_cast<float4 *>(L.m + base);
+    float4 *__restrict__ V = reinterpret_cast<float4 *>(L.v + base);
+    const f32x4 *__restrict__ G = reinterpret_cast<const f32x4 *>(L.g32 + base);
+    const int nvec = len / 4;
+    for (int o = tid; o < nvec; o += T) {
+        float4 p = W[o], m = M[o], v = V[o];
+        const f32x4 g = __builtin_nontemporal_load(G + o);
+        adam_update(p.x, m.x, v.x, (g.x * factor) * coef, k.adam);
+        adam_update(p.y, m.y, v.y, (g.y * factor) * coef, k.adam);
+        adam_update(p.z, m.z, v.z, (g.z * factor) * coef, k.adam);
+        adam_update(p.w, m.w, v.w, (g.w * factor) * coef, k.adam);
+        W[o] = p;
+        M[o] = m;
+        V[o] = v;
+    }
+    for (int e = nvec * 4 + tid; e < len; e += T) {                  // ragged end of the layer
+        float pe = L.w32[base + e], me = L.m[base + e], ve = L.v[base + e];
+        adam_update(pe, me, ve, (L.g32[base + e] * factor) * coef, k.adam);
+        L.w32[base + e] = pe;
+        L.m[base + e] = me;
+        L.v[base + e] = ve;
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void sparse_tile_fp32(const samo_layer &L, int s0, int nsegs, int64_t base, int len,
+                                                 float factor, float coef, const OptK &k, float *lds_f)
+{
+    const int tid = threadIdx.x;
+    float4 *l4 = reinterpret_cast<float4 *>(lds_f);
+    for (int o = tid; o < (len + 3) / 4; o += T) l4[o] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int c0 = L.seg_ptr[s0];
+    const int c1 = L.seg_ptr[s0 + nsegs];
+    __syncthreads();
+
+    const int cnt = c1 - c0;
+    const int32_t *__restrict__ IDX = L.idx + c0;
+    float *__restrict__ M = L.m + c0;
+    float *__restrict__ V = L.v + c0;
+    const float *__restrict__ G = L.g32;
+    const float *W = L.w32;                  // read at the kept positions here, rewritten as a whole tile below
+    const int ibase = (int)base;
+
+    constexpr int U = kTileUnrollFp32;
+    for (int r0 = tid; r0 < cnt; r0 += U * T) {
+        int j[U];
+        float pp[U], mm[U], vv[U], gg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u * T;
+            j[u] = ibase; pp[u] = 0.f; mm[u] = 0.f; vv[u] = 0.f; gg[u] = 0.f;
+            if (r < cnt) {
+                j[u] = IDX[r];
+                mm[u] = M[r];
+                vv[u] = V[r];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (r0 + u * T < cnt) {
+                gg[u] = __builtin_nontemporal_load(G + j[u]);
+                pp[u] = W[j[u]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u * T;
+            if (r < cnt) {
+                adam_update(pp[u], mm[u], vv[u], (gg[u] * factor) * coef, k.adam);
+                M[r] = mm[u];
+                V[r] = vv[u];
+                lds_f[j[u] - ibase] = pp[u];
+            }
+        }
+    }
+    __syncthreads();                          // every read of this tile of w32 has happened
+
+    float *Wout = L.w32 + base;              // aliases W: no restrict
+    const int nvec = len / 4;
+    for (int o = tid; o < nvec; o += T) store_f4_stream(Wout + 4 * o, l4[o]);
+    for (int e = nvec * 4 + tid; e < len; e += T) Wout[e] = lds_f[e];
+}
+
+template <int T>
+__global__ void __launch_bounds__(T)
+tile_fp32_kernel(const LaunchSet ls, float factor, const OptK k, const GuardK guard)
+{
+    __shared__ __attribute__((aligned(16))) float lds_f[kMaxTile];
+    bool skip;
+    const float coef = guard_coef(guard, &skip);
+    if (skip) return;
+    samo_layer L;
+    int s0, nsegs;
+    pick_tile(ls, &L, &s0, &nsegs);
+    if (nsegs <= 0) return;
+    const int64_t base = (int64_t)s0 * kSeg;
+    const int64_t rest = L.n - base;
+    const int len = rest < (int64_t)nsegs * kSeg ? (int)rest : nsegs * kSeg;
+    if (L.seg_ptr == nullptr)
+        dense_tile_fp32<T>(L, base, len, factor, coef, k);
+    else
+        sparse_tile_fp32<T>(L, s0, nsegs, base, len, factor, coef, k, lds_f);
+}
+
 // ------------------------------------------------------------------ statistics helpers
 // Sum over the 64 lanes of a wave, the same value returned to every lane.  Data-parallel
 // primitives move the operands between lanes inside the vector ALU (row shifts within 16 lanes,
@@ -367,12 +482,20 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
     const int cnt = (nnz - i >= 4) ? 4 : (nnz - i > 0 ? (int)(nnz - i) : 0);
     uint16_t hb[4] = {0, 0, 0, 0};
     float fv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (src == kGradC32) {
+    if (src == kGradC32 || (src == kGradDense32 && identity)) {
+        const float *S = (src == kGradC32) ? L.gc : L.g32;
         if (cnt == 4) {
-            const float4 q = *reinterpret_cast<const float4 *>(L.gc + i);
+            const float4 q = *reinterpret_cast<const float4 *>(S + i);
             fv[0] = q.x; fv[1] = q.y; fv[2] = q.z; fv[3] = q.w;
         } else {
-            for (int e = 0; e < cnt; ++e) fv[e] = L.gc[i + e];
+            for (int e = 0; e < cnt; ++e) fv[e] = S[i + e];
+        }
+    } else if (src == kGradDense32) {                        // dense fp32 gradient at the kept positions
+        if (cnt == 4) {
+            const int4 j = *reinterpret_cast<const int4 *>(L.idx + i);
+            fv[0] = L.g32[j.x]; fv[1] = L.g32[j.y]; fv[2] = L.g32[j.z]; fv[3] = L.g32[j.w];
+        } else {
+            for (int e = 0; e < cnt; ++e) fv[e] = L.g32[L.idx[i + e]];
         }
     } else if (src == kGradC16 || identity) {
         const uint16_t *S = (src == kGradC16) ? L.gc16 : L.g;
@@ -418,7 +541,7 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
             for (int e = 0; e < cnt; ++e) L.gc16[i + e] = hb[e];
         }
     }
-    if (src != kGradC32) {
+    if (src != kGradC32 && src != kGradDense32) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) fv[e] = half_bits_to_float(hb[e]) * inv_scale;
     } else {
@@ -672,7 +795,7 @@ static int occ_flat_gather(int src, float keep, bool with_stats)
     static const int forced_stats = env_int("SAMO_OCC_FLAT_STATS", -1);
     if (with_stats && forced_stats >= 0) return forced_stats;
     if (!with_stats && forced >= 0) return forced;
-    if (src != kGradDense) return with_stats ? 20 : 12;
+    if (src != kGradDense && src != kGradDense32) return with_stats ? 20 : 12;
     const float per_wave = 1024.f + 512.f / (keep > 0.01f ? keep : 0.01f);
     float t = 75.f * 1024.f / per_wave;
     if (t < 13.f) t = 13.f;
@@ -726,6 +849,21 @@ hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_r
     if (total <= 0) return hipSuccess;
     build_tile_recs_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, s>>>(d_layers, d_rec_start,
                                                                                               num_layers, total, d_recs);
+    return hipGetLastError();
+}
+
+static int occ_tile_step_fp32()
+{
+    static const int forced = env_int("SAMO_OCC_TILE_STEP32", -1);
+    return forced >= 0 ? forced : 3;          // a tile carries twice the dense bytes of the fp16 path: half the workgroups
+                                              // (measured at 90 %: 6.1 TB/s with 3 per CU, 5.6 with 2, 5.0 with 4)
+}
+
+hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s)
+{
+    if (ls.wgs <= 0) return hipSuccess;
+    const int pad = lds_pad_for(occ_tile_step_fp32(), kMaxTile * 4);
+    tile_fp32_kernel<kTileThreads><<<dim3((unsigned)ls.wgs), dim3(kTileThreads), pad, s>>>(ls, factor, k, guard);
     return hipGetLastError();
 }
 

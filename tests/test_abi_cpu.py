@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_abi_version_and_strings():
     L = samo.lib()
-    assert L.samo_abi_version() == 2
+    assert L.samo_abi_version() == 3
     assert samo.status_string(0) == "ok"
     for s in range(-6, 0):
         assert samo.status_string(s) not in ("ok", "unknown status")
