@@ -51,6 +51,13 @@ def grads_fp16(n: int, seed: int, step: int = 1, loss_scale: float = LOSS_SCALE)
     return _to_fp16_bits(g)
 
 
+def grads_fp32(n: int, seed: int, step: int = 1) -> np.ndarray:
+    """Dense fp32 gradient ~ N(0, 1e-3) for single-precision SAMO (no loss scale), fresh per step."""
+    g = _rng(seed, _STREAM_G, step).standard_normal(n, dtype=np.float32)
+    g *= np.float32(G_STD)
+    return g
+
+
 # ------------------------------------------------------------------ masks (uint8, != 0 keeps)
 def bernoulli_mask(n: int, keep: float, seed: int) -> np.ndarray:
     return (_rng(seed, _STREAM_MASK).random(n) < keep).astype(np.uint8)

@@ -120,6 +120,46 @@ def test_gpt350m_unfused_then_fused():
     model.check(2)
 
 
+def test_gpt2p7b_single_precision_slice():
+    """Eight layers (32 matrices, 629 M elements) of the 2.7B shape at 90 % through the batched
+    single-precision step, two steps, every element against the oracle."""
+    specs = si.config("gpt2.7b", 0.9, layers=8)
+    host, masks = [], []
+
+    def consume(i, data):
+        idx = oracle.build_index(data.mask)
+        w = np.where(data.mask != 0, data.w32, np.float32(0)).astype(np.float32)
+        host.append([data.spec, data.mask, idx, w, np.zeros(idx.shape[0], np.float32), np.zeros(idx.shape[0], np.float32)])
+        masks.append(torch.from_numpy(data.mask).to(DEV))
+
+    si.generate(specs, consume, workers=12)
+    built = samo.samo_build_index_many(masks)
+    del masks
+    layers = samo.alloc_model_fp32([(ix.n, ix.nnz, False) for ix in built], DEV)
+    for L, ix, h in zip(layers, built, host):
+        assert np.array_equal(ix.idx.cpu().numpy(), h[2]), h[0].name
+        L.idx.copy_(ix.idx)
+        L.seg_ptr.copy_(ix.seg_ptr)
+        dirty = h[3].copy()
+        dirty[h[1] == 0] = 5.0                                    # garbage at pruned positions goes away
+        L.w32.copy_(torch.from_numpy(dirty))
+    del built
+    plan = samo.Plan(layers)
+    for t in (1, 2):
+        for L, h in zip(layers, host):
+            L.g32.copy_(torch.from_numpy(si.grads_fp32(h[0].n, h[0].seed, t)))
+        plan.samo_fused_step_fp32_batched(1.0, samo.adam_cfg(t, **si.ADAM))
+        for L, h in zip(layers, host):
+            spec, mask, idx, w, m, v = h
+            oracle.step_fp32(si.grads_fp32(spec.n, spec.seed, t), w, idx, m, v, 1.0, OCFG, t)
+            got = L.w32.cpu().numpy()
+            assert_close(got[idx], w[idx], "%s w32 t=%d" % (spec.name, t))
+            assert not got.view(np.uint32)[mask == 0].any(), spec.name
+            assert_close(L.m.cpu().numpy(), m, "%s m t=%d" % (spec.name, t))
+            assert_close(L.v.cpu().numpy(), v, "%s v t=%d" % (spec.name, t))
+    plan.close()
+
+
 @pytest.mark.parametrize("sparsity", [0.8, 0.95])
 def test_gpt2p7b_sparsity_sweep_slice(sparsity):
     """Eight layers (32 matrices) of the 2.7B shape at the other sparsities of the sweep."""
