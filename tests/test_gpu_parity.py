@@ -419,6 +419,36 @@ def test_plan_tiles_cover_random_piecewise_masks(seed):
     plan.close()
 
 
+def test_checkpoint_resume_from_the_compressed_state(tmp_path):
+    """The compressed state (idx, p, m, v and the step counter) is the whole checkpoint: theta16 is
+    recomputed by expansion, seg_ptr from idx, and training continues bit for bit."""
+    h = _layer(150_001, 0.1, 61)
+    d = DevLayer(h)
+    for t in (1, 2):
+        d.set_grads(h.grads(t))
+        samo.samo_fused_step(d.g, d.w, d.idx, d.seg_ptr, d.p, d.m, d.v, INV, samo.adam_cfg(t, **si.ADAM))
+    path = tmp_path / "ckpt.npz"
+    np.savez(path, idx=d.idx.cpu().numpy(), p=d.p.cpu().numpy(), m=d.m.cpu().numpy(), v=d.v.cpu().numpy(), t=2, n=h.n)
+    w_before = host_bits(d.w).copy()
+    d.set_grads(h.grads(3))
+    samo.samo_fused_step(d.g, d.w, d.idx, d.seg_ptr, d.p, d.m, d.v, INV, samo.adam_cfg(3, **si.ADAM))
+
+    ck = np.load(path)
+    n = int(ck["n"])
+    idx = dev_i32(ck["idx"])
+    seg_ptr = samo.samo_build_seg_ptr(idx, n)
+    assert samo.samo_validate_index(idx, n, seg_ptr)
+    p, m, v = dev_f32(ck["p"]), dev_f32(ck["m"]), dev_f32(ck["v"])
+    w = nan_f16(n)
+    samo.samo_decompress(p, idx, seg_ptr, w)
+    assert np.array_equal(host_bits(w), w_before)                 # theta16 is recomputable
+    g = nan_f16(n)
+    g.copy_(dev_f16_bits(h.grads(3)))
+    samo.samo_fused_step(g, w, idx, seg_ptr, p, m, v, INV, samo.adam_cfg(int(ck["t"]) + 1, **si.ADAM))
+    assert torch.equal(p, d.p) and torch.equal(m, d.m) and torch.equal(v, d.v)
+    assert torch.equal(w.view(torch.int16), d.w.view(torch.int16))
+
+
 def test_plan_reports_missing_buffers():
     h = _layer(5000, 0.2, 9)
     d = DevLayer(h)                                     # no gc
