@@ -120,3 +120,19 @@ def test_index_preconditions_are_checked():
         oracle.decompress(p, np.array([2, 1], np.int32), 4)    # descending
     with pytest.raises(ValueError):
         oracle.decompress(p, np.array([0, 4], np.int32), 4)    # out of range
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle's C functions, built with -fsanitize=address,undefined and driven on exact-size
+    heap buffers (tests/oracle_sanitizer_driver.c): no out-of-bounds access, no undefined arithmetic."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_san")
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c99", "-ffp-contract=off", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-static-libasan", os.path.join(root, "oracle", "samo_oracle.c"),
+                           os.path.join(root, "tests", "oracle_sanitizer_driver.c"), "-lm", "-o", exe])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
+    out = subprocess.run([exe], capture_output=True, text=True, env=env)
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert out.stdout.startswith("checksum ")
