@@ -1,9 +1,9 @@
 // Mask -> index construction (the paper's ind_i, Section III and III-B) for gfx950.
 //
 // The pruner's output arrives as a byte mask over the flattened layer.  The mask is read ONCE.
-// A workgroup of four wavefronts owns 64 consecutive segments of SAMO_SEG_ELEMS = 1024 mask
-// bytes; a wavefront takes sixteen of them, every lane loading 16 bytes of each, so a segment is
-// one coalesced 1 KiB access and sixteen are in flight per lane.  The kept bytes are counted per
+// A workgroup of eight wavefronts owns 64 consecutive segments of SAMO_SEG_ELEMS = 1024 mask
+// bytes; a wavefront takes eight of them, every lane loading 16 bytes of each, so a segment is
+// one coalesced 1 KiB access and eight are in flight per lane.  The kept bytes are counted per
 // lane (popcount of a 16-bit flag word) and scanned across the wave, which gives every lane its
 // offset within the segment and the segment its total; the number of kept elements in front of
 // the workgroup then comes from a chained scan across workgroups (each publishes its own count at
@@ -24,7 +24,8 @@
 namespace samo {
 namespace {
 
-constexpr int kWavesPerWg = kThreads / 64;
+constexpr int kIndexThreads = 512;        // index_kernel: eight wavefronts per workgroup
+constexpr int kWavesPerWg = kIndexThreads / 64;
 
 // bit (8*b + 7) set for every non-zero byte b of x
 __device__ __forceinline__ uint32_t nonzero_byte_flags(uint32_t x)
@@ -99,8 +100,10 @@ __device__ __forceinline__ int find_job(const IndexBatch &batch, int wg)
 // in flight before anything is reduced, and the per-lane counts travel through the wave scans
 // packed two to a register — a count is at most 1024, a 16-bit field is enough.
 constexpr int kSegsPerLoad = 4;
-constexpr int kRounds = 4;                // rounds of four segments a wave takes: 64 KiB of mask per workgroup
-                                          // (measured: 16 KiB blocks are twice as slow — the chain is per block)
+constexpr int kRounds = 2;                // rounds of four segments a wave takes: 64 KiB of mask per workgroup
+                                          // (measured: 16 KiB blocks are twice as slow — the chain is per block;
+                                          // eight waves x 2 rounds need half the registers of four waves x 4 and
+                                          // are 2-3 % faster)
 constexpr int kSegsPerWave = kSegsPerLoad * kRounds;
 constexpr int kSegsPerWg = kSegsPerWave * kWavesPerWg;
 static_assert(kSegsPerWg <= 64, "the block's segment counts are scanned by one wave");
@@ -176,7 +179,7 @@ __device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t
     return prefix;
 }
 
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kIndexThreads)
 index_kernel(const IndexBatch batch, int fill)
 {
     __shared__ int sh_ticket;
@@ -319,7 +322,7 @@ hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s)
     const int wgs = batch.wg_start[batch.num];
     const int init_threads = wgs > batch.num ? wgs : batch.num;
     index_init_kernel<<<dim3((unsigned)ceil_div(init_threads, kThreads)), dim3(kThreads), 0, s>>>(batch);
-    if (wgs > 0) index_kernel<<<dim3((unsigned)wgs), dim3(kThreads), 0, s>>>(batch, fill ? 1 : 0);
+    if (wgs > 0) index_kernel<<<dim3((unsigned)wgs), dim3(kIndexThreads), 0, s>>>(batch, fill ? 1 : 0);
     return hipGetLastError();
 }
 
