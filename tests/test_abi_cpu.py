@@ -184,3 +184,32 @@ def test_header_is_plain_c(tmp_path):
                            "-o", str(tmp_path / "use_samo.o")])
     subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-pedantic", inc, "-x", "c++", "-c",
                            str(src), "-o", str(tmp_path / "use_samo_cpp.o")])
+
+
+def test_host_side_of_the_library_under_sanitizers(tmp_path):
+    """The library's host code (argument validation, status strings, byte accounting) built with
+    AddressSanitizer and UBSan and driven through every entry point with arguments it must reject
+    before enqueueing anything (tests/abi_sanitizer_driver.c): no GPU needed, nothing dereferenced."""
+    import subprocess
+    from paper_2302_05045_amd import _build
+    exe = str(tmp_path / "abi_san")
+    obj = str(tmp_path / "driver.o")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    clang = os.path.join(os.path.dirname(os.path.realpath(hipcc)), "..", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    inc = ["-I", os.path.join(ROOT, "include")]
+    # the driver is C (it also checks that the header serves a C caller), same compiler family as
+    # hipcc so that both halves share one sanitizer runtime
+    subprocess.check_call([clang, "-std=c99", "-O1", "-g", "-fsanitize=address,undefined", "-Wall", "-Werror"] + inc +
+                          ["-c", os.path.join(ROOT, "tests", "abi_sanitizer_driver.c"), "-o", obj])
+    srcs = [os.path.join(_build.CSRC, s) for s in _build.SOURCES]
+    cmd = [hipcc, "-O1", "-g", "-std=c++17", "--offload-arch=gfx950",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"] + inc + \
+          ["-I", _build.CSRC] + srcs + ["-x", "none", obj, "-o", exe]
+    subprocess.check_call(cmd, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    out = subprocess.run([exe], capture_output=True, text=True,
+                         env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0:protect_shadow_gap=0"))
+    assert out.returncode == 0, (out.stdout + out.stderr)[-3000:]
+    assert "all rejected as documented" in out.stdout
