@@ -319,6 +319,65 @@ def step_fp32(g32: np.ndarray, w32: np.ndarray, idx: np.ndarray, m: np.ndarray, 
                                   cfg.weight_decay, int(cfg.decoupled_wd), int(t))
 
 
+# ----------------------------------------------------------------- compression in the backward pass
+def _f16_matrix(bits: np.ndarray, rows: int, cols: int) -> np.ndarray:
+    bits = _arr(bits, np.uint16)
+    if bits.shape[0] != rows * cols:
+        raise ValueError("matrix of %d x %d needs %d elements, got %d" % (rows, cols, rows * cols, bits.shape[0]))
+    return bits.view(np.float16).reshape(rows, cols).astype(np.float64)
+
+
+def linear_weight_grad(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_features: int) -> np.ndarray:
+    """Gradient of a fully connected layer's weight (Section II-A: Y = X W^T for W of shape
+    out x in): dW[o, i] = sum over tokens t of dY[t, o] * X[t, i], in double precision from the
+    fp16 operands (dy: tokens x out, x: tokens x in, both row-major fp16 bit patterns).
+    Returned flattened row-major, as the layer's index counts positions."""
+    a = _f16_matrix(dy, tokens, out_features)
+    b = _f16_matrix(x, tokens, in_features)
+    return (a.T @ b).reshape(-1)
+
+
+def linear_weight_grad_magnitude(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int,
+                                 in_features: int) -> np.ndarray:
+    """sum_t |dY[t, o]| * |X[t, i]|: what the rounding error of any summation order of
+    linear_weight_grad is proportional to (used by tests to size their tolerance)."""
+    a = np.abs(_f16_matrix(dy, tokens, out_features))
+    b = np.abs(_f16_matrix(x, tokens, in_features))
+    return (a.T @ b).reshape(-1)
+
+
+def wgrad_compress(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_features: int,
+                   idx: np.ndarray) -> np.ndarray:
+    """What the backward pass followed by compression leaves (Section III-C: the dense fp16
+    gradient of a layer is compressed as soon as it is produced): the weight gradient rounded
+    once to fp16, taken at idx.  Returns fp16 bit patterns."""
+    idx = _arr(idx, np.int32)
+    _check_index(idx, out_features * in_features)
+    dense = linear_weight_grad(dy, x, tokens, out_features, in_features)
+    with np.errstate(over="ignore"):
+        return dense[idx].astype(np.float16).view(np.uint16)
+
+
+def wgrad_at(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_features: int,
+             positions: np.ndarray) -> tuple:
+    """linear_weight_grad and its magnitude sum at a few flattened positions only, one dot product
+    per position (for layers too large to form densely on the host)."""
+    a = _arr(dy, np.uint16).view(np.float16).reshape(tokens, out_features)
+    b = _arr(x, np.uint16).view(np.float16).reshape(tokens, in_features)
+    positions = np.asarray(positions, np.int64)
+    if positions.size and (positions.min() < 0 or positions.max() >= out_features * in_features):
+        raise ValueError("position outside the weight matrix")
+    rows, cols = positions // in_features, positions % in_features
+    val = np.empty(positions.shape[0], np.float64)
+    mag = np.empty(positions.shape[0], np.float64)
+    for k in range(positions.shape[0]):
+        u = a[:, rows[k]].astype(np.float64)
+        w = b[:, cols[k]].astype(np.float64)
+        val[k] = np.dot(u, w)
+        mag[k] = np.dot(np.abs(u), np.abs(w))
+    return val, mag
+
+
 def _check_index(idx: np.ndarray, n: int) -> None:
     if idx.shape[0] == 0:
         return

@@ -20,7 +20,7 @@ ADAM = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, decoupl
 W_STD = 0.02
 G_STD = 1e-3
 
-_STREAM_W, _STREAM_MASK, _STREAM_G, _STREAM_ROWS, _STREAM_P = range(5)
+_STREAM_W, _STREAM_MASK, _STREAM_G, _STREAM_ROWS, _STREAM_P, _STREAM_X, _STREAM_DY = range(7)
 
 
 def _rng(seed: int, stream: int, sub: int = 0) -> np.random.Generator:
@@ -56,6 +56,23 @@ def grads_fp32(n: int, seed: int, step: int = 1) -> np.ndarray:
     g = _rng(seed, _STREAM_G, step).standard_normal(n, dtype=np.float32)
     g *= np.float32(G_STD)
     return g
+
+
+def activations_fp16(tokens: int, features: int, seed: int, step: int = 1) -> np.ndarray:
+    """Input of a fully connected layer, tokens x features row-major fp16 bits ~ N(0, 1)
+    (what a layer norm hands to the layer)."""
+    x = _rng(seed, _STREAM_X, step).standard_normal(tokens * features, dtype=np.float32)
+    return _to_fp16_bits(x)
+
+
+def output_grads_fp16(tokens: int, features: int, seed: int, step: int = 1,
+                      loss_scale: float = LOSS_SCALE) -> np.ndarray:
+    """Gradient arriving at a fully connected layer's output, tokens x features row-major fp16
+    bits ~ N(0, G_STD * loss_scale / sqrt(tokens)), so that the weight gradient it forms with
+    activations_fp16 has the spread of grads_fp16."""
+    dy = _rng(seed, _STREAM_DY, step).standard_normal(tokens * features, dtype=np.float32)
+    dy *= np.float32(G_STD * loss_scale / np.sqrt(float(tokens)))
+    return _to_fp16_bits(dy)
 
 
 # ------------------------------------------------------------------ masks (uint8, != 0 keeps)
