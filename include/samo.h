@@ -295,6 +295,36 @@ samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_facto
                                          const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,
                                          void *stream);
 
+/* ---------------------------------------------------------------- compression inside the backward pass
+ * (Section III-C: a layer's dense gradient is compressed as soon as the backward
+ * pass has produced it; Section V, discussion of the compute overhead: fusing
+ * that compression into the backward kernel is what would remove it.)
+ * Weight gradient of a fully connected layer Y = X W^T with W of out x in
+ * (Section II-A), formed and compressed in one kernel: with
+ *   dW[o][i] = sum over t < tokens of dY[t][o] * X[t][i]   (fp16 products, fp32 sums),
+ * position o * in + i of the layer, and h = fp16(dW) rounded once to nearest
+ * even (the value the dense fp16 gradient tensor would have held),
+ *   samo_wgrad_gather:       gc[k]   = float(h[idx[k]]) * inv_loss_scale
+ *   samo_wgrad_gather_fp16:  gc16[k] = h[idx[k]], or fp16(gc16[k] + h[idx[k]]) if accumulate != 0
+ * i.e. samo_gather_grads / samo_gather_grads_fp16 applied to that tensor, which
+ * is never written to memory.  The order of the fp32 summation over tokens is
+ * the kernel's own: results agree with any other order within tokens * 2^-23 *
+ * sum_t |dY[t][o] * X[t][i]| before the rounding to fp16.
+ * d_dy: device, tokens x out row-major fp16; d_x: device, tokens x in row-major
+ * fp16; both read only and 16-byte aligned.  out and in must be multiples of 8
+ * with out * in < 2^31; tokens >= 0 (0: every dW is +0).  d_idx / d_seg_ptr
+ * describe the layer of n = out * in elements as everywhere else; d_idx may be
+ * NULL only when nnz == out * in (unpruned layer), d_seg_ptr is required
+ * whenever d_idx is given.  Nothing is written when nnz == 0. */
+samo_status samo_wgrad_gather(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens,
+                              int64_t out, int64_t in, const int32_t *d_idx,
+                              const int32_t *d_seg_ptr, int64_t nnz, float inv_loss_scale,
+                              float *d_gc, void *stream);
+samo_status samo_wgrad_gather_fp16(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens,
+                                   int64_t out, int64_t in, const int32_t *d_idx,
+                                   const int32_t *d_seg_ptr, int64_t nnz, uint16_t *d_gc16,
+                                   int32_t accumulate, void *stream);
+
 /* ---------------------------------------------------------------- byte accounting (Section III-D, Eq. 1-5)  [host only]
  * paper_default = 20 * n_total; paper_samo = 24 * nnz_total + 2 * n_total;
  * resident = what this library's fused pipeline keeps allocated:

@@ -126,6 +126,12 @@ _SIGNATURES = {
                                                      ctypes.POINTER(StepGuard), ctypes.c_void_p]),
     "samo_memory_model": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+    "samo_wgrad_gather": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                           ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]),
+    "samo_wgrad_gather_fp16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                                ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                                ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]),
     "samo_stream_copy": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
 }
 
@@ -301,6 +307,42 @@ def samo_gather_grads_fp16(g: torch.Tensor, idx: Optional[torch.Tensor], gc16: t
     _check(lib().samo_gather_grads_fp16(_dev(g, _F16, "g"), n, _dev(idx, torch.int32, "idx", nnz), nnz,
                                         _dev(gc16, _F16, "gc16"), int(bool(accumulate)), _stream()),
            "samo_gather_grads_fp16")
+
+
+def _dev_matrix(t: torch.Tensor, name: str) -> tuple:
+    """(device pointer, rows, columns) of a contiguous 2-D fp16 CUDA tensor."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a tensor on the GPU" % name)
+    if t.dtype != _F16 or t.dim() != 2 or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous 2-D float16 tensor" % name)
+    return (t.data_ptr() if t.numel() else None), t.shape[0], t.shape[1]
+
+
+def _wgrad_args(dy: torch.Tensor, x: torch.Tensor, idx: Optional[torch.Tensor], seg_ptr: Optional[torch.Tensor],
+                nnz: int) -> tuple:
+    dy_ptr, tokens, out_features = _dev_matrix(dy, "dy")
+    x_ptr, tokens_x, in_features = _dev_matrix(x, "x")
+    if tokens != tokens_x:
+        raise ValueError("dy has %d rows (tokens), x has %d" % (tokens, tokens_x))
+    n = out_features * in_features
+    seg = _dev(seg_ptr, torch.int32, "seg_ptr", samo_seg_ptr_len(n)) if idx is not None else None
+    return (dy_ptr, x_ptr, tokens, out_features, in_features, _dev(idx, torch.int32, "idx", nnz), seg, nnz)
+
+
+def samo_wgrad_gather(dy: torch.Tensor, x: torch.Tensor, idx: Optional[torch.Tensor], seg_ptr: Optional[torch.Tensor],
+                      inv_loss_scale: float, gc: torch.Tensor) -> None:
+    """gc = the weight gradient dy^T x (tokens x out, tokens x in -> out x in), rounded to fp16, at idx,
+    times inv_loss_scale."""
+    nnz = gc.numel()
+    _check(lib().samo_wgrad_gather(*_wgrad_args(dy, x, idx, seg_ptr, nnz), float(inv_loss_scale),
+                                   _dev(gc, torch.float32, "gc"), _stream()), "samo_wgrad_gather")
+
+
+def samo_wgrad_gather_fp16(dy: torch.Tensor, x: torch.Tensor, idx: Optional[torch.Tensor],
+                           seg_ptr: Optional[torch.Tensor], gc16: torch.Tensor, accumulate: bool = False) -> None:
+    nnz = gc16.numel()
+    _check(lib().samo_wgrad_gather_fp16(*_wgrad_args(dy, x, idx, seg_ptr, nnz), _dev(gc16, _F16, "gc16"),
+                                        int(bool(accumulate)), _stream()), "samo_wgrad_gather_fp16")
 
 
 def sgd_cfg(lr: float, momentum: float = 0.9, weight_decay: float = 0.0) -> SgdCfg:

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsamo.so")
-SOURCES = ["api.hip", "index.hip", "pipeline.hip"]
+SOURCES = ["api.hip", "index.hip", "pipeline.hip", "wgrad.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-Wall", "-Wextra", "-Wno-unused-parameter",

@@ -307,6 +307,42 @@ samo_status samo_gather_grads_fp16(const uint16_t *d_g, int64_t n, const int32_t
                                     nullptr, as_stream(stream)));
 }
 
+namespace {
+samo_status check_wgrad(const void *d_dy, const void *d_x, int64_t tokens, int64_t out, int64_t in,
+                        const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz, const void *d_out)
+{
+    if (tokens < 0 || tokens > kMaxN || out <= 0 || in <= 0 || out > kMaxN || in > kMaxN) return SAMO_ERR_SIZE;
+    if ((out & 7) || (in & 7)) return SAMO_ERR_SIZE;
+    if (out > kMaxN / in) return SAMO_ERR_SIZE;
+    if (samo_status s = check_sizes(out * in, nnz)) return s;
+    if (nnz == 0) return SAMO_OK;
+    if (!d_out || (tokens > 0 && (!d_dy || !d_x))) return SAMO_ERR_NULL;
+    if (!d_idx && nnz != out * in) return SAMO_ERR_NULL;
+    if (d_idx && !d_seg_ptr) return SAMO_ERR_NULL;
+    if (misaligned(d_dy) || misaligned(d_x) || misaligned(d_idx) || misaligned(d_out)) return SAMO_ERR_ALIGN;
+    return SAMO_OK;
+}
+}  // namespace
+
+samo_status samo_wgrad_gather(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens, int64_t out, int64_t in,
+                              const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz, float inv_loss_scale,
+                              float *d_gc, void *stream)
+{
+    if (samo_status s = check_wgrad(d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc)) return s;
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    return hip_status(launch_wgrad(kOutF32, reinterpret_cast<const _Float16 *>(d_dy), reinterpret_cast<const _Float16 *>(d_x),
+                                   tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc, inv_loss_scale, 0, as_stream(stream)));
+}
+
+samo_status samo_wgrad_gather_fp16(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens, int64_t out, int64_t in,
+                                   const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz, uint16_t *d_gc16,
+                                   int32_t accumulate, void *stream)
+{
+    if (samo_status s = check_wgrad(d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc16)) return s;
+    return hip_status(launch_wgrad(kOutF16, reinterpret_cast<const _Float16 *>(d_dy), reinterpret_cast<const _Float16 *>(d_x),
+                                   tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc16, 1.f, accumulate != 0, as_stream(stream)));
+}
+
 samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,
                            const samo_adam_cfg *h_cfg, void *stream)
 {

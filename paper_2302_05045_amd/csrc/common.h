@@ -129,6 +129,11 @@ hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const G
 int64_t stats_workspace_partials(int64_t gather_wgs);
 hipError_t launch_stats_finalize(StatPartial *partials, int64_t gather_wgs, samo_grad_stats *out, hipStream_t s);
 
+// Weight gradient dY^T X of a linear layer gathered at the index (out_kind: kOutF32 or kOutF16).
+hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
+                        const int32_t *idx, const int32_t *seg_ptr, int64_t nnz, void *gc, float inv_scale,
+                        int accumulate, hipStream_t s);
+
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 
 }  // namespace samo
