@@ -313,6 +313,7 @@ samo_status check_wgrad(const void *d_dy, const void *d_x, int64_t tokens, int64
 {
     if (tokens < 0 || tokens > kMaxN || out <= 0 || in <= 0 || out > kMaxN || in > kMaxN) return SAMO_ERR_SIZE;
     if ((out & 7) || (in & 7)) return SAMO_ERR_SIZE;
+    if (out > (1 << 24) || in > (1 << 24)) return SAMO_ERR_SIZE;   // 32-bit byte offsets within a stage of 32 tokens
     if (out > kMaxN / in) return SAMO_ERR_SIZE;
     if (samo_status s = check_sizes(out * in, nnz)) return s;
     if (nnz == 0) return SAMO_OK;

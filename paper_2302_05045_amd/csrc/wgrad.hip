@@ -6,6 +6,8 @@
 // LDS; the epilogue rounds each accumulator once to fp16 — the value the dense gradient tensor
 // would have held — and stores only the entries the layer's index keeps.  The dense gradient is
 // never written to or read back from HBM.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace samo {
@@ -51,23 +53,6 @@ __device__ __forceinline__ half8 read_fragment(const unsigned char *p)
     return __builtin_bit_cast(half8, q);
 }
 
-// First kept element at or after dense position p of a layer (p in [0, n]).
-__device__ __forceinline__ int first_kept_at(const int32_t *__restrict__ idx, const int32_t *__restrict__ seg_ptr,
-                                             int64_t n, int64_t nnz, int64_t p)
-{
-    if (p >= n) return (int)nnz;
-    if (!idx) return (int)p;                      // unpruned layer: position k is element k
-    const int64_t s = p / kSeg;
-    int a = seg_ptr[s], b = seg_ptr[s + 1];
-    const int key = (int)p;
-    while (a < b) {
-        const int mid = (a + b) >> 1;
-        if (idx[mid] < key) a = mid + 1;
-        else b = mid;
-    }
-    return a;
-}
-
 struct WgradArgs {
     const _Float16 *dy;      // tokens x out
     const _Float16 *x;       // tokens x in
@@ -81,6 +66,7 @@ struct WgradArgs {
     int accumulate;
     int tiles_in;
     int64_t tiles;
+    int map;
 };
 
 template <int OUT>
@@ -92,10 +78,17 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
     // Workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles so
     // that the tiles sharing operand panels, and neighbouring runs of idx, meet in one L2.
     const int64_t per_xcd = (A.tiles + 7) / 8;
-    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int64_t tile = A.map == 0 ? (int64_t)blockIdx.x : (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= A.tiles) return;
-    const int row0 = (int)(tile / A.tiles_in) * kWgOut;     // first row of dW (feature of dY)
-    const int col0 = (int)(tile % A.tiles_in) * kWgIn;      // first column of dW (feature of X)
+    int row0, col0;
+    if (A.map == 2) {                                        // out-tiles fastest
+        const int tiles_out = (int)(A.tiles / A.tiles_in);
+        row0 = (int)(tile % tiles_out) * kWgOut;
+        col0 = (int)(tile / tiles_out) * kWgIn;
+    } else {
+        row0 = (int)(tile / A.tiles_in) * kWgOut;            // first row of dW (feature of dY)
+        col0 = (int)(tile % A.tiles_in) * kWgIn;             // first column of dW (feature of X)
+    }
 
     const int t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
@@ -103,61 +96,96 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
     const int ml = lane >> 3;         // which feature block within the wave's share
     const int64_t n = (int64_t)A.out * A.in;
 
-    // This thread's end of one row's run of idx (threads 0..127: start, 128..255: end); the
-    // searches overlap the main loop.
-    int my_bound = 0;
+    // This thread's end of one row's run of idx (threads 0..127: start, 128..255: end), found by
+    // bisection inside the segment seg_ptr names.  The probes ride along with the main loop, one
+    // per stage, so that their latency costs nothing; what is left afterwards is finished there.
+    int s_lo = 0, s_hi = 0, s_key = 0;
     {
         const int r = row0 + (t & (kWgOut - 1));
         if (r < A.out) {
             const int c = t < kWgOut ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
-            my_bound = first_kept_at(A.idx, A.seg_ptr, n, A.nnz, (int64_t)r * A.in + c);
+            const int64_t p = (int64_t)r * A.in + c;
+            if (p >= n) s_lo = s_hi = (int)A.nnz;
+            else if (!A.idx) s_lo = s_hi = (int)p;           // unpruned layer: position k is element k
+            else {
+                s_lo = A.seg_ptr[p / kSeg];
+                s_hi = A.seg_ptr[p / kSeg + 1];
+                s_key = (int)p;
+            }
         }
     }
 
     // Global -> register -> LDS movers.  X: an 8-feature x 4-token block per thread (four 16-byte
     // loads), dY: a 4-feature x 4-token block (four 8-byte loads); both transposed in registers so
     // that LDS holds, per feature, tokens contiguously — what an MFMA operand lane needs.
+    // Addresses are a uniform per-stage base plus a 32-bit offset per lane that never changes.
+    // Features past the matrix are never gathered: their loads are only moved to a valid address.
     const int xf = col0 + (wave * 8 + ml) * 8;               // first X feature of the block
     const int yf = row0 + (wave * 8 + ml) * 4;               // first dY feature of the block
-    // Features past the matrix are never gathered: their loads are only moved to a valid address.
-    const _Float16 *xsrc = A.x + (xf < A.in ? xf : 0);
-    const _Float16 *ysrc = A.dy + (yf < A.out ? yf : 0);
-    uint4 xq[4];
-    uint2 yq[4];
-    auto load_stage = [&](int64_t tok0) {
+    uint32_t xoff[4], yoff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        xoff[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)A.in + (uint32_t)(xf < A.in ? xf : 0)) * 2u;
+        yoff[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)A.out + (uint32_t)(yf < A.out ? yf : 0)) * 2u;
+    }
+    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(A.x);
+    const unsigned char *ybase = reinterpret_cast<const unsigned char *>(A.dy);
+    const int64_t xstage = (int64_t)kWgTok * A.in * 2, ystage = (int64_t)kWgTok * A.out * 2;   // bytes per stage
+    struct Regs {
+        uint4 x[4];
+        uint2 y[4];
+    };
+    auto load_full_stage = [&](Regs &q, int64_t stage) {
+        const unsigned char *xs = xbase + stage * xstage, *ys = ybase + stage * ystage;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int64_t tok = tok0 + kg * 4 + j;
-            const bool in_range = tok < A.tokens;
-            const int64_t tc = in_range ? tok : A.tokens - 1;
-            const uint4 xv = *reinterpret_cast<const uint4 *>(xsrc + tc * A.in);
-            const uint2 yv = *reinterpret_cast<const uint2 *>(ysrc + tc * A.out);
-            xq[j] = in_range ? xv : make_uint4(0, 0, 0, 0);   // tokens past the end add nothing
-            yq[j] = in_range ? yv : make_uint2(0, 0);
+            q.x[j] = *reinterpret_cast<const uint4 *>(xs + xoff[j]);
+            q.y[j] = *reinterpret_cast<const uint2 *>(ys + yoff[j]);
         }
     };
-    auto store_stage = [&](unsigned char *stage) {
+    // The last stage when the token count is not a multiple of 32: rows past the end are read
+    // from the last token and cleared, so that they add nothing.
+    auto load_tail_stage = [&](Regs &q, int64_t stage) {
+        const unsigned char *xs = xbase + stage * xstage, *ys = ybase + stage * ystage;
+        const int rows = (int)(A.tokens - stage * kWgTok);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = kg * 4 + j;
+            const uint32_t keep = row < rows ? 0xffffffffu : 0u;
+            const uint32_t back = row < rows ? 0u : (uint32_t)(row - (rows - 1));
+            const uint4 xv = *reinterpret_cast<const uint4 *>(xs + (xoff[j] - back * (uint32_t)A.in * 2u));
+            const uint2 yv = *reinterpret_cast<const uint2 *>(ys + (yoff[j] - back * (uint32_t)A.out * 2u));
+            q.x[j] = make_uint4(xv.x & keep, xv.y & keep, xv.z & keep, xv.w & keep);
+            q.y[j] = make_uint2(yv.x & keep, yv.y & keep);
+        }
+    };
+    const int64_t full_stages = A.tokens / kWgTok;
+    const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;    // none: dW = 0
+    auto load_stage = [&](Regs &q, int64_t stage) {
+        if (stage < full_stages) load_full_stage(q, stage);
+        else load_tail_stage(q, stage);
+    };
+    // Two fp16 lanes of two registers into one: the low halves, or the high halves.
+    auto pack_lo = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); };
+    auto pack_hi = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); };
+    auto store_stage = [&](const Regs &q, unsigned char *stage) {
         {
-            const uint32_t d[4][4] = {{xq[0].x, xq[1].x, xq[2].x, xq[3].x}, {xq[0].y, xq[1].y, xq[2].y, xq[3].y},
-                                      {xq[0].z, xq[1].z, xq[2].z, xq[3].z}, {xq[0].w, xq[1].w, xq[2].w, xq[3].w}};
+            const uint32_t d[4][4] = {{q.x[0].x, q.x[1].x, q.x[2].x, q.x[3].x}, {q.x[0].y, q.x[1].y, q.x[2].y, q.x[3].y},
+                                      {q.x[0].z, q.x[1].z, q.x[2].z, q.x[3].z}, {q.x[0].w, q.x[1].w, q.x[2].w, q.x[3].w}};
             unsigned char *dst = stage + (wave * 8 + ml) * 8 * kRowBytes + kg * 8;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {                    // features 2e and 2e+1: tokens 0,1 | 2,3 of the block
-                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) =
-                    make_uint2((d[e][0] & 0xffffu) | (d[e][1] << 16), (d[e][2] & 0xffffu) | (d[e][3] << 16));
-                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) =
-                    make_uint2((d[e][0] >> 16) | (d[e][1] & 0xffff0000u), (d[e][2] >> 16) | (d[e][3] & 0xffff0000u));
+                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) = make_uint2(pack_lo(d[e][0], d[e][1]), pack_lo(d[e][2], d[e][3]));
+                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) = make_uint2(pack_hi(d[e][0], d[e][1]), pack_hi(d[e][2], d[e][3]));
             }
         }
         {
-            const uint32_t d[2][4] = {{yq[0].x, yq[1].x, yq[2].x, yq[3].x}, {yq[0].y, yq[1].y, yq[2].y, yq[3].y}};
+            const uint32_t d[2][4] = {{q.y[0].x, q.y[1].x, q.y[2].x, q.y[3].x}, {q.y[0].y, q.y[1].y, q.y[2].y, q.y[3].y}};
             unsigned char *dst = stage + (kWgIn + (wave * 8 + ml) * 4) * kRowBytes + kg * 8;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) =
-                    make_uint2((d[e][0] & 0xffffu) | (d[e][1] << 16), (d[e][2] & 0xffffu) | (d[e][3] << 16));
-                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) =
-                    make_uint2((d[e][0] >> 16) | (d[e][1] & 0xffff0000u), (d[e][2] >> 16) | (d[e][3] & 0xffff0000u));
+                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) = make_uint2(pack_lo(d[e][0], d[e][1]), pack_lo(d[e][2], d[e][3]));
+                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) = make_uint2(pack_hi(d[e][0], d[e][1]), pack_hi(d[e][2], d[e][3]));
             }
         }
     };
@@ -174,24 +202,13 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bo][bi][r] = 0.f;
-
-    const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;    // none: dW = 0
-    if (stages > 0) {
-        load_stage(0);
-        store_stage(lds);
-    }
-    __syncthreads();
-    for (int64_t st = 0; st < stages; ++st) {
-        const unsigned char *cur = lds + (st & 1) * kStageBytes;
-        const bool more = st + 1 < stages;
-        if (more) load_stage((st + 1) * kWgTok);
+    auto multiply_stage = [&](const unsigned char *cur) {
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int chunk = kk * 2 + khalf;
             half8 xa[4], yb[2];
 #pragma unroll
-            for (int bi = 0; bi < 4; ++bi)
-                xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
+            for (int bi = 0; bi < 4; ++bi) xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
 #pragma unroll
             for (int bo = 0; bo < 2; ++bo)
                 yb[bo] = read_fragment(cur + stage_offset(kWgIn + wo * 64 + bo * 32 + l32, chunk));
@@ -201,15 +218,53 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
                 for (int bi = 0; bi < 4; ++bi)
                     acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
         }
-        if (more) store_stage(lds + ((st + 1) & 1) * kStageBytes);
+    };
+    // One bisection probe: issued with a stage's loads, resolved after that stage's arithmetic.
+    int s_mid = 0, s_val = 0;
+    bool s_open = false;
+    auto probe_issue = [&]() {
+        s_open = s_lo < s_hi;
+        s_mid = (s_lo + s_hi) >> 1;
+        if (s_open) s_val = A.idx[s_mid];
+    };
+    auto probe_resolve = [&]() {
+        if (s_open) {
+            if (s_val < s_key) s_lo = s_mid + 1;
+            else s_hi = s_mid;
+        }
+    };
+
+    // Main loop: two LDS stages, the next stage's loads in flight during a stage's arithmetic, one
+    // barrier per stage; written out for the two stages so that every LDS offset is a constant.
+    unsigned char *const buf0 = lds, *const buf1 = lds + kStageBytes;
+    Regs q;
+    if (stages > 0) {
+        load_stage(q, 0);
+        store_stage(q, buf0);
+    }
+    __syncthreads();
+    auto step = [&](const unsigned char *cur, unsigned char *nxt, int64_t next_stage) {
+        const bool more = next_stage < stages;
+        if (more) load_stage(q, next_stage);
+        probe_issue();
+        multiply_stage(cur);
+        if (more) store_stage(q, nxt);
+        probe_resolve();
         __syncthreads();
+    };
+    for (int64_t st = 0; st < stages; ++st) step((st & 1) ? buf1 : buf0, (st & 1) ? buf0 : buf1, st + 1);
+    while (s_lo < s_hi) {
+        probe_issue();
+        probe_resolve();
     }
 
     // Epilogue, 64 rows of dW per pass (the two waves that own them write, everyone gathers):
-    // accumulators -> fp16 image in LDS -> the kept entries of each row, one half wave per row.
-    bounds[t] = my_bound;
+    // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes 8 rows
+    // of a pass and fetches their index runs together before it touches the image.
+    bounds[t] = s_lo;
     _Float16 *img = reinterpret_cast<_Float16 *>(lds);
     const int hw = t >> 5;
+    constexpr int kRowsPerHalfWave = kEpiRows / 8;
 #pragma unroll 1
     for (int pass = 0; pass < 2; ++pass) {
         if (wo == pass) {
@@ -227,15 +282,28 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
                     }
         }
         __syncthreads();
-#pragma unroll 1
-        for (int it = 0; it < kEpiRows / 8; ++it) {
-            const int rl = it * 8 + hw;
-            const int trow = pass * kEpiRows + rl;
-            const int lo = bounds[trow], hi = bounds[kWgOut + trow];
-            const int64_t base = (int64_t)(row0 + trow) * A.in + col0;
-            for (int k = lo + l32; k < hi; k += 32) {
-                const int pos = A.idx ? A.idx[k] : k;
-                const _Float16 v = img[rl * kEpiPitch + (int)(pos - base)];
+        int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
+#pragma unroll
+        for (int it = 0; it < kRowsPerHalfWave; ++it) {
+            const int trow = pass * kEpiRows + it * 8 + hw;
+            lo[it] = bounds[trow];
+            hi[it] = bounds[kWgOut + trow];
+            longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
+        }
+        for (int off = l32; off - l32 < longest; off += 32) {
+            int pos[kRowsPerHalfWave];
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                const int k = lo[it] + off;
+                pos[it] = k < hi[it] ? (A.idx ? A.idx[k] : k) : -1;
+            }
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                if (pos[it] < 0) continue;
+                const int k = lo[it] + off;
+                const int rl = it * 8 + hw;
+                const int64_t base = (int64_t)(row0 + pass * kEpiRows + rl) * A.in + col0;
+                const _Float16 v = img[rl * kEpiPitch + (int)(pos[it] - base)];
                 if (OUT == kOutF32) {
                     reinterpret_cast<float *>(A.gc)[k] = (float)v * A.inv_scale;
                 } else {
@@ -260,6 +328,8 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
     a.tiles_in = (int)ceil_div(in, kWgIn);
     a.tiles = ceil_div(out, kWgOut) * a.tiles_in;
+    static const int map = getenv("SAMO_WGRAD_MAP") ? atoi(getenv("SAMO_WGRAD_MAP")) : 1;
+    a.map = map;
     const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
     if (out_kind == kOutF32) wgrad_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
     else wgrad_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
