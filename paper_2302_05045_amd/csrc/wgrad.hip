@@ -316,6 +316,261 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Large-layer variant: a 256 x 256 tile per workgroup of 8 waves (each wave 64 x 128 as above).
+// Per stage a thread moves one 8-feature x 4-token block (16 registers), which leaves room to keep
+// the loads of TWO stages in flight.  Waves 0-3 move X, waves 4-7 move dY.
+constexpr int kBigOut = 256;
+constexpr int kBigIn = 256;
+constexpr int kBigThreads = 512;
+constexpr int kBigStageBytes = (kBigIn + kBigOut) * kRowBytes;
+constexpr int kBigLdsBytes = 2 * kBigStageBytes;
+static_assert(kBigLdsBytes >= kEpiBytes, "the epilogue image reuses the operand stages");
+
+struct Block8x4 {
+    uint4 r[4];      // 4 tokens x 8 features
+};
+
+__device__ __forceinline__ uint32_t pack_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+// Writes the block as 8 feature rows of 4 tokens each.
+__device__ __forceinline__ void store_block(const Block8x4 &q, unsigned char *dst)
+{
+    const uint32_t d[4][4] = {{q.r[0].x, q.r[1].x, q.r[2].x, q.r[3].x}, {q.r[0].y, q.r[1].y, q.r[2].y, q.r[3].y},
+                              {q.r[0].z, q.r[1].z, q.r[2].z, q.r[3].z}, {q.r[0].w, q.r[1].w, q.r[2].w, q.r[3].w}};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) = make_uint2(pack_lo16(d[e][0], d[e][1]), pack_lo16(d[e][2], d[e][3]));
+        *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) = make_uint2(pack_hi16(d[e][0], d[e][1]), pack_hi16(d[e][2], d[e][3]));
+    }
+}
+
+template <int OUT>
+__global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradArgs A)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
+    __shared__ int bounds[2 * kBigOut];
+
+    const int64_t per_xcd = (A.tiles + 7) / 8;
+    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= A.tiles) return;
+    const int row0 = (int)(tile / A.tiles_in) * kBigOut;
+    const int col0 = (int)(tile % A.tiles_in) * kBigIn;
+
+    const int t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int kg = lane & 7, ml = lane >> 3;
+    const int64_t n = (int64_t)A.out * A.in;
+
+    int s_lo = 0, s_hi = 0, s_key = 0;
+    {
+        const int r = row0 + (t & (kBigOut - 1));
+        if (r < A.out) {
+            const int c = t < kBigOut ? col0 : (col0 + kBigIn < A.in ? col0 + kBigIn : A.in);
+            const int64_t p = (int64_t)r * A.in + c;
+            if (p >= n) s_lo = s_hi = (int)A.nnz;
+            else if (!A.idx) s_lo = s_hi = (int)p;
+            else {
+                s_lo = A.seg_ptr[p / kSeg];
+                s_hi = A.seg_ptr[p / kSeg + 1];
+                s_key = (int)p;
+            }
+        }
+    }
+
+    // Mover role of this thread: one 8-feature block of X (waves 0-3) or of dY (waves 4-7).
+    const bool moves_dy = wave >= 4;
+    const int blk = (wave & 3) * 8 + ml;                                   // 0..31
+    const int features = moves_dy ? A.out : A.in;
+    const int f = (moves_dy ? row0 : col0) + blk * 8;
+    const unsigned char *src = reinterpret_cast<const unsigned char *>(moves_dy ? A.dy : A.x);
+    const int64_t stage_bytes = (int64_t)kWgTok * features * 2;
+    uint32_t off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) off[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)features + (uint32_t)(f < features ? f : 0)) * 2u;
+    const int lds_dst = ((moves_dy ? kBigIn : 0) + blk * 8) * kRowBytes + kg * 8;
+    auto load_full = [&](Block8x4 &q, int64_t stage) {
+        const unsigned char *sp = src + stage * stage_bytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q.r[j] = *reinterpret_cast<const uint4 *>(sp + off[j]);
+    };
+    auto load_tail = [&](Block8x4 &q, int64_t stage) {
+        const unsigned char *sp = src + stage * stage_bytes;
+        const int rows = (int)(A.tokens - stage * kWgTok);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = kg * 4 + j;
+            const uint32_t keep = row < rows ? 0xffffffffu : 0u;
+            const uint32_t back = row < rows ? 0u : (uint32_t)(row - (rows - 1));
+            const uint4 v = *reinterpret_cast<const uint4 *>(sp + (off[j] - back * (uint32_t)features * 2u));
+            q.r[j] = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
+        }
+    };
+
+    const int wo = wave & 3, wi = wave >> 2;
+    const int l32 = lane & 31, khalf = lane >> 5;
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int bo = 0; bo < 2; ++bo)
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bo][bi][r] = 0.f;
+    auto multiply_stage = [&](const unsigned char *cur) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int chunk = kk * 2 + khalf;
+            half8 xa[4], yb[2];
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi) xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
+#pragma unroll
+            for (int bo = 0; bo < 2; ++bo)
+                yb[bo] = read_fragment(cur + stage_offset(kBigIn + wo * 64 + bo * 32 + l32, chunk));
+#pragma unroll
+            for (int bo = 0; bo < 2; ++bo)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+                    acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
+        }
+    };
+
+    // One bisection probe per pair of stages: issued right behind the loads of the pair's first
+    // stage, used after the second stage has waited for those same loads — it never makes a
+    // stage wait for loads younger than the ones it needs anyway.
+    int s_mid = 0, s_val = 0;
+    bool s_open = false;
+    auto probe_issue = [&]() {
+        s_open = s_lo < s_hi;
+        s_mid = (s_lo + s_hi) >> 1;
+        if (s_open) s_val = A.idx[s_mid];
+    };
+    auto probe_resolve = [&]() {
+        if (s_open) {
+            if (s_val < s_key) s_lo = s_mid + 1;
+            else s_hi = s_mid;
+        }
+    };
+
+    // Main loop over the full stages, written out for the two LDS stages and the two register
+    // sets: while stage s is multiplied out of LDS, stage s+1 sits in (or is on its way to) one
+    // register set and stage s+2 is being requested into the other.  Inside the loop every load
+    // is unconditional, so that the wait before a store to LDS can leave exactly the younger
+    // stage's loads outstanding; the last two or three stages run after it.
+    unsigned char *const buf0 = big_lds, *const buf1 = big_lds + kBigStageBytes;
+    const int64_t full = A.tokens / kWgTok;
+    Block8x4 qa, qb;
+    if (full >= 2) {
+        load_full(qa, 0);
+        load_full(qb, 1);
+        store_block(qa, buf0 + lds_dst);
+        __syncthreads();
+        int64_t st = 0;
+        for (; st + 3 < full; st += 2) {
+            load_full(qa, st + 2);
+            probe_issue();
+            __builtin_amdgcn_sched_barrier(0);           // requests first, then the arithmetic that hides them
+            multiply_stage(buf0);
+            store_block(qb, buf1 + lds_dst);
+            __syncthreads();
+            load_full(qb, st + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply_stage(buf1);
+            store_block(qa, buf0 + lds_dst);
+            __builtin_amdgcn_sched_barrier(0);           // keep the probe's use behind the wait above
+            probe_resolve();
+            __syncthreads();
+        }
+        // stage st is in buf0, stage st+1 in qb; a third one remains when the count is odd
+        const bool third = st + 2 < full;
+        if (third) load_full(qa, st + 2);
+        multiply_stage(buf0);
+        store_block(qb, buf1 + lds_dst);
+        __syncthreads();
+        multiply_stage(buf1);
+        if (third) store_block(qa, buf0 + lds_dst);
+        __syncthreads();
+        if (third) {
+            multiply_stage(buf0);
+            __syncthreads();
+        }
+    } else if (full == 1) {
+        load_full(qa, 0);
+        store_block(qa, buf0 + lds_dst);
+        __syncthreads();
+        multiply_stage(buf0);
+        __syncthreads();
+    }
+    if (A.tokens > full * kWgTok) {                      // the partial last stage, on its own
+        load_tail(qa, full);
+        store_block(qa, buf0 + lds_dst);
+        __syncthreads();
+        multiply_stage(buf0);
+        __syncthreads();
+    }
+    while (s_lo < s_hi) {                                // what the main loop left of the bisection
+        const int mid = (s_lo + s_hi) >> 1;
+        if (A.idx[mid] < s_key) s_lo = mid + 1;
+        else s_hi = mid;
+    }
+
+    // Epilogue as in the small variant: 64 rows of dW per pass, 4 rows per half wave.
+    bounds[t] = s_lo;
+    _Float16 *img = reinterpret_cast<_Float16 *>(big_lds);
+    const int hw = t >> 5;                               // 0..15
+    constexpr int kRowsPerHalfWave = kEpiRows / 16;
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+        if (wo == pass) {
+#pragma unroll
+            for (int bo = 0; bo < 2; ++bo)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        half4 h;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];
+                        const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
+                        *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kEpiPitch + col) = h;
+                    }
+        }
+        __syncthreads();
+        int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
+#pragma unroll
+        for (int it = 0; it < kRowsPerHalfWave; ++it) {
+            const int trow = pass * kEpiRows + it * 16 + hw;
+            lo[it] = bounds[trow];
+            hi[it] = bounds[kBigOut + trow];
+            longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
+        }
+        for (int off_k = l32; off_k - l32 < longest; off_k += 32) {
+            int pos[kRowsPerHalfWave];
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                const int k = lo[it] + off_k;
+                pos[it] = k < hi[it] ? (A.idx ? A.idx[k] : k) : -1;
+            }
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                if (pos[it] < 0) continue;
+                const int k = lo[it] + off_k;
+                const int rl = it * 16 + hw;
+                const int64_t base = (int64_t)(row0 + pass * kEpiRows + rl) * A.in + col0;
+                const _Float16 v = img[rl * kEpiPitch + (int)(pos[it] - base)];
+                if (OUT == kOutF32) {
+                    reinterpret_cast<float *>(A.gc)[k] = (float)v * A.inv_scale;
+                } else {
+                    _Float16 *dst = reinterpret_cast<_Float16 *>(A.gc) + k;
+                    *dst = A.accumulate ? (_Float16)(*dst + v) : v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
@@ -326,10 +581,31 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     WgradArgs a;
     a.dy = dy; a.x = x; a.tokens = tokens; a.out = (int)out; a.in = (int)in;
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
-    a.tiles_in = (int)ceil_div(in, kWgIn);
-    a.tiles = ceil_div(out, kWgOut) * a.tiles_in;
     static const int map = getenv("SAMO_WGRAD_MAP") ? atoi(getenv("SAMO_WGRAD_MAP")) : 1;
     a.map = map;
+    // Large tiles once they fill the chip; small ones for layers that would leave compute units idle.
+    const char *forced = getenv("SAMO_WGRAD_TILE");           // read per call: tests switch it
+    const int force_tile = forced ? atoi(forced) : 0;
+    const int64_t big_tiles = ceil_div(out, kBigOut) * ceil_div(in, kBigIn);
+    const bool big = force_tile == 256 || (force_tile != 128 && big_tiles >= 256);
+    if (big) {
+        static hipError_t configured = [] {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF32>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+            if (e != hipSuccess) return e;
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+        }();
+        if (configured != hipSuccess) return configured;
+        a.tiles_in = (int)ceil_div(in, kBigIn);
+        a.tiles = big_tiles;
+        const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
+        if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kBigThreads), kBigLdsBytes, s>>>(a);
+        else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kBigThreads), kBigLdsBytes, s>>>(a);
+        return hipGetLastError();
+    }
+    a.tiles_in = (int)ceil_div(in, kWgIn);
+    a.tiles = ceil_div(out, kWgOut) * a.tiles_in;
     const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
     if (out_kind == kOutF32) wgrad_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
     else wgrad_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
