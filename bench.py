@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published peak
 
 
 def parse_args():
@@ -169,6 +170,7 @@ def main():
         return float(np.mean([ev[k].elapsed_time(ev[k + 1]) for k in range(iters)]))
 
     entries = {}
+    mfma_entries = {}
     if not args.no_entries:
         def entry(name, ms, nbytes):
             entries[name] = {"ms": round(ms, 4), "algorithmic_GB": round(nbytes / 1e9, 4),
@@ -212,6 +214,33 @@ def main():
         dst = torch.empty_like(src)
         entry("samo_stream_copy(ceiling)", time_entry(lambda: samo.samo_stream_copy(dst, src)), 2 * nb)
         del src, dst
+
+        # compression fused into the backward pass: the weight gradient dY^T X of the workload's
+        # largest pruned matrix, one micro-batch of one 2048-token sequence, written straight into
+        # the compressed gradient — a dense contraction, priced against the fp16 MFMA peak; beside
+        # it the same result by the library GEMM into a dense fp16 tensor plus samo_gather_grads
+        cand = [k for k, L in enumerate(layers) if L.seg_ptr is not None and specs[k].rows % 8 == 0 and specs[k].cols % 8 == 0]
+        if cand:
+            k = max(cand, key=lambda j: layers[j].n)
+            L, out_f, in_f, tokens = layers[k], specs[k].rows, specs[k].cols, 2048
+            dy = torch.from_numpy(si.output_grads_fp16(tokens, out_f, 1).view(np.int16)).to(dev).view(torch.float16).view(tokens, out_f)
+            xa = torch.from_numpy(si.activations_fp16(tokens, in_f, 1).view(np.int16)).to(dev).view(torch.float16).view(tokens, in_f)
+            dense_g = L.g.view(out_f, in_f)
+            flops = 2.0 * tokens * out_f * in_f
+
+            def mfma_entry(name, ms):
+                mfma_entries[name] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1),
+                                      "frac_of_peak": round(flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4)}
+            mfma_entries["layer"] = "%s: dW %d x %d (%.1f%% kept), %d tokens" % (specs[k].name, out_f, in_f,
+                                                                               100.0 * L.p.numel() / L.n, tokens)
+            mfma_entry("samo_wgrad_gather", time_entry(lambda: samo.samo_wgrad_gather(dy, xa, L.idx, L.seg_ptr, inv, L.gc)))
+
+            def library_path():
+                torch.matmul(dy.t(), xa, out=dense_g)
+                samo.samo_gather_grads(L.g, L.idx, inv, L.gc)
+            mfma_entry("library GEMM (dense fp16 dW) + samo_gather_grads", time_entry(library_path))
+            mfma_entry("library GEMM alone", time_entry(lambda: torch.matmul(dy.t(), xa, out=dense_g)))
+            del dy, xa
 
     achieved = fused_bytes / kernel_ms / 1e6
     traffic = None
@@ -271,6 +300,7 @@ def main():
                      "algorithmic_bytes_per_launch": fused_bytes},
         "cpu_baseline": cpu,
         "entries": entries,
+        "mfma_entries": mfma_entries,
         "setup_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))

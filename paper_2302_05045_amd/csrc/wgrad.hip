@@ -247,8 +247,10 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
         const bool more = next_stage < stages;
         if (more) load_stage(q, next_stage);
         probe_issue();
+        __builtin_amdgcn_sched_barrier(0);               // requests first, then the arithmetic that hides them
         multiply_stage(cur);
         if (more) store_stage(q, nxt);
+        __builtin_amdgcn_sched_barrier(0);               // the probe is used only behind the wait for the stage's loads
         probe_resolve();
         __syncthreads();
     };
@@ -583,11 +585,10 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
     static const int map = getenv("SAMO_WGRAD_MAP") ? atoi(getenv("SAMO_WGRAD_MAP")) : 1;
     a.map = map;
-    // Large tiles once they fill the chip; small ones for layers that would leave compute units idle.
     const char *forced = getenv("SAMO_WGRAD_TILE");           // read per call: tests switch it
     const int force_tile = forced ? atoi(forced) : 0;
     const int64_t big_tiles = ceil_div(out, kBigOut) * ceil_div(in, kBigIn);
-    const bool big = force_tile == 256 || (force_tile != 128 && big_tiles >= 256);
+    const bool big = force_tile != 128;   // measured: the large tile wins at every layer size, even at 16 tiles
     if (big) {
         static hipError_t configured = [] {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF32>),

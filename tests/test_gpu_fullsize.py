@@ -341,3 +341,50 @@ def test_index_build_statistics_and_guarded_split_step_under_hip_graph_replay():
         assert_close(L.p.cpu().numpy(), p, "p")
         assert_close(L.m.cpu().numpy(), m, "m")
         assert_close(L.v.cpu().numpy(), v, "v")
+
+
+def test_gpt2p7b_fc1_weight_gradient_compressed_in_the_backward_kernel():
+    """One full-size layer of the 2.7B model (FC1, 2560 x 10240, magnitude-pruned to 10 %), one
+    2048-token sequence: the fused weight gradient in the launch configuration bench.py times,
+    against the oracle on sampled outputs, and against the unfused route of this library (a
+    library GEMM into the dense fp16 tensor, then samo_gather_grads) on every output."""
+    spec = [s for s in si.config("gpt2.7b", 0.9, layers=1) if s.name.endswith("fc1")][0]
+    out_f, in_f, tokens = spec.rows, spec.cols, 2048
+    data = si.make_layer(spec)
+    idx = oracle.build_index(data.mask)
+    nnz = idx.shape[0]
+    dy = si.output_grads_fp16(tokens, out_f, spec.seed)
+    x = si.activations_fp16(tokens, in_f, spec.seed)
+    d_dy = torch.from_numpy(dy.view(np.int16)).to(DEV).view(torch.float16).view(tokens, out_f)
+    d_x = torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.float16).view(tokens, in_f)
+    ix = samo.samo_build_index(torch.from_numpy(data.mask).to(DEV))
+    assert ix.nnz == nnz
+    gc16 = torch.full((nnz,), float("nan"), dtype=torch.float16, device=DEV)
+    samo.samo_wgrad_gather_fp16(d_dy, d_x, ix.idx, ix.seg_ptr, gc16)
+    gc = torch.full((nnz,), float("nan"), dtype=torch.float32, device=DEV)
+    samo.samo_wgrad_gather(d_dy, d_x, ix.idx, ix.seg_ptr, INV, gc)
+    torch.cuda.synchronize()
+    got = host_bits(gc16)
+    # sampled outputs: first and last kept element, the ends of tiles, and 3000 random ones
+    rng = np.random.default_rng(12)
+    ks = np.unique(np.concatenate([[0, nnz - 1], rng.integers(0, nnz, 3000),
+                                   np.searchsorted(idx, np.arange(0, out_f * in_f, 256 * in_f // 8))[:200].clip(0, nnz - 1)]))
+    exact, mag = oracle.wgrad_at(dy, x, tokens, out_f, in_f, idx[ks])
+    slack = (tokens + 2) * 2.0 ** -23 * mag
+    lo, hi = (exact - slack).astype(np.float16), (exact + slack).astype(np.float16)
+    g = got[ks].view(np.float16)
+    assert np.all((g >= lo) & (g <= hi)), "sampled outputs outside the rounding bracket of the exact sums"
+    assert (g == exact.astype(np.float16)).mean() > 0.98
+    # fp32 output = the fp16 one widened, times 1/loss scale
+    assert np.array_equal(gc.cpu().numpy().view(np.uint32),
+                          (got.view(np.float16).astype(np.float32) * np.float32(INV)).view(np.uint32))
+    # every output against the unfused route: same products, fp32 sums in another order
+    dense = torch.empty((out_f, in_f), dtype=torch.float16, device=DEV)
+    torch.matmul(d_dy.t(), d_x, out=dense)
+    ref = torch.empty(nnz, dtype=torch.float32, device=DEV)
+    samo.samo_gather_grads(dense.view(-1), ix.idx, 1.0, ref)
+    torch.cuda.synchronize()
+    a, b = got.view(np.float16).astype(np.float32), ref.cpu().numpy()
+    assert (a == b).mean() > 0.995
+    ulp = np.maximum(np.abs(b), 2.0 ** -14) * 2.0 ** -10
+    assert np.all(np.abs(a - b) <= ulp), "more than one fp16 step from the library GEMM's rounding"
