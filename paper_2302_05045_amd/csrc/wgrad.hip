@@ -6,8 +6,6 @@
 // LDS; the epilogue rounds each accumulator once to fp16 — the value the dense gradient tensor
 // would have held — and stores only the entries the layer's index keeps.  The dense gradient is
 // never written to or read back from HBM.
-#include <cstdlib>
-
 #include "common.h"
 
 namespace samo {
@@ -17,25 +15,29 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// Workgroup tile: 128 rows of dW (features of dY) by 256 columns (features of X) — wide along the
-// direction in which the index runs, so that a row of the tile owns one contiguous run of idx —
-// four waves as 2 x 2, each 64 x 128 = 2 x 4 MFMA blocks (128 accumulator registers per lane,
-// two workgroups per compute unit).  32 tokens per stage, two stages in LDS.
-constexpr int kWgOut = 128;
+// Workgroup tile: 256 rows of dW (features of dY) by 256 columns (features of X), 8 waves as 4 x 2,
+// each 64 x 128 = 2 x 4 MFMA blocks (128 accumulator registers per lane, two waves per SIMD).
+// 32 tokens per stage, two stages in LDS, the loads of two further stages in flight in registers:
+// per stage a thread moves one 8-feature x 4-token block (16 registers; waves 0-3 move X, waves
+// 4-7 move dY).  Measured on MI355X against the alternatives that were built and dropped: a
+// 128 x 256 tile by 4 waves, two workgroups per compute unit, with one stage of loads in flight
+// (all its registers allow) reaches 0.6 of this one's rate at every layer size, down to 16 tiles;
+// the same 256 x 256 tile by 4 waves of 128 x 128 (256 accumulators, one wave per SIMD, half the
+// LDS reads per MFMA) reaches 0.9 — a lone wave per SIMD leaves its LDS stores, barrier and first
+// fragment reads of every stage uncovered.
+constexpr int kWgOut = 256;
 constexpr int kWgIn = 256;
 constexpr int kWgTok = 32;
-constexpr int kWgThreads = 256;
+constexpr int kWgThreads = 512;
 constexpr int kRowBytes = kWgTok * 2 + 8;                    // one feature's 32 tokens, padded: see stage_offset
 constexpr int kStageBytes = (kWgIn + kWgOut) * kRowBytes;    // X rows, then dY rows
+constexpr int kWgLdsBytes = 2 * kStageBytes;                 // dynamic LDS: above the 64 KiB a static array may have
 constexpr int kEpiRows = 64;                                 // rows of dW staged per epilogue pass
 constexpr int kEpiPitch = kWgIn + 8;                         // halves; +8 spreads a column of 32 rows over the banks
-constexpr int kOperandBytes = 2 * kStageBytes;
-constexpr int kEpiBytes = kEpiRows * kEpiPitch * 2;
-constexpr int kWgLdsBytes = kOperandBytes > kEpiBytes ? kOperandBytes : kEpiBytes;
-static_assert(kWgLdsBytes + kWgOut * 2 * 4 <= 65536, "static LDS");
-static_assert(kWgThreads == 256 && kWgIn == 256 && kWgOut == 128 && kWgTok == 32, "the thread-to-block maps below assume this shape");
+static_assert(kWgLdsBytes >= kEpiRows * kEpiPitch * 2, "the epilogue image reuses the operand stages");
+static_assert(kWgThreads == 512 && kWgIn == 256 && kWgOut == 256 && kWgTok == 32, "the thread-to-block maps below assume this shape");
 
-// LDS image of a stage: row = feature (X: 0..255, dY: 256..383), 32 tokens = 64 bytes in a pitch
+// LDS image of a stage: row = feature (X: 0..255, dY: 256..511), 32 tokens = 64 bytes in a pitch
 // of 72.  18 banks per row: a fragment read (32 lanes, 32 consecutive rows, 8 bytes each, twice)
 // touches every bank once, and a store of 8 rows x 64 bytes whose rows are 8 (or 4) apart touches
 // every bank twice — both the least possible.  Rows are 8-byte aligned only, so operands are
@@ -66,269 +68,7 @@ struct WgradArgs {
     int accumulate;
     int tiles_in;
     int64_t tiles;
-    int map;
 };
-
-template <int OUT>
-__global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kWgLdsBytes];
-    __shared__ int bounds[2 * kWgOut];
-
-    // Workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles so
-    // that the tiles sharing operand panels, and neighbouring runs of idx, meet in one L2.
-    const int64_t per_xcd = (A.tiles + 7) / 8;
-    const int64_t tile = A.map == 0 ? (int64_t)blockIdx.x : (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= A.tiles) return;
-    int row0, col0;
-    if (A.map == 2) {                                        // out-tiles fastest
-        const int tiles_out = (int)(A.tiles / A.tiles_in);
-        row0 = (int)(tile % tiles_out) * kWgOut;
-        col0 = (int)(tile / tiles_out) * kWgIn;
-    } else {
-        row0 = (int)(tile / A.tiles_in) * kWgOut;            // first row of dW (feature of dY)
-        col0 = (int)(tile % A.tiles_in) * kWgIn;             // first column of dW (feature of X)
-    }
-
-    const int t = threadIdx.x;
-    const int wave = t >> 6, lane = t & 63;
-    const int kg = lane & 7;          // which 4 tokens of the stage this thread moves
-    const int ml = lane >> 3;         // which feature block within the wave's share
-    const int64_t n = (int64_t)A.out * A.in;
-
-    // This thread's end of one row's run of idx (threads 0..127: start, 128..255: end), found by
-    // bisection inside the segment seg_ptr names.  The probes ride along with the main loop, one
-    // per stage, so that their latency costs nothing; what is left afterwards is finished there.
-    int s_lo = 0, s_hi = 0, s_key = 0;
-    {
-        const int r = row0 + (t & (kWgOut - 1));
-        if (r < A.out) {
-            const int c = t < kWgOut ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
-            const int64_t p = (int64_t)r * A.in + c;
-            if (p >= n) s_lo = s_hi = (int)A.nnz;
-            else if (!A.idx) s_lo = s_hi = (int)p;           // unpruned layer: position k is element k
-            else {
-                s_lo = A.seg_ptr[p / kSeg];
-                s_hi = A.seg_ptr[p / kSeg + 1];
-                s_key = (int)p;
-            }
-        }
-    }
-
-    // Global -> register -> LDS movers.  X: an 8-feature x 4-token block per thread (four 16-byte
-    // loads), dY: a 4-feature x 4-token block (four 8-byte loads); both transposed in registers so
-    // that LDS holds, per feature, tokens contiguously — what an MFMA operand lane needs.
-    // Addresses are a uniform per-stage base plus a 32-bit offset per lane that never changes.
-    // Features past the matrix are never gathered: their loads are only moved to a valid address.
-    const int xf = col0 + (wave * 8 + ml) * 8;               // first X feature of the block
-    const int yf = row0 + (wave * 8 + ml) * 4;               // first dY feature of the block
-    uint32_t xoff[4], yoff[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        xoff[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)A.in + (uint32_t)(xf < A.in ? xf : 0)) * 2u;
-        yoff[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)A.out + (uint32_t)(yf < A.out ? yf : 0)) * 2u;
-    }
-    const unsigned char *xbase = reinterpret_cast<const unsigned char *>(A.x);
-    const unsigned char *ybase = reinterpret_cast<const unsigned char *>(A.dy);
-    const int64_t xstage = (int64_t)kWgTok * A.in * 2, ystage = (int64_t)kWgTok * A.out * 2;   // bytes per stage
-    struct Regs {
-        uint4 x[4];
-        uint2 y[4];
-    };
-    auto load_full_stage = [&](Regs &q, int64_t stage) {
-        const unsigned char *xs = xbase + stage * xstage, *ys = ybase + stage * ystage;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            q.x[j] = *reinterpret_cast<const uint4 *>(xs + xoff[j]);
-            q.y[j] = *reinterpret_cast<const uint2 *>(ys + yoff[j]);
-        }
-    };
-    // The last stage when the token count is not a multiple of 32: rows past the end are read
-    // from the last token and cleared, so that they add nothing.
-    auto load_tail_stage = [&](Regs &q, int64_t stage) {
-        const unsigned char *xs = xbase + stage * xstage, *ys = ybase + stage * ystage;
-        const int rows = (int)(A.tokens - stage * kWgTok);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = kg * 4 + j;
-            const uint32_t keep = row < rows ? 0xffffffffu : 0u;
-            const uint32_t back = row < rows ? 0u : (uint32_t)(row - (rows - 1));
-            const uint4 xv = *reinterpret_cast<const uint4 *>(xs + (xoff[j] - back * (uint32_t)A.in * 2u));
-            const uint2 yv = *reinterpret_cast<const uint2 *>(ys + (yoff[j] - back * (uint32_t)A.out * 2u));
-            q.x[j] = make_uint4(xv.x & keep, xv.y & keep, xv.z & keep, xv.w & keep);
-            q.y[j] = make_uint2(yv.x & keep, yv.y & keep);
-        }
-    };
-    const int64_t full_stages = A.tokens / kWgTok;
-    const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;    // none: dW = 0
-    auto load_stage = [&](Regs &q, int64_t stage) {
-        if (stage < full_stages) load_full_stage(q, stage);
-        else load_tail_stage(q, stage);
-    };
-    // Two fp16 lanes of two registers into one: the low halves, or the high halves.
-    auto pack_lo = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); };
-    auto pack_hi = [](uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); };
-    auto store_stage = [&](const Regs &q, unsigned char *stage) {
-        {
-            const uint32_t d[4][4] = {{q.x[0].x, q.x[1].x, q.x[2].x, q.x[3].x}, {q.x[0].y, q.x[1].y, q.x[2].y, q.x[3].y},
-                                      {q.x[0].z, q.x[1].z, q.x[2].z, q.x[3].z}, {q.x[0].w, q.x[1].w, q.x[2].w, q.x[3].w}};
-            unsigned char *dst = stage + (wave * 8 + ml) * 8 * kRowBytes + kg * 8;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {                    // features 2e and 2e+1: tokens 0,1 | 2,3 of the block
-                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) = make_uint2(pack_lo(d[e][0], d[e][1]), pack_lo(d[e][2], d[e][3]));
-                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) = make_uint2(pack_hi(d[e][0], d[e][1]), pack_hi(d[e][2], d[e][3]));
-            }
-        }
-        {
-            const uint32_t d[2][4] = {{q.y[0].x, q.y[1].x, q.y[2].x, q.y[3].x}, {q.y[0].y, q.y[1].y, q.y[2].y, q.y[3].y}};
-            unsigned char *dst = stage + (kWgIn + (wave * 8 + ml) * 4) * kRowBytes + kg * 8;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                *reinterpret_cast<uint2 *>(dst + (2 * e) * kRowBytes) = make_uint2(pack_lo(d[e][0], d[e][1]), pack_lo(d[e][2], d[e][3]));
-                *reinterpret_cast<uint2 *>(dst + (2 * e + 1) * kRowBytes) = make_uint2(pack_hi(d[e][0], d[e][1]), pack_hi(d[e][2], d[e][3]));
-            }
-        }
-    };
-
-    // MFMA roles: the A operand (rows of a 32 x 32 block) takes X features, the B operand
-    // (columns) takes dY features, so that a lane ends up with 4 consecutive columns of one row
-    // of dW per accumulator quad.
-    const int wo = wave & 1, wi = wave >> 1;
-    const int l32 = lane & 31, khalf = lane >> 5;
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int bo = 0; bo < 2; ++bo)
-#pragma unroll
-        for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[bo][bi][r] = 0.f;
-    auto multiply_stage = [&](const unsigned char *cur) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int chunk = kk * 2 + khalf;
-            half8 xa[4], yb[2];
-#pragma unroll
-            for (int bi = 0; bi < 4; ++bi) xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
-#pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
-                yb[bo] = read_fragment(cur + stage_offset(kWgIn + wo * 64 + bo * 32 + l32, chunk));
-#pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
-#pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
-                    acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
-        }
-    };
-    // One bisection probe: issued with a stage's loads, resolved after that stage's arithmetic.
-    int s_mid = 0, s_val = 0;
-    bool s_open = false;
-    auto probe_issue = [&]() {
-        s_open = s_lo < s_hi;
-        s_mid = (s_lo + s_hi) >> 1;
-        if (s_open) s_val = A.idx[s_mid];
-    };
-    auto probe_resolve = [&]() {
-        if (s_open) {
-            if (s_val < s_key) s_lo = s_mid + 1;
-            else s_hi = s_mid;
-        }
-    };
-
-    // Main loop: two LDS stages, the next stage's loads in flight during a stage's arithmetic, one
-    // barrier per stage; written out for the two stages so that every LDS offset is a constant.
-    unsigned char *const buf0 = lds, *const buf1 = lds + kStageBytes;
-    Regs q;
-    if (stages > 0) {
-        load_stage(q, 0);
-        store_stage(q, buf0);
-    }
-    __syncthreads();
-    auto step = [&](const unsigned char *cur, unsigned char *nxt, int64_t next_stage) {
-        const bool more = next_stage < stages;
-        if (more) load_stage(q, next_stage);
-        probe_issue();
-        __builtin_amdgcn_sched_barrier(0);               // requests first, then the arithmetic that hides them
-        multiply_stage(cur);
-        if (more) store_stage(q, nxt);
-        __builtin_amdgcn_sched_barrier(0);               // the probe is used only behind the wait for the stage's loads
-        probe_resolve();
-        __syncthreads();
-    };
-    for (int64_t st = 0; st < stages; ++st) step((st & 1) ? buf1 : buf0, (st & 1) ? buf0 : buf1, st + 1);
-    while (s_lo < s_hi) {
-        probe_issue();
-        probe_resolve();
-    }
-
-    // Epilogue, 64 rows of dW per pass (the two waves that own them write, everyone gathers):
-    // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes 8 rows
-    // of a pass and fetches their index runs together before it touches the image.
-    bounds[t] = s_lo;
-    _Float16 *img = reinterpret_cast<_Float16 *>(lds);
-    const int hw = t >> 5;
-    constexpr int kRowsPerHalfWave = kEpiRows / 8;
-#pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
-        if (wo == pass) {
-#pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
-#pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        half4 h;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];   // round to nearest even
-                        const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
-                        *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kEpiPitch + col) = h;
-                    }
-        }
-        __syncthreads();
-        int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
-#pragma unroll
-        for (int it = 0; it < kRowsPerHalfWave; ++it) {
-            const int trow = pass * kEpiRows + it * 8 + hw;
-            lo[it] = bounds[trow];
-            hi[it] = bounds[kWgOut + trow];
-            longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
-        }
-        for (int off = l32; off - l32 < longest; off += 32) {
-            int pos[kRowsPerHalfWave];
-#pragma unroll
-            for (int it = 0; it < kRowsPerHalfWave; ++it) {
-                const int k = lo[it] + off;
-                pos[it] = k < hi[it] ? (A.idx ? A.idx[k] : k) : -1;
-            }
-#pragma unroll
-            for (int it = 0; it < kRowsPerHalfWave; ++it) {
-                if (pos[it] < 0) continue;
-                const int k = lo[it] + off;
-                const int rl = it * 8 + hw;
-                const int64_t base = (int64_t)(row0 + pass * kEpiRows + rl) * A.in + col0;
-                const _Float16 v = img[rl * kEpiPitch + (int)(pos[it] - base)];
-                if (OUT == kOutF32) {
-                    reinterpret_cast<float *>(A.gc)[k] = (float)v * A.inv_scale;
-                } else {
-                    _Float16 *dst = reinterpret_cast<_Float16 *>(A.gc) + k;
-                    *dst = A.accumulate ? (_Float16)(*dst + v) : v;
-                }
-            }
-        }
-        __syncthreads();
-    }
-}
-
-
-// ---------------------------------------------------------------------------------------------
-// Large-layer variant: a 256 x 256 tile per workgroup of 8 waves (each wave 64 x 128 as above).
-// Per stage a thread moves one 8-feature x 4-token block (16 registers), which leaves room to keep
-// the loads of TWO stages in flight.  Waves 0-3 move X, waves 4-7 move dY.
-constexpr int kBigOut = 256;
-constexpr int kBigIn = 256;
-constexpr int kBigThreads = 512;
-constexpr int kBigStageBytes = (kBigIn + kBigOut) * kRowBytes;
-constexpr int kBigLdsBytes = 2 * kBigStageBytes;
-static_assert(kBigLdsBytes >= kEpiBytes, "the epilogue image reuses the operand stages");
 
 struct Block8x4 {
     uint4 r[4];      // 4 tokens x 8 features
@@ -350,30 +90,41 @@ __device__ __forceinline__ void store_block(const Block8x4 &q, unsigned char *ds
 }
 
 template <int OUT>
-__global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradArgs A)
+__global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
-    __shared__ int bounds[2 * kBigOut];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ int bounds[2 * kWgOut];
 
+    // Workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles so
+    // that the tiles sharing operand panels, and neighbouring runs of idx, meet in one L2.
     const int64_t per_xcd = (A.tiles + 7) / 8;
     const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= A.tiles) return;
-    const int row0 = (int)(tile / A.tiles_in) * kBigOut;
-    const int col0 = (int)(tile % A.tiles_in) * kBigIn;
+    // Within the run, tiles go down groups of 4 tile rows before they go across: the 32 tiles an
+    // XCD works on at a time then share about 4 + 8 operand panels rather than 1 + 32.
+    const int tiles_out = (int)(A.tiles / A.tiles_in);
+    const int group = (int)(tile / (4 * A.tiles_in));
+    const int in_group = (int)(tile - (int64_t)group * 4 * A.tiles_in);
+    const int group_rows = tiles_out - group * 4 < 4 ? tiles_out - group * 4 : 4;
+    const int row0 = (group * 4 + in_group % group_rows) * kWgOut;   // first row of dW (feature of dY)
+    const int col0 = (in_group / group_rows) * kWgIn;                // first column of dW (feature of X)
 
     const int t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
     const int kg = lane & 7, ml = lane >> 3;
     const int64_t n = (int64_t)A.out * A.in;
 
+    // A row of the tile owns one contiguous run of idx.  This thread finds one end of one row's
+    // run (threads 0..255: the start, 256..511: the end) by bisection inside the segment that
+    // seg_ptr names; the probes ride along with the main loop.
     int s_lo = 0, s_hi = 0, s_key = 0;
     {
-        const int r = row0 + (t & (kBigOut - 1));
+        const int r = row0 + (t & (kWgOut - 1));
         if (r < A.out) {
-            const int c = t < kBigOut ? col0 : (col0 + kBigIn < A.in ? col0 + kBigIn : A.in);
+            const int c = t < kWgOut ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
             const int64_t p = (int64_t)r * A.in + c;
             if (p >= n) s_lo = s_hi = (int)A.nnz;
-            else if (!A.idx) s_lo = s_hi = (int)p;
+            else if (!A.idx) s_lo = s_hi = (int)p;           // unpruned layer: position k is element k
             else {
                 s_lo = A.seg_ptr[p / kSeg];
                 s_hi = A.seg_ptr[p / kSeg + 1];
@@ -382,7 +133,11 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
         }
     }
 
-    // Mover role of this thread: one 8-feature block of X (waves 0-3) or of dY (waves 4-7).
+    // Mover role of this thread: one 8-feature x 4-token block of X (waves 0-3) or of dY (waves
+    // 4-7) per stage: four 16-byte loads, transposed in registers so that LDS holds, per feature,
+    // tokens contiguously — what an MFMA operand lane needs.  Addresses are a uniform per-stage
+    // base plus a 32-bit offset per lane that never changes.  Features past the matrix are never
+    // gathered: their loads are only moved to a valid address.
     const bool moves_dy = wave >= 4;
     const int blk = (wave & 3) * 8 + ml;                                   // 0..31
     const int features = moves_dy ? A.out : A.in;
@@ -392,12 +147,14 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
     uint32_t off[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) off[j] = ((uint32_t)(kg * 4 + j) * (uint32_t)features + (uint32_t)(f < features ? f : 0)) * 2u;
-    const int lds_dst = ((moves_dy ? kBigIn : 0) + blk * 8) * kRowBytes + kg * 8;
+    const int lds_dst = ((moves_dy ? kWgIn : 0) + blk * 8) * kRowBytes + kg * 8;
     auto load_full = [&](Block8x4 &q, int64_t stage) {
         const unsigned char *sp = src + stage * stage_bytes;
 #pragma unroll
         for (int j = 0; j < 4; ++j) q.r[j] = *reinterpret_cast<const uint4 *>(sp + off[j]);
     };
+    // The last stage when the token count is not a multiple of 32: rows past the end are read
+    // from the last token and cleared, so that they add nothing.
     auto load_tail = [&](Block8x4 &q, int64_t stage) {
         const unsigned char *sp = src + stage * stage_bytes;
         const int rows = (int)(A.tokens - stage * kWgTok);
@@ -411,6 +168,10 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
         }
     };
 
+    // MFMA roles: the A operand (rows of a 32 x 32 block) takes X features, the B operand
+    // (columns) takes dY features, so that a lane ends up with 4 consecutive columns of one row
+    // of dW per accumulator quad.  Both operands give a lane the same 8 tokens (lanes 0-31 the
+    // first 8 of a group of 16, lanes 32-63 the rest), which is all the contraction needs.
     const int wo = wave & 3, wi = wave >> 2;
     const int l32 = lane & 31, khalf = lane >> 5;
     f32x16 acc[2][4];
@@ -429,7 +190,7 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
             for (int bi = 0; bi < 4; ++bi) xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
 #pragma unroll
             for (int bo = 0; bo < 2; ++bo)
-                yb[bo] = read_fragment(cur + stage_offset(kBigIn + wo * 64 + bo * 32 + l32, chunk));
+                yb[bo] = read_fragment(cur + stage_offset(kWgIn + wo * 64 + bo * 32 + l32, chunk));
 #pragma unroll
             for (int bo = 0; bo < 2; ++bo)
 #pragma unroll
@@ -460,7 +221,7 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
     // register set and stage s+2 is being requested into the other.  Inside the loop every load
     // is unconditional, so that the wait before a store to LDS can leave exactly the younger
     // stage's loads outstanding; the last two or three stages run after it.
-    unsigned char *const buf0 = big_lds, *const buf1 = big_lds + kBigStageBytes;
+    unsigned char *const buf0 = lds, *const buf1 = lds + kStageBytes;
     const int64_t full = A.tokens / kWgTok;
     Block8x4 qa, qb;
     if (full >= 2) {
@@ -517,9 +278,11 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
         else s_hi = mid;
     }
 
-    // Epilogue as in the small variant: 64 rows of dW per pass, 4 rows per half wave.
+    // Epilogue, 64 rows of dW per pass (the two waves that own them write, everyone gathers):
+    // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes 4 rows
+    // of a pass and fetches their index runs together before it touches the image.
     bounds[t] = s_lo;
-    _Float16 *img = reinterpret_cast<_Float16 *>(big_lds);
+    _Float16 *img = reinterpret_cast<_Float16 *>(lds);
     const int hw = t >> 5;                               // 0..15
     constexpr int kRowsPerHalfWave = kEpiRows / 16;
 #pragma unroll 1
@@ -544,7 +307,7 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
         for (int it = 0; it < kRowsPerHalfWave; ++it) {
             const int trow = pass * kEpiRows + it * 16 + hw;
             lo[it] = bounds[trow];
-            hi[it] = bounds[kBigOut + trow];
+            hi[it] = bounds[kWgOut + trow];
             longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
         }
         for (int off_k = l32; off_k - l32 < longest; off_k += 32) {
@@ -573,6 +336,7 @@ __global__ void __launch_bounds__(kBigThreads, 2) wgrad_big_kernel(const WgradAr
     }
 }
 
+
 }  // namespace
 
 hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
@@ -580,36 +344,22 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
                         int accumulate, hipStream_t s)
 {
     if (out <= 0 || in <= 0 || nnz <= 0) return hipSuccess;
+    static const hipError_t configured = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF32>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWgLdsBytes);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF16>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kWgLdsBytes);
+    }();
+    if (configured != hipSuccess) return configured;
     WgradArgs a;
     a.dy = dy; a.x = x; a.tokens = tokens; a.out = (int)out; a.in = (int)in;
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
-    static const int map = getenv("SAMO_WGRAD_MAP") ? atoi(getenv("SAMO_WGRAD_MAP")) : 1;
-    a.map = map;
-    const char *forced = getenv("SAMO_WGRAD_TILE");           // read per call: tests switch it
-    const int force_tile = forced ? atoi(forced) : 0;
-    const int64_t big_tiles = ceil_div(out, kBigOut) * ceil_div(in, kBigIn);
-    const bool big = force_tile != 128;   // measured: the large tile wins at every layer size, even at 16 tiles
-    if (big) {
-        static hipError_t configured = [] {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF32>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
-            if (e != hipSuccess) return e;
-            return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
-        }();
-        if (configured != hipSuccess) return configured;
-        a.tiles_in = (int)ceil_div(in, kBigIn);
-        a.tiles = big_tiles;
-        const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
-        if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kBigThreads), kBigLdsBytes, s>>>(a);
-        else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kBigThreads), kBigLdsBytes, s>>>(a);
-        return hipGetLastError();
-    }
     a.tiles_in = (int)ceil_div(in, kWgIn);
     a.tiles = ceil_div(out, kWgOut) * a.tiles_in;
-    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
-    if (out_kind == kOutF32) wgrad_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
-    else wgrad_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), 0, s>>>(a);
+    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);   // whole rounds of the 8 XCDs; the surplus exits at once
+    if (out_kind == kOutF32) wgrad_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kWgLdsBytes, s>>>(a);
+    else wgrad_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kWgLdsBytes, s>>>(a);
     return hipGetLastError();
 }
 
