@@ -297,10 +297,11 @@ samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_facto
 
 /* ---------------------------------------------------------------- compression inside the backward pass
  * (Section III-C: a layer's dense gradient is compressed as soon as the backward
- * pass has produced it; Section V, discussion of the compute overhead: fusing
+ * pass has produced it; Section VI-C, discussion of the compute overhead: fusing
  * that compression into the backward kernel is what would remove it.)
  * Weight gradient of a fully connected layer Y = X W^T with W of out x in
- * (Section II-A), formed and compressed in one kernel: with
+ * (Section I describes the layer as a linear transform of its input; the layout
+ * convention is the frameworks' usual one), formed and compressed in one kernel: with
  *   dW[o][i] = sum over t < tokens of dY[t][o] * X[t][i]   (fp16 products, fp32 sums),
  * position o * in + i of the layer, and h = fp16(dW) rounded once to nearest
  * even (the value the dense fp16 gradient tensor would have held),

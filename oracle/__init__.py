@@ -328,9 +328,10 @@ def _f16_matrix(bits: np.ndarray, rows: int, cols: int) -> np.ndarray:
 
 
 def linear_weight_grad(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_features: int) -> np.ndarray:
-    """Gradient of a fully connected layer's weight (Section II-A: Y = X W^T for W of shape
-    out x in): dW[o, i] = sum over tokens t of dY[t, o] * X[t, i], in double precision from the
-    fp16 operands (dy: tokens x out, x: tokens x in, both row-major fp16 bit patterns).
+    """Gradient of a fully connected layer's weight (Section I: a linear transform of the layer's
+    input; taken as Y = X W^T for W of shape out x in, the usual framework convention):
+    dW[o, i] = sum over tokens t of dY[t, o] * X[t, i], in double precision from the fp16
+    operands (dy: tokens x out, x: tokens x in, both row-major fp16 bit patterns).
     Returned flattened row-major, as the layer's index counts positions."""
     a = _f16_matrix(dy, tokens, out_features)
     b = _f16_matrix(x, tokens, in_features)

@@ -1,6 +1,6 @@
 // Weight gradient of a fully connected layer written straight into the compressed gradient
 // (Section III-C compresses each layer's dense fp16 gradient as soon as the backward pass has
-// produced it; the paper's closing discussion of the compute overhead names fusing that
+// produced it; Section VI-C, on the compute overhead of that compression, names fusing that
 // compression into the backward kernels as the way to remove it).  dW = dY^T X is a dense
 // contraction over the tokens: MFMA 32x32x16 fp16 with fp32 accumulation, operands staged through
 // LDS; the epilogue rounds each accumulator once to fp16 — the value the dense gradient tensor

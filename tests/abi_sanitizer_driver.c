@@ -68,6 +68,17 @@ int main(void)
     EXPECT(samo_fused_step_fp32(fake, NULL, 10, fake, fake, 5, fake, fake, 1.0f, &adam, NULL), SAMO_ERR_NULL);
     EXPECT(samo_fused_step_fp32(fake, fake, 10, fake, fake, 5, fake, fake, INFINITY, &adam, NULL), SAMO_ERR_ARG);
     EXPECT(samo_fused_step_fp32(fake, fake, 10, fake, fake, 5, odd, fake, 1.0f, &adam, NULL), SAMO_ERR_ALIGN);
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 12, NULL, NULL, 96, 1.0f, fake, NULL), SAMO_ERR_SIZE);      /* in % 8 */
+    EXPECT(samo_wgrad_gather(fake, fake, -1, 8, 16, NULL, NULL, 128, 1.0f, fake, NULL), SAMO_ERR_SIZE);
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 65536, 65536, NULL, NULL, 1, 1.0f, fake, NULL), SAMO_ERR_SIZE); /* out * in >= 2^31 */
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 16, NULL, NULL, 90, 1.0f, fake, NULL), SAMO_ERR_NULL);       /* no index, nnz < out * in */
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 16, fake, NULL, 90, 1.0f, fake, NULL), SAMO_ERR_NULL);       /* index without seg_ptr */
+    EXPECT(samo_wgrad_gather(NULL, fake, 4, 8, 16, fake, fake, 90, 1.0f, fake, NULL), SAMO_ERR_NULL);
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 16, fake, fake, 90, 0.0f, fake, NULL), SAMO_ERR_ARG);
+    EXPECT(samo_wgrad_gather(fake, odd, 4, 8, 16, fake, fake, 90, 1.0f, fake, NULL), SAMO_ERR_ALIGN);
+    EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 16, fake, fake, 0, 1.0f, NULL, NULL), SAMO_OK);              /* nothing kept: nothing to do */
+    EXPECT(samo_wgrad_gather_fp16(fake, fake, 4, 8, 16, fake, fake, 90, NULL, 0, NULL), SAMO_ERR_NULL);
+    EXPECT(samo_wgrad_gather_fp16(fake, fake, 4, 8, 16, fake, fake, 129, fake, 1, NULL), SAMO_ERR_SIZE);
 
     {
         samo_layer layers[2];

@@ -1,5 +1,5 @@
 """GPU parity of the weight gradient formed and compressed in one kernel (compression fused into
-the backward pass: Section III-C and the paper's discussion of its compute overhead) against the
+the backward pass: Section III-C, and Section VI-C on its compute overhead) against the
 CPU oracle, through the C ABI."""
 import numpy as np
 import pytest

@@ -1,6 +1,6 @@
 """Pins of the oracle's weight-gradient + compression functions: the backward pass of a fully
-connected layer (Section II-A) followed by the compression of Section III-C, which the paper's
-closing discussion names as the candidate for fusion into the backward kernels."""
+connected layer (Section I: a linear transform of its input) followed by the compression of
+Section III-C, which Section VI-C names as the candidate for fusion into the backward kernels."""
 import numpy as np
 import pytest
 import torch
