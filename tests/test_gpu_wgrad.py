@@ -193,3 +193,58 @@ def test_rejections():
         samo.samo_wgrad_gather(dy, x, idx, None, 1.0, gc[:90])       # an index without seg_ptr
     with pytest.raises(samo.SamoError):
         samo.samo_wgrad_gather(dy, x, None, None, 0.0, torch.zeros(128, dtype=torch.float32, device=DEV))
+
+
+def test_fused_backward_compression_feeds_statistics_and_the_optimizer():
+    """Two micro-batches of a three-layer model, the gradient of every layer compressed inside its
+    backward kernel into the stored fp16 gradient (the second micro-batch accumulated), then the
+    batched statistics, clipping and Adam + expansion — against the oracle's unfused route through
+    a dense fp16 gradient.  Small-integer operands make every weight gradient exact in fp16, so
+    the comparison does not depend on the order of the kernel's sums."""
+    from gpu_util import INV, OCFG, DevLayer, HostLayer, assert_close
+    shapes = [(136, 264, 0.2, False), (264, 72, 0.5, False), (24, 40, 1.0, True)]      # (out, in, keep, unpruned)
+    tokens = 70
+    hosts, devs, ops = [], [], []
+    rng = np.random.default_rng(31)
+    for k, (out_f, in_f, keep, dense) in enumerate(shapes):
+        n = out_f * in_f
+        mask = np.ones(n, np.uint8) if dense else si.bernoulli_mask(n, keep, 40 + k)
+        hosts.append(HostLayer(n, mask, si.weights(n, 40 + k), 40 + k, dense=dense))
+        devs.append(DevLayer(hosts[-1], with_gc16=True))
+        ops.append([(rng.integers(-2, 3, (tokens, out_f)).astype(np.float16), rng.integers(-3, 4, (tokens, in_f)).astype(np.float16))
+                    for _ in range(2)])
+    plan = samo.Plan([d.layer() for d in devs])
+    stats = samo.GradStats(plan)
+    # backward passes: micro-batch 0 overwrites, micro-batch 1 accumulates
+    ref_gc16 = []
+    for (out_f, in_f, _, _), h, d, mb in zip(shapes, hosts, devs, ops):
+        acc = None
+        for j, (dy, x) in enumerate(mb):
+            dyb, xb = dy.reshape(-1).view(np.uint16), x.reshape(-1).view(np.uint16)
+            samo.samo_wgrad_gather_fp16(dev_f16_bits(dyb).view(tokens, out_f), dev_f16_bits(xb).view(tokens, in_f),
+                                        d.idx, d.seg_ptr, d.gc16, accumulate=j > 0)
+            dense16 = oracle.linear_weight_grad(dyb, xb, tokens, out_f, in_f).astype(np.float16).view(np.uint16)
+            if acc is None:
+                acc = oracle.compress_f16(dense16, h.idx)
+            else:
+                oracle.accumulate_f16(dense16, h.idx, acc)
+        ref_gc16.append(acc)
+        assert np.array_equal(host_bits(d.gc16), acc)                   # exact sums: bit-exact
+    # statistics over the stored fp16 gradient, then clipped Adam + expansion
+    plan.samo_grad_stats_batched(1, INV, stats)
+    total = sum(oracle.sum_squares(oracle.upcast(g, INV)) for g in ref_gc16)
+    ss, bad = stats.read()
+    assert not bad and abs(ss - total) <= 1e-12 * total
+    max_norm = 0.25 * total ** 0.5
+    plan.samo_adam_expand_batched(INV, samo.adam_cfg(1, **si.ADAM), stats.guard(max_grad_norm=max_norm))
+    torch.cuda.synchronize()
+    coef = oracle.clip_coefficient(total, max_norm)
+    for h, d, g in zip(hosts, devs, ref_gc16):
+        gc = oracle.upcast(g, INV)
+        oracle.scale(gc, coef)
+        oracle.adam(h.p, h.m, h.v, gc, OCFG, 1)
+        assert_close(d.p.cpu().numpy(), h.p, "p")
+        assert_close(d.m.cpu().numpy(), h.m, "m")
+        assert_close(d.v.cpu().numpy(), h.v, "v")
+        assert np.array_equal(host_bits(d.w), oracle.decompress(d.p.cpu().numpy(), h.idx, h.n))
+    plan.close()
