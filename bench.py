@@ -241,6 +241,29 @@ def main():
             mfma_entry("library GEMM (dense fp16 dW) + samo_gather_grads", time_entry(library_path))
             mfma_entry("library GEMM alone", time_entry(lambda: torch.matmul(dy.t(), xa, out=dense_g)))
             del dy, xa
+            # the same two routes over the pruned matrices of the first transformer layer, launched back to back
+            block = cand[:4]
+            ops = []
+            for j in block:
+                r, c = specs[j].rows, specs[j].cols
+                ops.append((layers[j],
+                            torch.from_numpy(si.output_grads_fp16(tokens, r, 2 + j).view(np.int16)).to(dev).view(torch.float16).view(tokens, r),
+                            torch.from_numpy(si.activations_fp16(tokens, c, 2 + j).view(np.int16)).to(dev).view(torch.float16).view(tokens, c)))
+            flops = sum(2.0 * tokens * Lj.n for Lj, _, _ in ops)
+
+            def fused_block():
+                for Lj, dyj, xj in ops:
+                    samo.samo_wgrad_gather(dyj, xj, Lj.idx, Lj.seg_ptr, inv, Lj.gc)
+
+            def library_block():
+                for Lj, dyj, xj in ops:
+                    torch.matmul(dyj.t(), xj, out=Lj.g.view(dyj.shape[1], xj.shape[1]))
+                    samo.samo_gather_grads(Lj.g, Lj.idx, inv, Lj.gc)
+            mfma_entries["block"] = "%s: %d matrices, %.1f M elements, %d tokens" % (
+                ", ".join(specs[j].name for j in block), len(block), sum(Lj.n for Lj, _, _ in ops) / 1e6, tokens)
+            mfma_entry("samo_wgrad_gather over the block", time_entry(fused_block))
+            mfma_entry("library GEMM + samo_gather_grads over the block", time_entry(library_block))
+            del ops
 
     achieved = fused_bytes / kernel_ms / 1e6
     traffic = None

@@ -316,7 +316,9 @@ samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_facto
  * with out * in < 2^31; tokens >= 0 (0: every dW is +0).  d_idx / d_seg_ptr
  * describe the layer of n = out * in elements as everywhere else; d_idx may be
  * NULL only when nnz == out * in (unpruned layer), d_seg_ptr is required
- * whenever d_idx is given.  Nothing is written when nnz == 0. */
+ * whenever d_idx is given.  Nothing is written when nnz == 0.
+ * The first call in a process configures the kernel's LDS size (a HIP function
+ * attribute): make it outside stream capture; later calls only enqueue. */
 samo_status samo_wgrad_gather(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens,
                               int64_t out, int64_t in, const int32_t *d_idx,
                               const int32_t *d_seg_ptr, int64_t nnz, float inv_loss_scale,

@@ -248,3 +248,59 @@ def test_fused_backward_compression_feeds_statistics_and_the_optimizer():
         assert_close(d.v.cpu().numpy(), h.v, "v")
         assert np.array_equal(host_bits(d.w), oracle.decompress(d.p.cpu().numpy(), h.idx, h.n))
     plan.close()
+
+
+def test_fused_weight_gradient_under_hip_graph_replay():
+    """The backward kernel, the statistics and the guarded optimizer phase captured once and
+    replayed with eager work in between; every replay equals the eager result bit for bit."""
+    from gpu_util import INV, DevLayer, HostLayer
+    out_f, in_f, tokens = 264, 520, 100
+    n = out_f * in_f
+    h = HostLayer(n, si.bernoulli_mask(n, 0.15, 71), si.weights(n, 71), 71)
+    a, b = DevLayer(h, with_gc16=True), DevLayer(h, with_gc16=True)
+    plan_a, plan_b = samo.Plan([a.layer()]), samo.Plan([b.layer()])
+    stats_a, stats_b = samo.GradStats(plan_a), samo.GradStats(plan_b)
+    dy = torch.empty((tokens, out_f), dtype=torch.float16, device=DEV)
+    x = torch.empty((tokens, in_f), dtype=torch.float16, device=DEV)
+    cfg = samo.adam_cfg(1, **si.ADAM)
+
+    def work(d, plan, stats):
+        samo.samo_wgrad_gather_fp16(dy, x, d.idx, d.seg_ptr, d.gc16)
+        plan.samo_grad_stats_batched(1, INV, stats)
+        plan.samo_adam_expand_batched(INV, cfg, stats.guard(max_grad_norm=0.5, skip_on_nonfinite=True))
+
+    def feed(step):
+        dy.copy_(dev_f16_bits(si.output_grads_fp16(tokens, out_f, 71, step)).view(tokens, out_f))
+        x.copy_(dev_f16_bits(si.activations_fp16(tokens, in_f, 71, step)).view(tokens, in_f))
+
+    feed(1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work(a, plan_a, stats_a)                                       # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work(a, plan_a, stats_a)
+    work(b, plan_b, stats_b)                                           # both sides have taken step 1 once...
+    graph.replay()
+    work(b, plan_b, stats_b)                                           # ...and twice
+    for step in (2, 3, 4):
+        feed(step)
+        a.w.fill_(float("nan"))
+        b.w.fill_(float("nan"))
+        torch.cuda.synchronize()
+        work(b, plan_b, stats_b)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert stats_a.read() == stats_b.read(), step
+        assert torch.equal(a.gc16.view(torch.int16), b.gc16.view(torch.int16)), step
+        assert torch.equal(a.p, b.p) and torch.equal(a.m, b.m) and torch.equal(a.v, b.v), step
+        assert torch.equal(a.w.view(torch.int16), b.w.view(torch.int16)), step
+    # the eager side once more against the oracle: its last compressed gradient
+    lo, hi = _bracket(si.output_grads_fp16(tokens, out_f, 71, 4), si.activations_fp16(tokens, in_f, 71, 4), tokens, out_f, in_f, h.idx)
+    got = host_bits(b.gc16).view(np.float16)
+    assert np.all((got >= lo) & (got <= hi))
+    plan_a.close()
+    plan_b.close()
