@@ -235,23 +235,36 @@ def samo_build_index_into(mask: torch.Tensor, idx: torch.Tensor, seg_ptr: torch.
                                   _dev(nnz_out, torch.int64, "nnz_out", 1), _stream()), "samo_build_index")
 
 
+class IndexJobs:
+    """The marshalled argument of samo_build_index_batched: the C job table plus references that
+    keep its tensors alive.  Build it once, launch it as often as needed."""
+
+    def __init__(self, masks: Sequence[torch.Tensor], idxs: Sequence[Optional[torch.Tensor]],
+                 seg_ptrs: Sequence[torch.Tensor], nnz_out: torch.Tensor):
+        k = len(masks)
+        if not (len(idxs) == len(seg_ptrs) == k):
+            raise ValueError("masks, idxs and seg_ptrs differ in length")
+        nnz_ptr = _dev(nnz_out, torch.int64, "nnz_out", k) if k else None
+        jobs = (IndexJob * max(k, 1))()
+        for i in range(k):
+            n = masks[i].numel()
+            jobs[i].mask = _dev(masks[i], torch.uint8, "mask")
+            jobs[i].n = n
+            jobs[i].idx = _dev(idxs[i], torch.int32, "idx")
+            jobs[i].idx_capacity = idxs[i].numel() if idxs[i] is not None else 0
+            jobs[i].seg_ptr = _dev(seg_ptrs[i], torch.int32, "seg_ptr", samo_seg_ptr_len(n))
+            jobs[i].nnz = nnz_ptr + 8 * i
+        self.jobs, self.count = jobs, k
+        self._keep = (list(masks), list(idxs), list(seg_ptrs), nnz_out)
+
+    def launch(self) -> None:
+        _check(lib().samo_build_index_batched(self.jobs, self.count, _stream()), "samo_build_index_batched")
+
+
 def samo_build_index_batched(masks: Sequence[torch.Tensor], idxs: Sequence[Optional[torch.Tensor]],
                              seg_ptrs: Sequence[torch.Tensor], nnz_out: torch.Tensor) -> None:
     """Raw batched form: one job per mask; idxs[i] may be None (count only); nnz_out is int64[len(masks)]."""
-    k = len(masks)
-    if not (len(idxs) == len(seg_ptrs) == k):
-        raise ValueError("masks, idxs and seg_ptrs differ in length")
-    nnz_ptr = _dev(nnz_out, torch.int64, "nnz_out", k) if k else None
-    jobs = (IndexJob * max(k, 1))()
-    for i in range(k):
-        n = masks[i].numel()
-        jobs[i].mask = _dev(masks[i], torch.uint8, "mask")
-        jobs[i].n = n
-        jobs[i].idx = _dev(idxs[i], torch.int32, "idx")
-        jobs[i].idx_capacity = idxs[i].numel() if idxs[i] is not None else 0
-        jobs[i].seg_ptr = _dev(seg_ptrs[i], torch.int32, "seg_ptr", samo_seg_ptr_len(n))
-        jobs[i].nnz = nnz_ptr + 8 * i
-    _check(lib().samo_build_index_batched(jobs, k, _stream()), "samo_build_index_batched")
+    IndexJobs(masks, idxs, seg_ptrs, nnz_out).launch()
 
 
 def samo_build_index_many(masks: Sequence[torch.Tensor]) -> list:
