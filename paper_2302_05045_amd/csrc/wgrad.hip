@@ -6,6 +6,8 @@
 // LDS; the epilogue rounds each accumulator once to fp16 — the value the dense gradient tensor
 // would have held — and stores only the entries the layer's index keeps.  The dense gradient is
 // never written to or read back from HBM.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace samo {
@@ -15,29 +17,47 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// Workgroup tile: 256 rows of dW (features of dY) by 256 columns (features of X), 8 waves as 4 x 2,
-// each 64 x 128 = 2 x 4 MFMA blocks (128 accumulator registers per lane, two waves per SIMD).
-// 32 tokens per stage, two stages in LDS, the loads of two further stages in flight in registers:
-// per stage a thread moves one 8-feature x 4-token block (16 registers; waves 0-3 move X, waves
-// 4-7 move dY).  Measured on MI355X against the alternatives that were built and dropped: a
-// 128 x 256 tile by 4 waves, two workgroups per compute unit, with one stage of loads in flight
-// (all its registers allow) reaches 0.6 of this one's rate at every layer size, down to 16 tiles;
-// the same 256 x 256 tile by 4 waves of 128 x 128 (256 accumulators, one wave per SIMD, half the
-// LDS reads per MFMA) reaches 0.9 — a lone wave per SIMD leaves its LDS stores, barrier and first
-// fragment reads of every stage uncovered.
-constexpr int kWgOut = 256;
-constexpr int kWgIn = 256;
+// Workgroup tile, large shape: 256 rows of dW (features of dY) by 256 columns (features of X), 8
+// waves as 4 x 2, each 64 x 128 = 2 x 4 MFMA blocks (128 accumulator registers per lane, two waves
+// per SIMD, one workgroup per CU).  32 tokens per stage, two stages in LDS, the loads of two
+// further stages in flight in registers: per stage a thread moves one 8-feature x 4-token block
+// (16 registers; the first half of the threads move X, the rest dY).  Small shape, for layers
+// whose large tiles would leave compute units idle: 128 x 128 by 4 waves of 64 x 64, three
+// workgroups per CU; it tops out at 0.6 of the large shape's rate (a third more LDS bytes per
+// MFMA, twice the operand traffic) but is twice as fast on a 1024 x 4096 layer (64 large tiles).
+// Measured on MI355X against the alternatives that were built and dropped: a 128 x 256 tile by 4
+// waves, two workgroups per compute unit, with one stage of loads in flight (all its registers
+// allow) reaches 0.6 of the large shape's rate at every layer size; the same 256 x 256 tile by 4
+// waves of 128 x 128 (256 accumulators, one wave per SIMD, a third less LDS traffic) reaches 0.9
+// — a lone wave per SIMD leaves its LDS stores, barrier and first fragment reads of every stage
+// uncovered.
 constexpr int kWgTok = 32;
-constexpr int kWgThreads = 512;
 constexpr int kRowBytes = kWgTok * 2 + 8;                    // one feature's 32 tokens, padded: see stage_offset
-constexpr int kStageBytes = (kWgIn + kWgOut) * kRowBytes;    // X rows, then dY rows
-constexpr int kWgLdsBytes = 2 * kStageBytes;                 // dynamic LDS: above the 64 KiB a static array may have
 constexpr int kEpiRows = 64;                                 // rows of dW staged per epilogue pass
-constexpr int kEpiPitch = kWgIn + 8;                         // halves; +8 spreads a column of 32 rows over the banks
-static_assert(kWgLdsBytes >= kEpiRows * kEpiPitch * 2, "the epilogue image reuses the operand stages");
-static_assert(kWgThreads == 512 && kWgIn == 256 && kWgOut == 256 && kWgTok == 32, "the thread-to-block maps below assume this shape");
 
-// LDS image of a stage: row = feature (X: 0..255, dY: 256..511), 32 tokens = 64 bytes in a pitch
+// A tile shape: WO x WI waves, each BO x BI blocks of 32 x 32.  Every thread moves exactly one
+// 8-feature block per stage and finds exactly one bound of the epilogue, so the tile's rows and
+// columns together must equal the thread count.
+template <int WO_, int WI_, int BO_, int BI_>
+struct TileShape {
+    static constexpr int WO = WO_, WI = WI_, BO = BO_, BI = BI_;
+    static constexpr int kOut = WO * BO * 32;                // rows of dW per workgroup (features of dY)
+    static constexpr int kIn = WI * BI * 32;                 // columns of dW per workgroup (features of X)
+    static constexpr int kThreads = WO * WI * 64;
+    static constexpr int kStageBytes = (kIn + kOut) * kRowBytes;     // X rows, then dY rows
+    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kEpiPitch = kIn + 8;                // halves; +8 spreads a column of 32 rows over the banks
+    static constexpr int kMinWaves = kThreads / 256;         // waves per SIMD of one workgroup
+    static_assert(kIn + kOut == kThreads && 2 * kOut == kThreads, "one block to move and one bound to find per thread");
+    static_assert(BO * 32 == kEpiRows, "an epilogue pass is the rows of one wave row");
+    static_assert(kLdsBytes >= kEpiRows * kEpiPitch * 2, "the epilogue image reuses the operand stages");
+    static_assert(kOut % 64 == 0 && kThreads % 32 == 0 && kEpiRows % (kThreads / 32) == 0, "epilogue row split");
+};
+using BigTile = TileShape<4, 2, 2, 4>;      // 256 x 256, 8 waves of 64 x 128: 128 accumulator registers, one workgroup per CU
+using SmallTile = TileShape<2, 2, 2, 2>;    // 128 x 128, 4 waves of 64 x 64: layers whose 256 x 256 tiles would leave CUs idle
+constexpr int64_t kSmallTileBelow = 160;    // 256 x 256 tiles of a layer below which the small shape is used (measured)
+
+// LDS image of a stage: row = feature (X rows first, then dY rows), 32 tokens = 64 bytes in a pitch
 // of 72.  18 banks per row: a fragment read (32 lanes, 32 consecutive rows, 8 bytes each, twice)
 // touches every bank once, and a store of 8 rows x 64 bytes whose rows are 8 (or 4) apart touches
 // every bank twice — both the least possible.  Rows are 8-byte aligned only, so operands are
@@ -89,9 +109,10 @@ __device__ __forceinline__ void store_block(const Block8x4 &q, unsigned char *ds
     }
 }
 
-template <int OUT>
-__global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
+template <int OUT, typename T>
+__global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A)
 {
+    constexpr int kWgOut = T::kOut, kWgIn = T::kIn, kStageBytes = T::kStageBytes, kEpiPitch = T::kEpiPitch;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int bounds[2 * kWgOut];
 
@@ -111,11 +132,11 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
 
     const int t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
-    const int kg = lane & 7, ml = lane >> 3;
+    const int kg = lane & 7;          // which 4 tokens of the stage this thread moves
     const int64_t n = (int64_t)A.out * A.in;
 
     // A row of the tile owns one contiguous run of idx.  This thread finds one end of one row's
-    // run (threads 0..255: the start, 256..511: the end) by bisection inside the segment that
+    // run (the first half of the threads: the start, the rest: the end) by bisection inside the segment that
     // seg_ptr names; the probes ride along with the main loop.
     int s_lo = 0, s_hi = 0, s_key = 0;
     {
@@ -133,13 +154,13 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
         }
     }
 
-    // Mover role of this thread: one 8-feature x 4-token block of X (waves 0-3) or of dY (waves
-    // 4-7) per stage: four 16-byte loads, transposed in registers so that LDS holds, per feature,
+    // Mover role of this thread: one 8-feature x 4-token block of X (the first waves) or of dY (the
+    // rest) per stage: four 16-byte loads, transposed in registers so that LDS holds, per feature,
     // tokens contiguously — what an MFMA operand lane needs.  Addresses are a uniform per-stage
     // base plus a 32-bit offset per lane that never changes.  Features past the matrix are never
     // gathered: their loads are only moved to a valid address.
-    const bool moves_dy = wave >= 4;
-    const int blk = (wave & 3) * 8 + ml;                                   // 0..31
+    const bool moves_dy = t >= kWgIn;                                      // uniform within a wave
+    const int blk = (moves_dy ? t - kWgIn : t) >> 3;                       // which 8 features of its operand's tile
     const int features = moves_dy ? A.out : A.in;
     const int f = (moves_dy ? row0 : col0) + blk * 8;
     const unsigned char *src = reinterpret_cast<const unsigned char *>(moves_dy ? A.dy : A.x);
@@ -172,29 +193,30 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
     // (columns) takes dY features, so that a lane ends up with 4 consecutive columns of one row
     // of dW per accumulator quad.  Both operands give a lane the same 8 tokens (lanes 0-31 the
     // first 8 of a group of 16, lanes 32-63 the rest), which is all the contraction needs.
-    const int wo = wave & 3, wi = wave >> 2;
+    constexpr int BO = T::BO, BI = T::BI;
+    const int wo = wave % T::WO, wi = wave / T::WO;
     const int l32 = lane & 31, khalf = lane >> 5;
-    f32x16 acc[2][4];
+    f32x16 acc[BO][BI];
 #pragma unroll
-    for (int bo = 0; bo < 2; ++bo)
+    for (int bo = 0; bo < BO; ++bo)
 #pragma unroll
-        for (int bi = 0; bi < 4; ++bi)
+        for (int bi = 0; bi < BI; ++bi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[bo][bi][r] = 0.f;
     auto multiply_stage = [&](const unsigned char *cur) {
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int chunk = kk * 2 + khalf;
-            half8 xa[4], yb[2];
+            half8 xa[BI], yb[BO];
 #pragma unroll
-            for (int bi = 0; bi < 4; ++bi) xa[bi] = read_fragment(cur + stage_offset(wi * 128 + bi * 32 + l32, chunk));
+            for (int bi = 0; bi < BI; ++bi) xa[bi] = read_fragment(cur + stage_offset((wi * BI + bi) * 32 + l32, chunk));
 #pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
-                yb[bo] = read_fragment(cur + stage_offset(kWgIn + wo * 64 + bo * 32 + l32, chunk));
+            for (int bo = 0; bo < BO; ++bo)
+                yb[bo] = read_fragment(cur + stage_offset(kWgIn + (wo * BO + bo) * 32 + l32, chunk));
 #pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
+            for (int bo = 0; bo < BO; ++bo)
 #pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
+                for (int bi = 0; bi < BI; ++bi)
                     acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
         }
     };
@@ -278,26 +300,27 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
         else s_hi = mid;
     }
 
-    // Epilogue, 64 rows of dW per pass (the two waves that own them write, everyone gathers):
-    // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes 4 rows
-    // of a pass and fetches their index runs together before it touches the image.
+    // Epilogue, 64 rows of dW per pass (the waves that own them write, everyone gathers):
+    // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes its
+    // share of the rows of a pass and fetches their index runs together before it touches the image.
     bounds[t] = s_lo;
     _Float16 *img = reinterpret_cast<_Float16 *>(lds);
-    const int hw = t >> 5;                               // 0..15
-    constexpr int kRowsPerHalfWave = kEpiRows / 16;
+    const int hw = t >> 5;
+    constexpr int kHalfWaves = T::kThreads / 32;
+    constexpr int kRowsPerHalfWave = kEpiRows / kHalfWaves;
 #pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
+    for (int pass = 0; pass < T::WO; ++pass) {
         if (wo == pass) {
 #pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
+            for (int bo = 0; bo < BO; ++bo)
 #pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
+                for (int bi = 0; bi < BI; ++bi)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         half4 h;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];
-                        const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
+                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];   // round to nearest even
+                        const int col = (wi * BI + bi) * 32 + q * 8 + khalf * 4;
                         *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kEpiPitch + col) = h;
                     }
         }
@@ -305,7 +328,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
         int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
 #pragma unroll
         for (int it = 0; it < kRowsPerHalfWave; ++it) {
-            const int trow = pass * kEpiRows + it * 16 + hw;
+            const int trow = pass * kEpiRows + it * kHalfWaves + hw;
             lo[it] = bounds[trow];
             hi[it] = bounds[kWgOut + trow];
             longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
@@ -321,7 +344,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
             for (int it = 0; it < kRowsPerHalfWave; ++it) {
                 if (pos[it] < 0) continue;
                 const int k = lo[it] + off_k;
-                const int rl = it * 16 + hw;
+                const int rl = it * kHalfWaves + hw;
                 const int64_t base = (int64_t)(row0 + pass * kEpiRows + rl) * A.in + col0;
                 const _Float16 v = img[rl * kEpiPitch + (int)(pos[it] - base)];
                 if (OUT == kOutF32) {
@@ -337,6 +360,25 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_kernel(const WgradArgs A)
 }
 
 
+template <typename T>
+hipError_t launch_shape(int out_kind, WgradArgs a, int64_t out, int64_t in, hipStream_t s)
+{
+    static const hipError_t configured = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF32, T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF16, T>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+    }();
+    if (configured != hipSuccess) return configured;
+    a.tiles_in = (int)ceil_div(in, T::kIn);
+    a.tiles = ceil_div(out, T::kOut) * a.tiles_in;
+    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);   // whole rounds of the 8 XCDs; the surplus exits at once
+    if (out_kind == kOutF32) wgrad_kernel<kOutF32, T><<<dim3(grid), dim3(T::kThreads), T::kLdsBytes, s>>>(a);
+    else wgrad_kernel<kOutF16, T><<<dim3(grid), dim3(T::kThreads), T::kLdsBytes, s>>>(a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
@@ -344,23 +386,15 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
                         int accumulate, hipStream_t s)
 {
     if (out <= 0 || in <= 0 || nnz <= 0) return hipSuccess;
-    static const hipError_t configured = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF32>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kWgLdsBytes);
-        if (e != hipSuccess) return e;
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF16>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kWgLdsBytes);
-    }();
-    if (configured != hipSuccess) return configured;
     WgradArgs a;
     a.dy = dy; a.x = x; a.tokens = tokens; a.out = (int)out; a.in = (int)in;
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
-    a.tiles_in = (int)ceil_div(in, kWgIn);
-    a.tiles = ceil_div(out, kWgOut) * a.tiles_in;
-    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);   // whole rounds of the 8 XCDs; the surplus exits at once
-    if (out_kind == kOutF32) wgrad_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kWgLdsBytes, s>>>(a);
-    else wgrad_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kWgLdsBytes, s>>>(a);
-    return hipGetLastError();
+    a.tiles_in = 0; a.tiles = 0;
+    const int64_t big_tiles = ceil_div(out, BigTile::kOut) * ceil_div(in, BigTile::kIn);
+    const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128 or 256
+    const int force = forced ? atoi(forced) : 0;
+    const bool small = force == 128 || (force != 256 && big_tiles < kSmallTileBelow);
+    return small ? launch_shape<SmallTile>(out_kind, a, out, in, s) : launch_shape<BigTile>(out_kind, a, out, in, s);
 }
 
 }  // namespace samo

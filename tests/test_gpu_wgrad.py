@@ -12,7 +12,7 @@ from gpu_util import DEV, dev_f16_bits, dev_i32, host_bits, ref_seg_ptr
 
 pytestmark = pytest.mark.gpu
 
-# (tokens, out, in): single blocks, ragged tails in every direction, several tiles of 256 x 256,
+# (tokens, out, in): single blocks, ragged tails in every direction, several tiles of either shape,
 # one to nine 32-token stages (the pipeline's start-up, even and odd counts) with and without a tail
 SHAPES = [(1, 8, 8), (7, 8, 16), (31, 16, 8), (32, 24, 40), (33, 136, 264), (100, 256, 512),
           (64, 384, 520), (257, 128, 256), (96, 264, 776), (45, 520, 72), (130, 520, 528),
@@ -72,9 +72,17 @@ def _problem(tokens, out_f, in_f, kind, seed):
     return dy, x, idx, d_dy, d_x, dev_i32(idx), dev_i32(ref_seg_ptr(idx, out_f * in_f))
 
 
+@pytest.fixture(params=["128", "256"])
+def tile(request, monkeypatch):
+    """Both tile shapes (128 x 128 and 256 x 256) on every case; left alone, the library picks by
+    the size of the layer."""
+    monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("kind", ["bernoulli10", "bernoulli50", "rows", "edges", "dense_idx"])
 @pytest.mark.parametrize("tokens,out_f,in_f", SHAPES)
-def test_compressed_weight_gradient_matches_the_oracle(tokens, out_f, in_f, kind):
+def test_compressed_weight_gradient_matches_the_oracle(tokens, out_f, in_f, kind, tile):
     seed = 1000 + tokens + out_f + in_f
     dy, x, idx, d_dy, d_x, d_idx, d_seg = _problem(tokens, out_f, in_f, kind, seed)
     nnz = idx.shape[0]
@@ -97,7 +105,7 @@ def test_compressed_weight_gradient_matches_the_oracle(tokens, out_f, in_f, kind
     assert torch.isnan(gc[nnz:]).all()
 
 
-def test_unpruned_layer_without_an_index():
+def test_unpruned_layer_without_an_index(tile):
     tokens, out_f, in_f = 70, 136, 264
     dy, x, _, d_dy, d_x, _, _ = _problem(tokens, out_f, in_f, "dense_idx", 5)
     n = out_f * in_f
@@ -109,7 +117,7 @@ def test_unpruned_layer_without_an_index():
     _check_f16(host_bits(gc16), lo, hi, oracle.wgrad_compress(dy, x, tokens, out_f, in_f, idx), "dense gc16")
 
 
-def test_micro_batches_accumulate_in_half_precision():
+def test_micro_batches_accumulate_in_half_precision(tile):
     """Second micro-batch added to the stored fp16 gradient: one correctly rounded half addition of
     the kernel's own fp16 weight gradient (Section II-E micro-batches, Section III-A storage)."""
     tokens, out_f, in_f = 90, 136, 520
@@ -136,7 +144,7 @@ def test_micro_batches_accumulate_in_half_precision():
     _check_f16(b, lo, hi, oracle.wgrad_compress(dy2, x2, tokens, out_f, in_f, idx), "second micro-batch")
 
 
-def test_no_tokens_and_no_kept_elements():
+def test_no_tokens_and_no_kept_elements(tile):
     out_f, in_f = 136, 264
     n = out_f * in_f
     idx = oracle.build_index(si.bernoulli_mask(n, 0.2, 3))
@@ -156,7 +164,7 @@ def test_no_tokens_and_no_kept_elements():
     torch.cuda.synchronize()
 
 
-def test_overflow_rounds_to_infinity_and_specials_propagate():
+def test_overflow_rounds_to_infinity_and_specials_propagate(tile):
     tokens, out_f, in_f = 40, 8, 8
     dy = np.full((tokens, out_f), 64.0, np.float16)
     x = np.full((tokens, in_f), 64.0, np.float16)
