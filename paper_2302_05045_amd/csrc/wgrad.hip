@@ -6,6 +6,7 @@
 // LDS; the epilogue rounds each accumulator once to fp16 — the value the dense gradient tensor
 // would have held — and stores only the entries the layer's index keeps.  The dense gradient is
 // never written to or read back from HBM.
+#include <atomic>
 #include <cstdlib>
 
 #include "common.h"
@@ -363,14 +364,20 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
 template <typename T>
 hipError_t launch_shape(int out_kind, WgradArgs a, int64_t out, int64_t in, hipStream_t s)
 {
-    static const hipError_t configured = [] {
+    // The LDS size above 64 KiB is a per-device attribute of the kernel: set once per device.
+    static std::atomic<uint64_t> configured{0};
+    int device = 0;
+    if (hipError_t e = hipGetDevice(&device)) return e;
+    const uint64_t bit = 1ull << (device & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF32, T>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF16, T>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
         if (e != hipSuccess) return e;
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<kOutF16, T>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes);
-    }();
-    if (configured != hipSuccess) return configured;
+        configured.fetch_or(bit, std::memory_order_release);
+    }
     a.tiles_in = (int)ceil_div(in, T::kIn);
     a.tiles = ceil_div(out, T::kOut) * a.tiles_in;
     const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);   // whole rounds of the 8 XCDs; the surplus exits at once
