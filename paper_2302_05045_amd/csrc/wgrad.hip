@@ -361,6 +361,246 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
 }
 
 
+// ---------------------------------------------------------------------------------------------
+// Variant for long token runs: the operands go global -> LDS without passing registers
+// (global_load_lds_dwordx4: each lane names 16 bytes of global memory, the wave's 1 KiB lands
+// contiguously in LDS at a base held in M0), in the layout they have in memory — per token, 256
+// features of X then 256 of dY — and the MFMA operands are formed by the transposing LDS read
+// ds_read_b64_tr_b16: within each group of 16 lanes, lanes 4r .. 4r+3 name the 16 features of
+// token r (r = 0..3), and lane i receives feature i of those four tokens.  No transposes on the
+// vector ALU and no registers for bytes in flight: three whole stages are on their way while a
+// fourth is multiplied, by 4 waves of 128 x 128 (256 accumulators, one wave per SIMD).
+// The compiler cannot know which LDS reads alias a copy in flight and would wait for all of
+// them before every read, so the copies are issued from inline assembly and this kernel counts
+// its outstanding copies itself: every stage issues exactly 8 per wave.
+// Measured against the register-staged kernel above (FC1 of the 2.7B model): 0.84 against 1.2
+// microseconds per 32-token stage at 8192 tokens, the same at 2048, slower below (its start-up
+// and its epilogue by 256 threads cost 3 microseconds more per tile): used from 4096 tokens up.
+#define LDS_AS __attribute__((address_space(3)))
+typedef short short4v __attribute__((ext_vector_type(4)));
+constexpr int kDmaRowBytes = 1024 + 64;                 // one token: 256 X features, 256 dY features, pad
+constexpr int kDmaStageBytes = kWgTok * kDmaRowBytes;   // 34816
+constexpr int kDmaStages = 4;
+constexpr int kDmaLdsBytes = kDmaStages * kDmaStageBytes;
+constexpr int kDmaThreads = 256;
+constexpr int kDmaEpiPitch = 256 + 8;
+constexpr int64_t kDmaFromTokens = 4096;                // token count from which this variant is used (measured)
+
+__device__ __forceinline__ void dma16(const void *g, unsigned lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_addr) : "memory");
+}
+
+// 8 tokens of one feature for an MFMA lane: two transposing reads of 4 tokens each.
+__device__ __forceinline__ half8 read_tr_fragment(const unsigned char *p)
+{
+    const short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS short4v *)(LDS_AS unsigned char *)p);
+    const short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS short4v *)(LDS_AS unsigned char *)(p + 4 * kDmaRowBytes));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    const short8v q = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    return __builtin_bit_cast(half8, q);
+}
+
+template <int OUT>
+__global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradArgs A)
+{
+    constexpr int kWgOut = 256, kWgIn = 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ int bounds[2 * kWgOut];
+
+    const int64_t per_xcd = (A.tiles + 7) / 8;
+    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= A.tiles) return;
+    const int tiles_out = (int)(A.tiles / A.tiles_in);
+    const int group = (int)(tile / (4 * A.tiles_in));
+    const int in_group = (int)(tile - (int64_t)group * 4 * A.tiles_in);
+    const int group_rows = tiles_out - group * 4 < 4 ? tiles_out - group * 4 : 4;
+    const int row0 = (group * 4 + in_group % group_rows) * kWgOut;
+    const int col0 = (in_group / group_rows) * kWgIn;
+
+    const int t = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
+    const int64_t n = (int64_t)A.out * A.in;
+
+    int s_lo[2] = {0, 0}, s_hi[2] = {0, 0}, s_key[2] = {0, 0};
+    if (row0 + t < A.out) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int c = e == 0 ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
+            const int64_t p = (int64_t)(row0 + t) * A.in + c;
+            if (p >= n) s_lo[e] = s_hi[e] = (int)A.nnz;
+            else if (!A.idx) s_lo[e] = s_hi[e] = (int)p;
+            else {
+                s_lo[e] = A.seg_ptr[p / kSeg];
+                s_hi[e] = A.seg_ptr[p / kSeg + 1];
+                s_key[e] = (int)p;
+            }
+        }
+    }
+
+    // DMA role of a lane: lanes 0-31 fetch 8 features of X each, lanes 32-63 8 features of dY; one
+    // instruction of a wave moves one token's row of the stage.  Wave w owns rows 8w .. 8w+7.
+    const bool is_y = lane >= 32;
+    const int features = is_y ? A.out : A.in;
+    const int f = (is_y ? row0 : col0) + (lane & 31) * 8;
+    const int64_t row_bytes = (int64_t)features * 2;
+    const unsigned char *gbase = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2 +
+                                 (int64_t)(wave * 8) * row_bytes;
+    const unsigned char *gvalid = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2;
+    const unsigned lds_base = (unsigned)(size_t)(LDS_AS unsigned char *)lds;
+    const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;
+    auto issue_stage = [&](int64_t s) {
+        const unsigned dst = lds_base + (unsigned)(s % kDmaStages) * kDmaStageBytes + (unsigned)(wave * 8) * kDmaRowBytes;
+        const unsigned char *g = gbase + s * kWgTok * row_bytes;
+        const int64_t rows = A.tokens - s * kWgTok - wave * 8;      // rows of this wave's share that exist
+        if (rows >= 8) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
+        } else {
+            // the last, partial stage: tokens past the end are rows of zeros; the wave issues 8
+            // operations either way so that the wait counts below stay the same
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i < rows) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
+                else {
+                    dma16(gvalid, lds_base + kDmaLdsBytes);           // a valid load (token 0) into a spare row
+                    *reinterpret_cast<uint4 *>(lds + (s % kDmaStages) * kDmaStageBytes + (wave * 8 + i) * kDmaRowBytes + lane * 16) =
+                        make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    const int wo = wave & 1, wi = wave >> 1;
+    const int l32 = lane & 31;
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int bo = 0; bo < 4; ++bo)
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[bo][bi][r] = 0.f;
+    // lane address of a transposing read inside a stage: group of 16 lanes g, lane j of the group
+    // reads token 8*(g>>1) + (j>>2), features 16*(g&1) + 4*(j&3) .. +3 of a 32-feature block
+    const int g16 = lane >> 4, j16 = lane & 15;
+    const int tr_off = (8 * (g16 >> 1) + (j16 >> 2)) * kDmaRowBytes + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+    const int x_off = tr_off + (wi * 128) * 2, y_off = tr_off + 512 + (wo * 128) * 2;
+    auto multiply_stage = [&](const unsigned char *cur) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            half8 xa[4], yb[4];
+#pragma unroll
+            for (int bi = 0; bi < 4; ++bi) xa[bi] = read_tr_fragment(cur + x_off + kk * 16 * kDmaRowBytes + bi * 64);
+#pragma unroll
+            for (int bo = 0; bo < 4; ++bo) yb[bo] = read_tr_fragment(cur + y_off + kk * 16 * kDmaRowBytes + bo * 64);
+#pragma unroll
+            for (int bo = 0; bo < 4; ++bo)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+                    acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
+        }
+    };
+
+    // Three stages requested ahead, one barrier per stage.  At the top of stage s the copies of
+    // stages s+1 and s+2 may still be outstanding (16 per wave), those of stage s may not.
+    for (int64_t s = 0; s < 3 && s < stages; ++s) issue_stage(s);
+    // The bounds are searched while those first stages are on their way.  First a guess by
+    // interpolation inside the segment (kept elements spread evenly over it would put the bound
+    // at lo + (hi - lo) * offset / 1024) and a look at the 8 entries around it — on masks without
+    // structure that settles it in one round trip; then plain bisection of whatever is left.
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        if (s_lo[e] < s_hi[e]) {
+            const int guess = s_lo[e] + (int)(((int64_t)(s_hi[e] - s_lo[e]) * (s_key[e] & (kSeg - 1))) >> 10);
+            int w0 = guess - 4 > s_lo[e] ? guess - 4 : s_lo[e];
+            if (w0 + 8 > s_hi[e]) w0 = s_hi[e] - 8 > s_lo[e] ? s_hi[e] - 8 : s_lo[e];
+            const int wn = s_hi[e] - w0 < 8 ? s_hi[e] - w0 : 8;
+            int v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = A.idx[w0 + (i < wn ? i : wn - 1)];
+            int below = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) below += (i < wn && v[i] < s_key[e]) ? 1 : 0;
+            if (below == 0) s_hi[e] = w0;                          // the bound is at or before the window
+            else if (below == wn) s_lo[e] = w0 + wn;                // at or after its end
+            else s_lo[e] = s_hi[e] = w0 + below;                    // inside
+        }
+        while (s_lo[e] < s_hi[e]) {
+            const int mid = (s_lo[e] + s_hi[e]) >> 1;
+            if (A.idx[mid] < s_key[e]) s_lo[e] = mid + 1;
+            else s_hi[e] = mid;
+        }
+    }
+    bounds[t] = s_lo[0];
+    bounds[kWgOut + t] = s_lo[1];
+    for (int64_t s = 0; s < stages; ++s) {
+        const int64_t younger = stages - 1 - s < 2 ? stages - 1 - s : 2;
+        if (younger == 2) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+        else if (younger == 1) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (s + 3 < stages) issue_stage(s + 3);
+        multiply_stage(lds + (s % kDmaStages) * kDmaStageBytes);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    _Float16 *img = reinterpret_cast<_Float16 *>(lds);
+    const int hw = t >> 5, khalf = lane >> 5;
+    constexpr int kPassRows = 128;
+    constexpr int kRowsPerHalfWave = kPassRows / 8;
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        if (wo == pass) {
+#pragma unroll
+            for (int bo = 0; bo < 4; ++bo)
+#pragma unroll
+                for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        half4 h;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];
+                        const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
+                        *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kDmaEpiPitch + col) = h;
+                    }
+        }
+        __syncthreads();
+        int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
+#pragma unroll
+        for (int it = 0; it < kRowsPerHalfWave; ++it) {
+            const int trow = pass * kPassRows + it * 8 + hw;
+            lo[it] = bounds[trow];
+            hi[it] = bounds[kWgOut + trow];
+            longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
+        }
+        for (int off_k = l32; off_k - l32 < longest; off_k += 32) {
+            int pos[kRowsPerHalfWave];
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                const int k = lo[it] + off_k;
+                pos[it] = k < hi[it] ? (A.idx ? A.idx[k] : k) : -1;
+            }
+#pragma unroll
+            for (int it = 0; it < kRowsPerHalfWave; ++it) {
+                if (pos[it] < 0) continue;
+                const int k = lo[it] + off_k;
+                const int rl = it * 8 + hw;
+                const int64_t base = (int64_t)(row0 + pass * kPassRows + rl) * A.in + col0;
+                const _Float16 v = img[rl * kDmaEpiPitch + (int)(pos[it] - base)];
+                if (OUT == kOutF32) {
+                    reinterpret_cast<float *>(A.gc)[k] = (float)v * A.inv_scale;
+                } else {
+                    _Float16 *dst = reinterpret_cast<_Float16 *>(A.gc) + k;
+                    *dst = A.accumulate ? (_Float16)(*dst + v) : v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 template <typename T>
 hipError_t launch_shape(int out_kind, WgradArgs a, int64_t out, int64_t in, hipStream_t s)
 {
@@ -386,6 +626,30 @@ hipError_t launch_shape(int out_kind, WgradArgs a, int64_t out, int64_t in, hipS
     return hipGetLastError();
 }
 
+hipError_t launch_dma(int out_kind, WgradArgs a, int64_t out, int64_t in, hipStream_t s)
+{
+    constexpr int kBytes = kDmaLdsBytes + kDmaRowBytes;        // the stages and one spare row
+    static std::atomic<uint64_t> configured{0};
+    int device = 0;
+    if (hipError_t e = hipGetDevice(&device)) return e;
+    const uint64_t bit = 1ull << (device & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_dma_kernel<kOutF32>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_dma_kernel<kOutF16>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+        if (e != hipSuccess) return e;
+        configured.fetch_or(bit, std::memory_order_release);
+    }
+    a.tiles_in = (int)ceil_div(in, 256);
+    a.tiles = ceil_div(out, 256) * a.tiles_in;
+    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);
+    if (out_kind == kOutF32) wgrad_dma_kernel<kOutF32><<<dim3(grid), dim3(kDmaThreads), kBytes, s>>>(a);
+    else wgrad_dma_kernel<kOutF16><<<dim3(grid), dim3(kDmaThreads), kBytes, s>>>(a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
@@ -398,10 +662,12 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
     a.tiles_in = 0; a.tiles = 0;
     const int64_t big_tiles = ceil_div(out, BigTile::kOut) * ceil_div(in, BigTile::kIn);
-    const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128 or 256
+    const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128, 256 or 512 (= 256, copies straight to LDS)
     const int force = forced ? atoi(forced) : 0;
-    const bool small = force == 128 || (force != 256 && big_tiles < kSmallTileBelow);
-    return small ? launch_shape<SmallTile>(out_kind, a, out, in, s) : launch_shape<BigTile>(out_kind, a, out, in, s);
+    const bool small = force == 128 || (force != 256 && force != 512 && big_tiles < kSmallTileBelow);
+    if (small) return launch_shape<SmallTile>(out_kind, a, out, in, s);
+    if (force == 512 || (force != 256 && tokens >= kDmaFromTokens)) return launch_dma(out_kind, a, out, in, s);
+    return launch_shape<BigTile>(out_kind, a, out, in, s);
 }
 
 }  // namespace samo

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 # one to nine 32-token stages (the pipeline's start-up, even and odd counts) with and without a tail
 SHAPES = [(1, 8, 8), (7, 8, 16), (31, 16, 8), (32, 24, 40), (33, 136, 264), (100, 256, 512),
           (64, 384, 520), (257, 128, 256), (96, 264, 776), (45, 520, 72), (130, 520, 528),
-          (64, 8, 8), (65, 16, 16), (128, 264, 8), (160, 8, 264), (289, 24, 24)]
+          (64, 8, 8), (65, 16, 16), (128, 264, 8), (160, 8, 264), (289, 24, 24), (421, 264, 520)]
 
 
 def _mask(kind, out_f, in_f, seed):
@@ -72,10 +72,11 @@ def _problem(tokens, out_f, in_f, kind, seed):
     return dy, x, idx, d_dy, d_x, dev_i32(idx), dev_i32(ref_seg_ptr(idx, out_f * in_f))
 
 
-@pytest.fixture(params=["128", "256"])
+@pytest.fixture(params=["128", "256", "512"])
 def tile(request, monkeypatch):
-    """Both tile shapes (128 x 128 and 256 x 256) on every case; left alone, the library picks by
-    the size of the layer."""
+    """Every kernel variant (128 x 128 tiles, 256 x 256 tiles staged through registers, 256 x 256
+    tiles copied straight to LDS) on every case; left alone, the library picks by layer size and
+    token count."""
     monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
     return request.param
 
