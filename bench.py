@@ -242,6 +242,16 @@ def main():
             mfma_entry("library GEMM (dense fp16 dW) + samo_gather_grads", time_entry(library_path))
             mfma_entry("library GEMM alone", time_entry(lambda: torch.matmul(dy.t(), xa, out=dense_g)))
             del dy, xa
+            # a micro-batch of four sequences on the same layer
+            long_tokens = 4 * tokens
+            dy = torch.from_numpy(si.output_grads_fp16(long_tokens, out_f, 1).view(np.int16)).to(dev).view(torch.float16).view(long_tokens, out_f)
+            xa = torch.from_numpy(si.activations_fp16(long_tokens, in_f, 1).view(np.int16)).to(dev).view(torch.float16).view(long_tokens, in_f)
+            flops = 2.0 * long_tokens * out_f * in_f
+            mfma_entry("samo_wgrad_gather, %d tokens" % long_tokens,
+                       time_entry(lambda: samo.samo_wgrad_gather(dy, xa, L.idx, L.seg_ptr, inv, L.gc)))
+            mfma_entry("library GEMM + samo_gather_grads, %d tokens" % long_tokens, time_entry(library_path))
+            del dy, xa
+            flops = 2.0 * tokens * out_f * in_f
             # the same two routes over the pruned matrices of the first transformer layer, launched back to back
             block = cand[:4]
             ops = []
