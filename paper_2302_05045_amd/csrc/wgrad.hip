@@ -48,7 +48,6 @@ struct TileShape {
     static constexpr int kStageBytes = (kIn + kOut) * kRowBytes;     // X rows, then dY rows
     static constexpr int kLdsBytes = 2 * kStageBytes;
     static constexpr int kEpiPitch = kIn + 8;                // halves; +8 spreads a column of 32 rows over the banks
-    static constexpr int kMinWaves = kThreads / 256;         // waves per SIMD of one workgroup
     static_assert(kIn + kOut == kThreads && 2 * kOut == kThreads, "one block to move and one bound to find per thread");
     static_assert(BO * 32 == kEpiRows, "an epilogue pass is the rows of one wave row");
     static_assert(kLdsBytes >= kEpiRows * kEpiPitch * 2, "the epilogue image reuses the operand stages");
