@@ -34,7 +34,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // uncovered.
 constexpr int kWgTok = 32;
 constexpr int kRowBytes = kWgTok * 2 + 8;                    // one feature's 32 tokens, padded: see stage_offset
-constexpr int kEpiRows = 64;                                 // rows of dW staged per epilogue pass
+constexpr int kEpiRows = 128;                                // rows of dW staged per epilogue pass: two wave rows
 
 // A tile shape: WO x WI waves, each BO x BI blocks of 32 x 32.  Every thread moves exactly one
 // 8-feature block per stage and finds exactly one bound of the epilogue, so the tile's rows and
@@ -49,7 +49,7 @@ struct TileShape {
     static constexpr int kLdsBytes = 2 * kStageBytes;
     static constexpr int kEpiPitch = kIn + 8;                // halves; +8 spreads a column of 32 rows over the banks
     static_assert(kIn + kOut == kThreads && 2 * kOut == kThreads, "one block to move and one bound to find per thread");
-    static_assert(BO * 32 == kEpiRows, "an epilogue pass is the rows of one wave row");
+    static_assert(2 * BO * 32 == kEpiRows && WO % 2 == 0, "an epilogue pass is the rows of two wave rows");
     static_assert(kLdsBytes >= kEpiRows * kEpiPitch * 2, "the epilogue image reuses the operand stages");
     static_assert(kOut % 64 == 0 && kThreads % 32 == 0 && kEpiRows % (kThreads / 32) == 0, "epilogue row split");
 };
@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
         else s_hi = mid;
     }
 
-    // Epilogue, 64 rows of dW per pass (the waves that own them write, everyone gathers):
+    // Epilogue, 128 rows of dW per pass (the waves that own them write, everyone gathers):
     // accumulators -> fp16 image in LDS -> the kept entries of each row.  A half wave takes its
     // share of the rows of a pass and fetches their index runs together before it touches the image.
     bounds[t] = s_lo;
@@ -309,8 +309,8 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
     constexpr int kHalfWaves = T::kThreads / 32;
     constexpr int kRowsPerHalfWave = kEpiRows / kHalfWaves;
 #pragma unroll 1
-    for (int pass = 0; pass < T::WO; ++pass) {
-        if (wo == pass) {
+    for (int pass = 0; pass < T::WO / 2; ++pass) {
+        if ((wo >> 1) == pass) {
 #pragma unroll
             for (int bo = 0; bo < BO; ++bo)
 #pragma unroll
@@ -321,7 +321,7 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
 #pragma unroll
                         for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];   // round to nearest even
                         const int col = (wi * BI + bi) * 32 + q * 8 + khalf * 4;
-                        *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kEpiPitch + col) = h;
+                        *reinterpret_cast<half4 *>(img + ((wo & 1) * 64 + bo * 32 + l32) * kEpiPitch + col) = h;
                     }
         }
         __syncthreads();
