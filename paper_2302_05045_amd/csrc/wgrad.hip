@@ -55,7 +55,7 @@ struct TileShape {
 };
 using BigTile = TileShape<4, 2, 2, 4>;      // 256 x 256, 8 waves of 64 x 128: 128 accumulator registers, one workgroup per CU
 using SmallTile = TileShape<2, 2, 2, 2>;    // 128 x 128, 4 waves of 64 x 64: layers whose 256 x 256 tiles would leave CUs idle
-constexpr int64_t kSmallTileBelow = 160;    // 256 x 256 tiles of a layer below which the small shape is used (measured)
+constexpr int64_t kSmallTileBelow = 65;     // 256 x 256 tiles of a layer below which the small shape is used (measured)
 
 // LDS image of a stage: row = feature (X rows first, then dY rows), 32 tokens = 64 bytes in a pitch
 // of 72.  18 banks per row: a fragment read (32 lanes, 32 consecutive rows, 8 bytes each, twice)
@@ -361,29 +361,29 @@ __global__ void __launch_bounds__(T::kThreads, 2) wgrad_kernel(const WgradArgs A
 
 
 // ---------------------------------------------------------------------------------------------
-// Variant for long token runs: the operands go global -> LDS without passing registers
-// (global_load_lds_dwordx4: each lane names 16 bytes of global memory, the wave's 1 KiB lands
-// contiguously in LDS at a base held in M0), in the layout they have in memory — per token, 256
-// features of X then 256 of dY — and the MFMA operands are formed by the transposing LDS read
-// ds_read_b64_tr_b16: within each group of 16 lanes, lanes 4r .. 4r+3 name the 16 features of
-// token r (r = 0..3), and lane i receives feature i of those four tokens.  No transposes on the
-// vector ALU and no registers for bytes in flight: three whole stages are on their way while a
-// fourth is multiplied, by 4 waves of 128 x 128 (256 accumulators, one wave per SIMD).
+// The kernel for layers of 65 tiles and more: the operands go global -> LDS without passing
+// registers (global_load_lds_dwordx4: each lane names 16 bytes of global memory, the wave's
+// 1 KiB lands contiguously in LDS at a base held in M0), in the layout they have in memory — per
+// token, 256 features of X then 256 of dY — and the MFMA operands are formed by the transposing
+// LDS read ds_read_b64_tr_b16: within each group of 16 lanes, lanes 4r .. 4r+3 name the 16
+// features of token r (r = 0..3), and lane i receives feature i of those four tokens.  No
+// transposes on the vector ALU and no registers for bytes in flight: three whole stages are on
+// their way while a fourth is multiplied, by 8 waves of 64 x 128 (128 accumulators each, two
+// waves per SIMD, so that one wave's LDS reads and barrier waits sit under the other's MFMAs).
 // The compiler cannot know which LDS reads alias a copy in flight and would wait for all of
 // them before every read, so the copies are issued from inline assembly and this kernel counts
-// its outstanding copies itself: every stage issues exactly 8 per wave.
-// Measured against the register-staged kernel above (FC1 of the 2.7B model): 0.84 against 1.2
-// microseconds per 32-token stage at 8192 tokens, the same at 2048, slower below (its start-up
-// and its epilogue by 256 threads cost 3 microseconds more per tile): used from 4096 tokens up.
+// its outstanding copies itself: every stage issues exactly 4 per wave.
+// Measured against the register-staged kernel above at 256 x 256 (FC1 of the 2.7B model, 2048
+// tokens): 0.144 against 0.168 ms; with 4 waves of 128 x 128 and one wave per SIMD the same
+// copies gave 0.167 ms.
 #define LDS_AS __attribute__((address_space(3)))
 typedef short short4v __attribute__((ext_vector_type(4)));
 constexpr int kDmaRowBytes = 1024 + 64;                 // one token: 256 X features, 256 dY features, pad
 constexpr int kDmaStageBytes = kWgTok * kDmaRowBytes;   // 34816
 constexpr int kDmaStages = 4;
 constexpr int kDmaLdsBytes = kDmaStages * kDmaStageBytes;
-constexpr int kDmaThreads = 256;
+constexpr int kDmaThreads = 512;
 constexpr int kDmaEpiPitch = 256 + 8;
-constexpr int64_t kDmaFromTokens = 4096;                // token count from which this variant is used (measured)
 
 __device__ __forceinline__ void dma16(const void *g, unsigned lds_byte_addr)
 {
@@ -401,7 +401,7 @@ __device__ __forceinline__ half8 read_tr_fragment(const unsigned char *p)
 }
 
 template <int OUT>
-__global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradArgs A)
+__global__ void __launch_bounds__(kDmaThreads, 2) wgrad_dma_kernel(const WgradArgs A)
 {
     constexpr int kWgOut = 256, kWgIn = 256;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -421,60 +421,62 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const int64_t n = (int64_t)A.out * A.in;
 
-    int s_lo[2] = {0, 0}, s_hi[2] = {0, 0}, s_key[2] = {0, 0};
-    if (row0 + t < A.out) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int c = e == 0 ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
-            const int64_t p = (int64_t)(row0 + t) * A.in + c;
-            if (p >= n) s_lo[e] = s_hi[e] = (int)A.nnz;
-            else if (!A.idx) s_lo[e] = s_hi[e] = (int)p;
+    // Thread t < 256 looks for the first kept position of tile row t, thread 256 + t for the first
+    // one past the row's end inside the tile.
+    int s_lo = 0, s_hi = 0, s_key = 0;
+    {
+        const int r = row0 + (t & (kWgOut - 1));
+        if (r < A.out) {
+            const int c = t < kWgOut ? col0 : (col0 + kWgIn < A.in ? col0 + kWgIn : A.in);
+            const int64_t p = (int64_t)r * A.in + c;
+            if (p >= n) s_lo = s_hi = (int)A.nnz;
+            else if (!A.idx) s_lo = s_hi = (int)p;
             else {
-                s_lo[e] = A.seg_ptr[p / kSeg];
-                s_hi[e] = A.seg_ptr[p / kSeg + 1];
-                s_key[e] = (int)p;
+                s_lo = A.seg_ptr[p / kSeg];
+                s_hi = A.seg_ptr[p / kSeg + 1];
+                s_key = (int)p;
             }
         }
     }
 
     // DMA role of a lane: lanes 0-31 fetch 8 features of X each, lanes 32-63 8 features of dY; one
-    // instruction of a wave moves one token's row of the stage.  Wave w owns rows 8w .. 8w+7.
+    // instruction of a wave moves one token's row of the stage.  Wave w owns rows 4w .. 4w+3.
     const bool is_y = lane >= 32;
     const int features = is_y ? A.out : A.in;
     const int f = (is_y ? row0 : col0) + (lane & 31) * 8;
     const int64_t row_bytes = (int64_t)features * 2;
     const unsigned char *gbase = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2 +
-                                 (int64_t)(wave * 8) * row_bytes;
+                                 (int64_t)(wave * 4) * row_bytes;
     const unsigned char *gvalid = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2;
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS unsigned char *)lds;
     const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;
     auto issue_stage = [&](int64_t s) {
-        const unsigned dst = lds_base + (unsigned)(s % kDmaStages) * kDmaStageBytes + (unsigned)(wave * 8) * kDmaRowBytes;
+        const unsigned dst = lds_base + (unsigned)(s % kDmaStages) * kDmaStageBytes + (unsigned)(wave * 4) * kDmaRowBytes;
         const unsigned char *g = gbase + s * kWgTok * row_bytes;
-        const int64_t rows = A.tokens - s * kWgTok - wave * 8;      // rows of this wave's share that exist
-        if (rows >= 8) {
+        const int64_t rows = A.tokens - s * kWgTok - wave * 4;      // rows of this wave's share that exist
+        if (rows >= 4) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
+            for (int i = 0; i < 4; ++i) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
         } else {
-            // the last, partial stage: tokens past the end are rows of zeros; the wave issues 8
+            // the last, partial stage: tokens past the end are rows of zeros; the wave issues 4
             // operations either way so that the wait counts below stay the same
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 4; ++i) {
                 if (i < rows) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
                 else {
                     dma16(gvalid, lds_base + kDmaLdsBytes);           // a valid load (token 0) into a spare row
-                    *reinterpret_cast<uint4 *>(lds + (s % kDmaStages) * kDmaStageBytes + (wave * 8 + i) * kDmaRowBytes + lane * 16) =
+                    *reinterpret_cast<uint4 *>(lds + (s % kDmaStages) * kDmaStageBytes + (wave * 4 + i) * kDmaRowBytes + lane * 16) =
                         make_uint4(0, 0, 0, 0);
                 }
             }
         }
     };
 
-    const int wo = wave & 1, wi = wave >> 1;
+    const int wo = wave & 3, wi = wave >> 2;
     const int l32 = lane & 31;
-    f32x16 acc[4][4];
+    f32x16 acc[2][4];
 #pragma unroll
-    for (int bo = 0; bo < 4; ++bo)
+    for (int bo = 0; bo < 2; ++bo)
 #pragma unroll
         for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
@@ -483,17 +485,17 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
     // reads token 8*(g>>1) + (j>>2), features 16*(g&1) + 4*(j&3) .. +3 of a 32-feature block
     const int g16 = lane >> 4, j16 = lane & 15;
     const int tr_off = (8 * (g16 >> 1) + (j16 >> 2)) * kDmaRowBytes + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
-    const int x_off = tr_off + (wi * 128) * 2, y_off = tr_off + 512 + (wo * 128) * 2;
+    const int x_off = tr_off + (wi * 128) * 2, y_off = tr_off + 512 + (wo * 64) * 2;
     auto multiply_stage = [&](const unsigned char *cur) {
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            half8 xa[4], yb[4];
+            half8 xa[4], yb[2];
 #pragma unroll
             for (int bi = 0; bi < 4; ++bi) xa[bi] = read_tr_fragment(cur + x_off + kk * 16 * kDmaRowBytes + bi * 64);
 #pragma unroll
-            for (int bo = 0; bo < 4; ++bo) yb[bo] = read_tr_fragment(cur + y_off + kk * 16 * kDmaRowBytes + bo * 64);
+            for (int bo = 0; bo < 2; ++bo) yb[bo] = read_tr_fragment(cur + y_off + kk * 16 * kDmaRowBytes + bo * 64);
 #pragma unroll
-            for (int bo = 0; bo < 4; ++bo)
+            for (int bo = 0; bo < 2; ++bo)
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi)
                     acc[bo][bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[bi], yb[bo], acc[bo][bi], 0, 0, 0);
@@ -501,41 +503,37 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
     };
 
     // Three stages requested ahead, one barrier per stage.  At the top of stage s the copies of
-    // stages s+1 and s+2 may still be outstanding (16 per wave), those of stage s may not.
+    // stages s+1 and s+2 may still be outstanding (8 per wave), those of stage s may not.
     for (int64_t s = 0; s < 3 && s < stages; ++s) issue_stage(s);
     // The bounds are searched while those first stages are on their way.  First a guess by
     // interpolation inside the segment (kept elements spread evenly over it would put the bound
     // at lo + (hi - lo) * offset / 1024) and a look at the 8 entries around it — on masks without
     // structure that settles it in one round trip; then plain bisection of whatever is left.
+    if (s_lo < s_hi) {
+        const int guess = s_lo + (int)(((int64_t)(s_hi - s_lo) * (s_key & (kSeg - 1))) >> 10);
+        int w0 = guess - 4 > s_lo ? guess - 4 : s_lo;
+        if (w0 + 8 > s_hi) w0 = s_hi - 8 > s_lo ? s_hi - 8 : s_lo;
+        const int wn = s_hi - w0 < 8 ? s_hi - w0 : 8;
+        int v[8];
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        if (s_lo[e] < s_hi[e]) {
-            const int guess = s_lo[e] + (int)(((int64_t)(s_hi[e] - s_lo[e]) * (s_key[e] & (kSeg - 1))) >> 10);
-            int w0 = guess - 4 > s_lo[e] ? guess - 4 : s_lo[e];
-            if (w0 + 8 > s_hi[e]) w0 = s_hi[e] - 8 > s_lo[e] ? s_hi[e] - 8 : s_lo[e];
-            const int wn = s_hi[e] - w0 < 8 ? s_hi[e] - w0 : 8;
-            int v[8];
+        for (int i = 0; i < 8; ++i) v[i] = A.idx[w0 + (i < wn ? i : wn - 1)];
+        int below = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = A.idx[w0 + (i < wn ? i : wn - 1)];
-            int below = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) below += (i < wn && v[i] < s_key[e]) ? 1 : 0;
-            if (below == 0) s_hi[e] = w0;                          // the bound is at or before the window
-            else if (below == wn) s_lo[e] = w0 + wn;                // at or after its end
-            else s_lo[e] = s_hi[e] = w0 + below;                    // inside
-        }
-        while (s_lo[e] < s_hi[e]) {
-            const int mid = (s_lo[e] + s_hi[e]) >> 1;
-            if (A.idx[mid] < s_key[e]) s_lo[e] = mid + 1;
-            else s_hi[e] = mid;
-        }
+        for (int i = 0; i < 8; ++i) below += (i < wn && v[i] < s_key) ? 1 : 0;
+        if (below == 0) s_hi = w0;                          // the bound is at or before the window
+        else if (below == wn) s_lo = w0 + wn;                // at or after its end
+        else s_lo = s_hi = w0 + below;                    // inside
     }
-    bounds[t] = s_lo[0];
-    bounds[kWgOut + t] = s_lo[1];
+    while (s_lo < s_hi) {
+        const int mid = (s_lo + s_hi) >> 1;
+        if (A.idx[mid] < s_key) s_lo = mid + 1;
+        else s_hi = mid;
+    }
+    bounds[t] = s_lo;
     for (int64_t s = 0; s < stages; ++s) {
         const int64_t younger = stages - 1 - s < 2 ? stages - 1 - s : 2;
-        if (younger == 2) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-        else if (younger == 1) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        if (younger == 2) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        else if (younger == 1) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -548,12 +546,12 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
     _Float16 *img = reinterpret_cast<_Float16 *>(lds);
     const int hw = t >> 5, khalf = lane >> 5;
     constexpr int kPassRows = 128;
-    constexpr int kRowsPerHalfWave = kPassRows / 8;
+    constexpr int kRowsPerHalfWave = kPassRows / 16;
 #pragma unroll 1
     for (int pass = 0; pass < 2; ++pass) {
-        if (wo == pass) {
+        if ((wo >> 1) == pass) {
 #pragma unroll
-            for (int bo = 0; bo < 4; ++bo)
+            for (int bo = 0; bo < 2; ++bo)
 #pragma unroll
                 for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
@@ -562,14 +560,14 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
 #pragma unroll
                         for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];
                         const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
-                        *reinterpret_cast<half4 *>(img + (bo * 32 + l32) * kDmaEpiPitch + col) = h;
+                        *reinterpret_cast<half4 *>(img + ((wo & 1) * 64 + bo * 32 + l32) * kDmaEpiPitch + col) = h;
                     }
         }
         __syncthreads();
         int lo[kRowsPerHalfWave], hi[kRowsPerHalfWave], longest = 0;
 #pragma unroll
         for (int it = 0; it < kRowsPerHalfWave; ++it) {
-            const int trow = pass * kPassRows + it * 8 + hw;
+            const int trow = pass * kPassRows + it * 16 + hw;
             lo[it] = bounds[trow];
             hi[it] = bounds[kWgOut + trow];
             longest = hi[it] - lo[it] > longest ? hi[it] - lo[it] : longest;
@@ -585,7 +583,7 @@ __global__ void __launch_bounds__(kDmaThreads, 1) wgrad_dma_kernel(const WgradAr
             for (int it = 0; it < kRowsPerHalfWave; ++it) {
                 if (pos[it] < 0) continue;
                 const int k = lo[it] + off_k;
-                const int rl = it * 8 + hw;
+                const int rl = it * 16 + hw;
                 const int64_t base = (int64_t)(row0 + pass * kPassRows + rl) * A.in + col0;
                 const _Float16 v = img[rl * kDmaEpiPitch + (int)(pos[it] - base)];
                 if (OUT == kOutF32) {
@@ -665,8 +663,8 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     const int force = forced ? atoi(forced) : 0;
     const bool small = force == 128 || (force != 256 && force != 512 && big_tiles < kSmallTileBelow);
     if (small) return launch_shape<SmallTile>(out_kind, a, out, in, s);
-    if (force == 512 || (force != 256 && tokens >= kDmaFromTokens)) return launch_dma(out_kind, a, out, in, s);
-    return launch_shape<BigTile>(out_kind, a, out, in, s);
+    if (force == 256) return launch_shape<BigTile>(out_kind, a, out, in, s);
+    return launch_dma(out_kind, a, out, in, s);
 }
 
 }  // namespace samo
