@@ -385,6 +385,8 @@ constexpr int kDmaLdsBytes = kDmaStages * kDmaStageBytes;
 constexpr int kDmaThreads = 512;
 constexpr int kDmaEpiPitch = 256 + 8;
 
+__device__ __attribute__((aligned(16))) const unsigned char wgrad_zero_row[16] = {0};
+
 __device__ __forceinline__ void dma16(const void *g, unsigned lds_byte_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_addr) : "memory");
@@ -440,36 +442,22 @@ __global__ void __launch_bounds__(kDmaThreads, 2) wgrad_dma_kernel(const WgradAr
     }
 
     // DMA role of a lane: lanes 0-31 fetch 8 features of X each, lanes 32-63 8 features of dY; one
-    // instruction of a wave moves one token's row of the stage.  Wave w owns rows 4w .. 4w+3.
+    // instruction of a wave moves one token's row of the stage.  Wave w owns rows 4w .. 4w+3.  Rows
+    // past the last token are copied from 16 bytes of zeros, so that every stage is 4 copies per
+    // wave and the wait counts below hold for the partial last stage too.
     const bool is_y = lane >= 32;
     const int features = is_y ? A.out : A.in;
     const int f = (is_y ? row0 : col0) + (lane & 31) * 8;
     const int64_t row_bytes = (int64_t)features * 2;
-    const unsigned char *gbase = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2 +
-                                 (int64_t)(wave * 4) * row_bytes;
-    const unsigned char *gvalid = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2;
+    const unsigned char *gbase = reinterpret_cast<const unsigned char *>(is_y ? A.dy : A.x) + (int64_t)(f < features ? f : 0) * 2;
     const unsigned lds_base = (unsigned)(size_t)(LDS_AS unsigned char *)lds;
     const int64_t stages = (A.tokens + kWgTok - 1) / kWgTok;
     auto issue_stage = [&](int64_t s) {
         const unsigned dst = lds_base + (unsigned)(s % kDmaStages) * kDmaStageBytes + (unsigned)(wave * 4) * kDmaRowBytes;
-        const unsigned char *g = gbase + s * kWgTok * row_bytes;
-        const int64_t rows = A.tokens - s * kWgTok - wave * 4;      // rows of this wave's share that exist
-        if (rows >= 4) {
+        const int64_t token = s * kWgTok + wave * 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
-        } else {
-            // the last, partial stage: tokens past the end are rows of zeros; the wave issues 4
-            // operations either way so that the wait counts below stay the same
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (i < rows) dma16(g + i * row_bytes, dst + i * kDmaRowBytes);
-                else {
-                    dma16(gvalid, lds_base + kDmaLdsBytes);           // a valid load (token 0) into a spare row
-                    *reinterpret_cast<uint4 *>(lds + (s % kDmaStages) * kDmaStageBytes + (wave * 4 + i) * kDmaRowBytes + lane * 16) =
-                        make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
+        for (int i = 0; i < 4; ++i)
+            dma16(token + i < A.tokens ? gbase + (token + i) * row_bytes : wgrad_zero_row, dst + i * kDmaRowBytes);
     };
 
     const int wo = wave & 3, wi = wave >> 2;
@@ -625,7 +613,7 @@ hipError_t launch_shape(int out_kind, WgradArgs a, int64_t out, int64_t in, hipS
 
 hipError_t launch_dma(int out_kind, WgradArgs a, int64_t out, int64_t in, hipStream_t s)
 {
-    constexpr int kBytes = kDmaLdsBytes + kDmaRowBytes;        // the stages and one spare row
+    constexpr int kBytes = kDmaLdsBytes;
     static std::atomic<uint64_t> configured{0};
     int device = 0;
     if (hipError_t e = hipGetDevice(&device)) return e;
