@@ -351,10 +351,9 @@ samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void
  *                        Read once per process.
  *   SAMO_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it gives
  *                        up (default 2^20); 0 makes the give-up path reachable in tests.  Read per call.
- *   SAMO_WGRAD_TILE        128, 256 or 512: forces the kernel variant of samo_wgrad_gather / _fp16 (default:
- *                        128 x 128 tiles staged through registers for layers with fewer than 65 tiles
- *                        of 256 x 256, else 256 x 256 tiles copied straight to LDS; 512 forces the
- *                        latter, 256 the same tile staged through registers).  Read per call. */
+ *   SAMO_WGRAD_TILE        128 or 256: forces the tile shape of samo_wgrad_gather / _fp16 (default: 128 x 128
+ *                        for layers of at most 128 tiles of 256 x 256, which would leave compute units
+ *                        idle, else 256 x 256).  Read per call. */
 
 #ifdef __cplusplus
 }

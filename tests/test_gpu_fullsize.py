@@ -346,9 +346,8 @@ def test_index_build_statistics_and_guarded_split_step_under_hip_graph_replay():
 @pytest.mark.parametrize("tokens", [2048, 4096 + 24])
 def test_gpt2p7b_fc1_weight_gradient_compressed_in_the_backward_kernel(tokens):
     """One full-size layer of the 2.7B model (FC1, 2560 x 10240, magnitude-pruned to 10 %): the
-    fused weight gradient in the launch configurations bench.py times — one 2048-token sequence
-    (operands staged through registers) and a longer run with a ragged end (operands copied
-    straight to LDS) — against the oracle on sampled outputs, and against the unfused route of
+    fused weight gradient in the launch configuration bench.py times — one 2048-token sequence —
+    and on a longer run with a ragged end, against the oracle on sampled outputs, and against the unfused route of
     this library (a library GEMM into the dense fp16 tensor, then samo_gather_grads) on every
     output."""
     spec = [s for s in si.config("gpt2.7b", 0.9, layers=1) if s.name.endswith("fc1")][0]

@@ -13,7 +13,7 @@ from gpu_util import DEV, dev_f16_bits, dev_i32, host_bits, ref_seg_ptr
 pytestmark = pytest.mark.gpu
 
 # (tokens, out, in): single blocks, ragged tails in every direction, several tiles of either shape,
-# one to nine 32-token stages (the pipeline's start-up, even and odd counts) with and without a tail
+# one to fourteen stages of 32 tokens, one to seven of 64 (the ring's start-up, wrap-around and drain), with and without a tail
 SHAPES = [(1, 8, 8), (7, 8, 16), (31, 16, 8), (32, 24, 40), (33, 136, 264), (100, 256, 512),
           (64, 384, 520), (257, 128, 256), (96, 264, 776), (45, 520, 72), (130, 520, 528),
           (64, 8, 8), (65, 16, 16), (128, 264, 8), (160, 8, 264), (289, 24, 24), (421, 264, 520)]
@@ -72,11 +72,10 @@ def _problem(tokens, out_f, in_f, kind, seed):
     return dy, x, idx, d_dy, d_x, dev_i32(idx), dev_i32(ref_seg_ptr(idx, out_f * in_f))
 
 
-@pytest.fixture(params=["128", "256", "512"])
+@pytest.fixture(params=["128", "256"])
 def tile(request, monkeypatch):
-    """Every kernel variant (128 x 128 tiles, 256 x 256 tiles staged through registers, 256 x 256
-    tiles copied straight to LDS) on every case; left alone, the library picks by layer size and
-    token count."""
+    """Both kernels (128 x 128 tiles by two wave groups that split each stage's tokens, 256 x 256
+    tiles) on every case; left alone, the library picks by layer size."""
     monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
     return request.param
 
