@@ -353,7 +353,10 @@ samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void
  *                        up (default 2^20); 0 makes the give-up path reachable in tests.  Read per call.
  *   SAMO_WGRAD_TILE        128 or 256: forces the tile shape of samo_wgrad_gather / _fp16 (default: 128 x 128
  *                        for layers of at most 128 tiles of 256 x 256, which would leave compute units
- *                        idle, else 256 x 256).  Read per call. */
+ *                        idle, else 256 x 256 in whole rounds of the compute units and 128 x 128 for a
+ *                        remainder of at most half a round).  Read per call.
+ *   SAMO_WGRAD_ROUND       test aid: the number of tiles taken as one round in that rule, in place of
+ *                        the device's compute-unit count.  Read per call. */
 
 #ifdef __cplusplus
 }

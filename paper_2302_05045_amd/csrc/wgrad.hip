@@ -25,7 +25,8 @@
 // 4 waves of 128 x 128, 0.144 ms with 8 waves of 64 x 128, FC1 of the GPT-3 2.7B shape at 2048
 // tokens):
 //   256 x 256, waves as 4 x 2 of 64 x 128 (128 accumulators), 32 tokens per stage;
-//   128 x 128 for layers of at most 128 large tiles, which would leave compute units idle: two
+//   128 x 128 for what is left of a layer after whole rounds of large tiles, where that is at
+//   most half a round (so also for every layer of up to 128 large tiles): two
 //   groups of four waves, each group covers the whole tile with 64 x 64 per wave (64 accumulators)
 //   and multiplies half of the tokens of every 64-token stage; group 1 hands its sums to group 0
 //   through LDS at the end.
@@ -53,7 +54,6 @@ constexpr int kLdsBytes = kStages * kStageBytes;     // 139264: one workgroup pe
 constexpr int kBigTile = 256, kBigTokens = 32;       // tokens per stage: one per LDS row
 constexpr int kSmallTile = 128, kSmallTokens = 64;   // two per LDS row
 constexpr int kEpiRows = 128;                        // rows of dW per epilogue pass
-constexpr int64_t kSmallUpTo = 128;                  // 256 x 256 tiles of a layer up to which the small shape is used (measured)
 
 struct WgradArgs {
     const _Float16 *dy;      // tokens x out
@@ -66,8 +66,11 @@ struct WgradArgs {
     void *gc;                // fp32 or fp16, by the kernel's OUT
     float inv_scale;
     int accumulate;
-    int tiles_in;
-    int64_t tiles;
+    // the workgroups of a launch take tiles first .. first + count - 1 of the layer's tiles_out x
+    // tiles_in tiles of tile x tile; with quadrants set, those are 256 x 256 tiles and every four
+    // workgroups take the 128 x 128 quarters of one
+    int tile, tiles_out, tiles_in, quadrants;
+    int64_t first, count;
 };
 
 __device__ __attribute__((aligned(16))) const unsigned char wgrad_zero_row[16] = {0};
@@ -99,20 +102,25 @@ __device__ __forceinline__ int tr_lane_offset(int lane)
 // that the tiles sharing operand panels, and neighbouring runs of idx, meet in one L2.  Within
 // the run, tiles go down groups of 4 tile rows before they go across: the 32 tiles an XCD works on
 // at a time then share about 4 + 8 operand panels rather than 1 + 32.
-// Returns false for the surplus workgroups of the last round.
-template <int TILE>
+// Returns false for a workgroup with nothing to do: the surplus of the last round, or a quarter
+// that lies outside the matrix.
 __device__ __forceinline__ bool tile_origin(const WgradArgs &A, int &row0, int &col0)
 {
-    const int64_t per_xcd = (A.tiles + 7) / 8;
-    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= A.tiles) return false;
-    const int tiles_out = (int)(A.tiles / A.tiles_in);
+    const int64_t blocks = A.quadrants ? A.count * 4 : A.count;
+    const int64_t per_xcd = (blocks + 7) / 8;
+    const int64_t local = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (local >= blocks) return false;
+    const int64_t tile = A.first + (A.quadrants ? local >> 2 : local);
     const int group = (int)(tile / (4 * A.tiles_in));
     const int in_group = (int)(tile - (int64_t)group * 4 * A.tiles_in);
-    const int group_rows = tiles_out - group * 4 < 4 ? tiles_out - group * 4 : 4;
-    row0 = (group * 4 + in_group % group_rows) * TILE;   // first row of dW (feature of dY)
-    col0 = (in_group / group_rows) * TILE;               // first column of dW (feature of X)
-    return true;
+    const int group_rows = A.tiles_out - group * 4 < 4 ? A.tiles_out - group * 4 : 4;
+    row0 = (group * 4 + in_group % group_rows) * A.tile;   // first row of dW (feature of dY)
+    col0 = (in_group / group_rows) * A.tile;               // first column of dW (feature of X)
+    if (A.quadrants) {
+        row0 += (int)(local & 1) * (A.tile / 2);
+        col0 += (int)((local >> 1) & 1) * (A.tile / 2);
+    }
+    return row0 < A.out && col0 < A.in;
 }
 
 // The kept entries of a tile row are a run of idx between two bounds: the first kept position at
@@ -234,7 +242,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradArg
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int bounds[2 * kTile];
     int row0, col0;
-    if (!tile_origin<kTile>(A, row0, col0)) return;
+    if (!tile_origin(A, row0, col0)) return;
 
     const int t = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
@@ -321,7 +329,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradA
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int bounds[2 * kTile];
     int row0, col0;
-    if (!tile_origin<kTile>(A, row0, col0)) return;
+    if (!tile_origin(A, row0, col0)) return;
 
     const int t = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
@@ -417,21 +425,28 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradA
     gather_pass<OUT>(A, img, kEpiPitch, bounds, bounds + kTile, row0, col0);
 }
 
-// The LDS size above 64 KiB is a per-device attribute of a kernel: set once per device.
-hipError_t configure_once()
+// The LDS size above 64 KiB is a per-device attribute of a kernel: set once per device, where the
+// device's number of compute units is read too.
+hipError_t configure_once(int *cus)
 {
     static std::atomic<uint64_t> configured{0};
+    static int cus_of[64];
     int device = 0;
     if (hipError_t e = hipGetDevice(&device)) return e;
     const uint64_t bit = 1ull << (device & 63);
-    if (configured.load(std::memory_order_acquire) & bit) return hipSuccess;
-    const void *kernels[4] = {reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF32>),
-                              reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF16>),
-                              reinterpret_cast<const void *>(&wgrad_small_kernel<kOutF32>),
-                              reinterpret_cast<const void *>(&wgrad_small_kernel<kOutF16>)};
-    for (const void *k : kernels)
-        if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)) return e;
-    configured.fetch_or(bit, std::memory_order_release);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
+        const void *kernels[4] = {reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF32>),
+                                  reinterpret_cast<const void *>(&wgrad_big_kernel<kOutF16>),
+                                  reinterpret_cast<const void *>(&wgrad_small_kernel<kOutF32>),
+                                  reinterpret_cast<const void *>(&wgrad_small_kernel<kOutF16>)};
+        for (const void *k : kernels)
+            if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)) return e;
+        int n = 0;
+        if (hipError_t e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device)) return e;
+        cus_of[device & 63] = n;
+        configured.fetch_or(bit, std::memory_order_release);
+    }
+    *cus = cus_of[device & 63];
     return hipSuccess;
 }
 
@@ -442,24 +457,43 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
                         int accumulate, hipStream_t s)
 {
     if (out <= 0 || in <= 0 || nnz <= 0) return hipSuccess;
-    if (hipError_t e = configure_once()) return e;
+    int cus = 0;
+    if (hipError_t e = configure_once(&cus)) return e;
     WgradArgs a;
     a.dy = dy; a.x = x; a.tokens = tokens; a.out = (int)out; a.in = (int)in;
     a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
-    const int64_t big_tiles = ceil_div(out, kBigTile) * ceil_div(in, kBigTile);
+    const int64_t big_out = ceil_div(out, kBigTile), big_in = ceil_div(in, kBigTile), big_tiles = big_out * big_in;
     const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128 or 256
     const int force = forced ? atoi(forced) : 0;
-    const bool small = force == kSmallTile || (force != kBigTile && big_tiles <= kSmallUpTo);
-    const int tile = small ? kSmallTile : kBigTile;
-    a.tiles_in = (int)ceil_div(in, tile);
-    a.tiles = ceil_div(out, tile) * a.tiles_in;
-    const unsigned grid = (unsigned)(ceil_div(a.tiles, 8) * 8);   // whole rounds of the 8 XCDs; the surplus exits at once
-    if (small) {
-        if (out_kind == kOutF32) wgrad_small_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
-        else wgrad_small_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
-    } else {
-        if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
-        else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+    if (const char *round = getenv("SAMO_WGRAD_ROUND"))        // test aid: tiles per round in place of the CU count
+        if (atoi(round) > 0) cus = atoi(round);
+    // Large tiles in whole rounds of the compute units; what is left over after the last whole
+    // round goes to the small shape when that is the quicker way to finish it: up to half a round
+    // of large tiles is at most two rounds of small ones, and a small round takes 0.4 of a large.
+    int64_t as_big = big_tiles, as_small = 0;
+    if (force == kSmallTile) as_big = 0, as_small = big_tiles;
+    else if (force != kBigTile && cus > 0 && big_tiles % cus != 0 && big_tiles % cus <= cus / 2) {
+        as_small = big_tiles % cus;
+        as_big = big_tiles - as_small;
+    }
+    auto launch = [&](bool small, unsigned blocks) {
+        const unsigned grid = (blocks + 7) / 8 * 8;             // whole rounds of the 8 XCDs; the surplus exits at once
+        if (small) {
+            if (out_kind == kOutF32) wgrad_small_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+            else wgrad_small_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+        } else {
+            if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+            else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+        }
+    };
+    a.tile = kBigTile; a.tiles_out = (int)big_out; a.tiles_in = (int)big_in;
+    if (as_big > 0) {
+        a.quadrants = 0; a.first = 0; a.count = as_big;
+        launch(false, (unsigned)as_big);
+    }
+    if (as_small > 0) {
+        a.quadrants = 1; a.first = as_big; a.count = as_small;
+        launch(true, (unsigned)(as_small * 4));
     }
     return hipGetLastError();
 }

@@ -72,11 +72,16 @@ def _problem(tokens, out_f, in_f, kind, seed):
     return dy, x, idx, d_dy, d_x, dev_i32(idx), dev_i32(ref_seg_ptr(idx, out_f * in_f))
 
 
-@pytest.fixture(params=["128", "256"])
+@pytest.fixture(params=["128", "256", "mixed"])
 def tile(request, monkeypatch):
     """Both kernels (128 x 128 tiles by two wave groups that split each stage's tokens, 256 x 256
-    tiles) on every case; left alone, the library picks by layer size."""
-    monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
+    tiles) on every case, and the library's own rule with a round of 4 tiles, so that layers of 5,
+    6 or 9 large tiles here are split between the two as a layer of 300 is on 256 compute units."""
+    if request.param == "mixed":
+        monkeypatch.delenv("SAMO_WGRAD_TILE", raising=False)
+        monkeypatch.setenv("SAMO_WGRAD_ROUND", "4")
+    else:
+        monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
     return request.param
 
 
