@@ -125,8 +125,9 @@ __device__ __forceinline__ bool tile_origin(const WgradArgs &A, int &row0, int &
 
 // The kept entries of a tile row are a run of idx between two bounds: the first kept position at
 // or after the row's first column in the tile, and the first one at or after the column where the
-// tile ends.  A bound is searched in two steps so that the copies of the first stages can be
-// issued between them: bound_open reads the segment's range from seg_ptr, bound_close settles it.
+// tile ends.  A bound is searched in three steps with the tile's other work between them:
+// bound_open reads the segment's range from seg_ptr, bound_window requests a few entries of idx
+// where the bound should be, bound_settle decides.
 struct Bound {
     int lo, hi, key;
 };
@@ -149,22 +150,39 @@ __device__ __forceinline__ Bound bound_open(const WgradArgs &A, int row, int col
 // First a guess by interpolation inside the segment (kept elements spread evenly over it would
 // put the bound at lo + (hi - lo) * offset / 1024) and a look at the 8 entries around it — on
 // masks without structure that settles it in one round trip; then bisection of what is left.
-__device__ __forceinline__ int bound_close(const WgradArgs &A, Bound b)
+// The look is requested by bound_window and used by bound_settle, which a kernel calls after its
+// main loop: the entries travel while the tile is multiplied.
+struct Window {
+    int w0, wn;
+    int v[8];
+};
+
+__device__ __forceinline__ Window bound_window(const WgradArgs &A, const Bound &b)
 {
+    Window w;
+    w.w0 = 0; w.wn = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w.v[i] = 0;
     if (b.lo < b.hi) {
         const int guess = b.lo + (int)(((int64_t)(b.hi - b.lo) * (b.key & (kSeg - 1))) >> 10);
-        int w0 = guess - 4 > b.lo ? guess - 4 : b.lo;
-        if (w0 + 8 > b.hi) w0 = b.hi - 8 > b.lo ? b.hi - 8 : b.lo;
-        const int wn = b.hi - w0 < 8 ? b.hi - w0 : 8;
-        int v[8];
+        w.w0 = guess - 4 > b.lo ? guess - 4 : b.lo;
+        if (w.w0 + 8 > b.hi) w.w0 = b.hi - 8 > b.lo ? b.hi - 8 : b.lo;
+        w.wn = b.hi - w.w0 < 8 ? b.hi - w.w0 : 8;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = A.idx[w0 + (i < wn ? i : wn - 1)];
+        for (int i = 0; i < 8; ++i) w.v[i] = A.idx[w.w0 + (i < w.wn ? i : w.wn - 1)];
+    }
+    return w;
+}
+
+__device__ __forceinline__ int bound_settle(const WgradArgs &A, Bound b, const Window &w)
+{
+    if (b.lo < b.hi) {
         int below = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) below += (i < wn && v[i] < b.key) ? 1 : 0;
-        if (below == 0) b.hi = w0;                               // the bound is at or before the window
-        else if (below == wn) b.lo = w0 + wn;                    // at or after its end
-        else b.lo = b.hi = w0 + below;                           // inside
+        for (int i = 0; i < 8; ++i) below += (i < w.wn && w.v[i] < b.key) ? 1 : 0;
+        if (below == 0) b.hi = w.w0;                             // the bound is at or before the window
+        else if (below == w.wn) b.lo = w.w0 + w.wn;              // at or after its end
+        else b.lo = b.hi = w.w0 + below;                         // inside
     }
     while (b.lo < b.hi) {
         const int mid = (b.lo + b.hi) >> 1;
@@ -293,30 +311,29 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradArg
     };
 
     for (int64_t s = 0; s < 3 && s < stages; ++s) issue_stage(s);
-    bounds[t] = bound_close(A, open);            // while those first stages are on their way
+    const Window window = bound_window(A, open);
     run_stages(stages, lds, issue_stage, multiply_stage);
+    bounds[t] = bound_settle(A, open, window);
 
     _Float16 *img = reinterpret_cast<_Float16 *>(lds);
+    static_assert(kTile * kEpiPitch * 2 <= kLdsBytes, "the whole tile's image fits in the stages");
+#pragma unroll
+    for (int bo = 0; bo < 2; ++bo)
+#pragma unroll
+        for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                half4 h;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];   // round to nearest even
+                const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
+                *reinterpret_cast<half4 *>(img + (wo * 64 + bo * 32 + l32) * kEpiPitch + col) = h;
+            }
+    __syncthreads();
 #pragma unroll 1
-    for (int pass = 0; pass < kTile / kEpiRows; ++pass) {
-        if ((wo >> 1) == pass) {
-#pragma unroll
-            for (int bo = 0; bo < 2; ++bo)
-#pragma unroll
-                for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        half4 h;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[bo][bi][q * 4 + e];   // round to nearest even
-                        const int col = wi * 128 + bi * 32 + q * 8 + khalf * 4;
-                        *reinterpret_cast<half4 *>(img + ((wo & 1) * 64 + bo * 32 + l32) * kEpiPitch + col) = h;
-                    }
-        }
-        __syncthreads();
-        gather_pass<OUT>(A, img, kEpiPitch, bounds + pass * kEpiRows, bounds + kTile + pass * kEpiRows, row0 + pass * kEpiRows, col0);
-        __syncthreads();
-    }
+    for (int pass = 0; pass < kTile / kEpiRows; ++pass)
+        gather_pass<OUT>(A, img + pass * kEpiRows * kEpiPitch, kEpiPitch, bounds + pass * kEpiRows, bounds + kTile + pass * kEpiRows,
+                         row0 + pass * kEpiRows, col0);
 }
 
 // 128 x 128 tile.  LDS row j of a stage: token j and token j + 32, each as 128 X features then
@@ -382,9 +399,10 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradA
     };
 
     for (int64_t s = 0; s < 3 && s < stages; ++s) issue_stage(s);
-    const int closed = bound_close(A, open);
-    if (t < 2 * kTile) bounds[t] = closed;
+    const Window window = bound_window(A, open);
     run_stages(stages, lds, issue_stage, multiply_stage);
+    const int closed = bound_settle(A, open, window);
+    if (t < 2 * kTile) bounds[t] = closed;
 
     // group 1's sums -> LDS as fp32; group 0 adds them to its own, rounds once to fp16 and writes
     // the image behind them
