@@ -53,7 +53,6 @@ constexpr int kStages = 4;
 constexpr int kLdsBytes = kStages * kStageBytes;     // 139264: one workgroup per CU
 constexpr int kBigTile = 256, kBigTokens = 32;       // tokens per stage: one per LDS row
 constexpr int kSmallTile = 128, kSmallTokens = 64;   // two per LDS row
-constexpr int kEpiRows = 128;                        // rows of dW per epilogue pass
 
 struct WgradArgs {
     const _Float16 *dy;      // tokens x out
@@ -212,14 +211,14 @@ __device__ __forceinline__ void run_stages(int64_t stages, unsigned char *lds, I
     __syncthreads();
 }
 
-// Epilogue pass over kEpiRows rows of dW held as an fp16 image in LDS: each of the 16 half-waves
-// takes 8 rows; per row, idx between the row's two bounds is read coalesced, the values are picked
+// Epilogue over the ROWS rows of a tile held as an fp16 image in LDS: each of the 16 half-waves
+// takes every 16th row, all of them at once; per row, idx between the row's two bounds is read coalesced, the values are picked
 // from the image and the compressed gradient is written coalesced.
-template <int OUT>
+template <int OUT, int ROWS>
 __device__ __forceinline__ void gather_pass(const WgradArgs &A, const _Float16 *img, int pitch, const int *first, const int *last,
                                             int first_row, int col0)
 {
-    constexpr int kRows = kEpiRows / (kWgThreads / 32);
+    constexpr int kRows = ROWS / (kWgThreads / 32);
     const int hw = threadIdx.x >> 5, l32 = threadIdx.x & 31;
     int lo[kRows], hi[kRows], longest = 0;
 #pragma unroll
@@ -330,10 +329,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradArg
                 *reinterpret_cast<half4 *>(img + (wo * 64 + bo * 32 + l32) * kEpiPitch + col) = h;
             }
     __syncthreads();
-#pragma unroll 1
-    for (int pass = 0; pass < kTile / kEpiRows; ++pass)
-        gather_pass<OUT>(A, img + pass * kEpiRows * kEpiPitch, kEpiPitch, bounds + pass * kEpiRows, bounds + kTile + pass * kEpiRows,
-                         row0 + pass * kEpiRows, col0);
+    gather_pass<OUT, kTile>(A, img, kEpiPitch, bounds, bounds + kTile, row0, col0);
 }
 
 // 128 x 128 tile.  LDS row j of a stage: token j and token j + 32, each as 128 X features then
@@ -439,8 +435,7 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradA
                 }
     }
     __syncthreads();
-    static_assert(kTile == kEpiRows, "one epilogue pass");
-    gather_pass<OUT>(A, img, kEpiPitch, bounds, bounds + kTile, row0, col0);
+    gather_pass<OUT, kTile>(A, img, kEpiPitch, bounds, bounds + kTile, row0, col0);
 }
 
 // The LDS size above 64 KiB is a per-device attribute of a kernel: set once per device, where the
