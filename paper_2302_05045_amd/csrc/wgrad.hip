@@ -74,6 +74,10 @@ struct WgradArgs {
 
 __device__ __attribute__((aligned(16))) const unsigned char wgrad_zero_row[16] = {0};
 
+// One copy instruction: the wave's 64 x 16 bytes from the lanes' global addresses to LDS at
+// lds_byte_addr + 16 * lane.  It writes M0, a register the compiler reserves and does not let an
+// asm statement declare as clobbered; nothing else in these kernels makes the compiler use M0 (no
+// register arrays indexed at run time, no other LDS-direct or GWS operation).
 __device__ __forceinline__ void dma16(const void *g, unsigned lds_byte_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_addr) : "memory");
