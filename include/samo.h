@@ -328,6 +328,31 @@ samo_status samo_wgrad_gather_fp16(const uint16_t *d_dy, const uint16_t *d_x, in
                                    const int32_t *d_seg_ptr, int64_t nnz, uint16_t *d_gc16,
                                    int32_t accumulate, void *stream);
 
+/* The same for several layers in one call: the tiles of all the jobs' layers are dealt to the
+ * compute units as one list, so that a layer whose own tiles would end in a partly filled round
+ * shares that round with the next layer (the four matrices of a GPT-3 2.7B transformer layer at
+ * 2048 tokens: 0.37 ms in one call against 0.45 ms in four).  The caller holds dY and X of all
+ * the jobs' layers until the call — it trades that memory for the time.  Each job is one layer
+ * with the arguments of samo_wgrad_gather / samo_wgrad_gather_fp16 (d_gc: fp32 for
+ * samo_wgrad_gather_batched, fp16 for samo_wgrad_gather_fp16_batched; tokens may differ between
+ * jobs); h_jobs is a host array that is read before the call returns; count <=
+ * SAMO_WGRAD_MAX_JOBS; jobs with nnz == 0 are skipped.  A call with one job is the unbatched
+ * entry.  Any invalid job rejects the whole call before anything is launched. */
+#define SAMO_WGRAD_MAX_JOBS 8
+typedef struct samo_wgrad_job {
+    const uint16_t *d_dy;         /* device, tokens x out fp16 */
+    const uint16_t *d_x;          /* device, tokens x in fp16 */
+    int64_t tokens, out, in;
+    const int32_t *d_idx;         /* device, nnz; NULL for an unpruned layer */
+    const int32_t *d_seg_ptr;     /* device; required with d_idx */
+    int64_t nnz;
+    void *d_gc;                   /* device, nnz elements of the entry's output type */
+} samo_wgrad_job;
+samo_status samo_wgrad_gather_batched(int32_t count, const samo_wgrad_job *h_jobs,
+                                      float inv_loss_scale, void *stream);
+samo_status samo_wgrad_gather_fp16_batched(int32_t count, const samo_wgrad_job *h_jobs,
+                                           int32_t accumulate, void *stream);
+
 /* ---------------------------------------------------------------- byte accounting (Section III-D, Eq. 1-5)  [host only]
  * paper_default = 20 * n_total; paper_samo = 24 * nnz_total + 2 * n_total;
  * resident = what this library's fused pipeline keeps allocated:

@@ -53,6 +53,16 @@ class SgdCfg(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float)]
 
 
+class WgradJob(ctypes.Structure):
+    """samo_wgrad_job"""
+    _fields_ = [("d_dy", ctypes.c_void_p), ("d_x", ctypes.c_void_p), ("tokens", ctypes.c_int64),
+                ("out", ctypes.c_int64), ("in_", ctypes.c_int64), ("d_idx", ctypes.c_void_p),
+                ("d_seg_ptr", ctypes.c_void_p), ("nnz", ctypes.c_int64), ("d_gc", ctypes.c_void_p)]
+
+
+SAMO_WGRAD_MAX_JOBS = 8
+
+
 class StepGuard(ctypes.Structure):
     """samo_step_guard"""
     _fields_ = [("d_stats", ctypes.c_void_p), ("max_grad_norm", ctypes.c_float), ("skip_on_nonfinite", ctypes.c_int32)]
@@ -132,6 +142,10 @@ _SIGNATURES = {
     "samo_wgrad_gather_fp16": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                                 ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                                 ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]),
+    "samo_wgrad_gather_batched": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(WgradJob), ctypes.c_float,
+                                                   ctypes.c_void_p]),
+    "samo_wgrad_gather_fp16_batched": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(WgradJob), ctypes.c_int32,
+                                                        ctypes.c_void_p]),
     "samo_stream_copy": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
 }
 
@@ -353,9 +367,34 @@ def samo_wgrad_gather(dy: torch.Tensor, x: torch.Tensor, idx: Optional[torch.Ten
 
 def samo_wgrad_gather_fp16(dy: torch.Tensor, x: torch.Tensor, idx: Optional[torch.Tensor],
                            seg_ptr: Optional[torch.Tensor], gc16: torch.Tensor, accumulate: bool = False) -> None:
+    """gc16 = that weight gradient, rounded to fp16, at idx; added to gc16 (in fp16) if accumulate."""
     nnz = gc16.numel()
     _check(lib().samo_wgrad_gather_fp16(*_wgrad_args(dy, x, idx, seg_ptr, nnz), _dev(gc16, _F16, "gc16"),
                                         int(bool(accumulate)), _stream()), "samo_wgrad_gather_fp16")
+
+
+def _wgrad_jobs(jobs, dtype, name: str):
+    """A samo_wgrad_job array from (dy, x, idx, seg_ptr, gc) tuples."""
+    arr = (WgradJob * max(len(jobs), 1))()
+    for j, (dy, x, idx, seg_ptr, gc) in enumerate(jobs):
+        nnz = gc.numel()
+        dy_ptr, x_ptr, tokens, out_features, in_features, idx_ptr, seg, _ = _wgrad_args(dy, x, idx, seg_ptr, nnz)
+        arr[j] = WgradJob(dy_ptr, x_ptr, tokens, out_features, in_features, idx_ptr, seg, nnz,
+                          _dev(gc, dtype, "%s of job %d" % (name, j)))
+    return arr
+
+
+def samo_wgrad_gather_batched(jobs, inv_loss_scale: float) -> None:
+    """samo_wgrad_gather for every (dy, x, idx, seg_ptr, gc) of jobs (at most SAMO_WGRAD_MAX_JOBS), the
+    layers' tiles dealt to the compute units as one list."""
+    _check(lib().samo_wgrad_gather_batched(len(jobs), _wgrad_jobs(jobs, torch.float32, "gc"), float(inv_loss_scale),
+                                           _stream()), "samo_wgrad_gather_batched")
+
+
+def samo_wgrad_gather_fp16_batched(jobs, accumulate: bool = False) -> None:
+    """samo_wgrad_gather_fp16 for every (dy, x, idx, seg_ptr, gc16) of jobs."""
+    _check(lib().samo_wgrad_gather_fp16_batched(len(jobs), _wgrad_jobs(jobs, _F16, "gc16"), int(bool(accumulate)),
+                                                _stream()), "samo_wgrad_gather_fp16_batched")
 
 
 def sgd_cfg(lr: float, momentum: float = 0.9, weight_decay: float = 0.0) -> SgdCfg:

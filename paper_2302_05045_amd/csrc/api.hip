@@ -325,23 +325,48 @@ samo_status check_wgrad(const void *d_dy, const void *d_x, int64_t tokens, int64
 }
 }  // namespace
 
+namespace {
+samo_status wgrad_batched(int out_kind, int32_t count, const samo_wgrad_job *h_jobs, float inv_scale, int accumulate,
+                          void *stream)
+{
+    if (count < 0 || count > SAMO_WGRAD_MAX_JOBS) return SAMO_ERR_SIZE;
+    if (count > 0 && !h_jobs) return SAMO_ERR_NULL;
+    WgradJob jobs[SAMO_WGRAD_MAX_JOBS];
+    for (int j = 0; j < count; ++j) {
+        const samo_wgrad_job &h = h_jobs[j];
+        if (samo_status s = check_wgrad(h.d_dy, h.d_x, h.tokens, h.out, h.in, h.d_idx, h.d_seg_ptr, h.nnz, h.d_gc)) return s;
+        jobs[j] = {reinterpret_cast<const _Float16 *>(h.d_dy), reinterpret_cast<const _Float16 *>(h.d_x), h.tokens,
+                   (int)h.out, (int)h.in, h.d_idx, h.d_seg_ptr, h.nnz, h.d_gc};
+    }
+    return hip_status(launch_wgrad(out_kind, jobs, count, inv_scale, accumulate, as_stream(stream)));
+}
+}  // namespace
+
 samo_status samo_wgrad_gather(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens, int64_t out, int64_t in,
                               const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz, float inv_loss_scale,
                               float *d_gc, void *stream)
 {
-    if (samo_status s = check_wgrad(d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc)) return s;
-    if (samo_status s = check_scale(inv_loss_scale)) return s;
-    return hip_status(launch_wgrad(kOutF32, reinterpret_cast<const _Float16 *>(d_dy), reinterpret_cast<const _Float16 *>(d_x),
-                                   tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc, inv_loss_scale, 0, as_stream(stream)));
+    const samo_wgrad_job job = {d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc};
+    return samo_wgrad_gather_batched(1, &job, inv_loss_scale, stream);
 }
 
 samo_status samo_wgrad_gather_fp16(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens, int64_t out, int64_t in,
                                    const int32_t *d_idx, const int32_t *d_seg_ptr, int64_t nnz, uint16_t *d_gc16,
                                    int32_t accumulate, void *stream)
 {
-    if (samo_status s = check_wgrad(d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc16)) return s;
-    return hip_status(launch_wgrad(kOutF16, reinterpret_cast<const _Float16 *>(d_dy), reinterpret_cast<const _Float16 *>(d_x),
-                                   tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc16, 1.f, accumulate != 0, as_stream(stream)));
+    const samo_wgrad_job job = {d_dy, d_x, tokens, out, in, d_idx, d_seg_ptr, nnz, d_gc16};
+    return samo_wgrad_gather_fp16_batched(1, &job, accumulate, stream);
+}
+
+samo_status samo_wgrad_gather_batched(int32_t count, const samo_wgrad_job *h_jobs, float inv_loss_scale, void *stream)
+{
+    if (samo_status s = check_scale(inv_loss_scale)) return s;
+    return wgrad_batched(kOutF32, count, h_jobs, inv_loss_scale, 0, stream);
+}
+
+samo_status samo_wgrad_gather_fp16_batched(int32_t count, const samo_wgrad_job *h_jobs, int32_t accumulate, void *stream)
+{
+    return wgrad_batched(kOutF16, count, h_jobs, 1.f, accumulate != 0, stream);
 }
 
 samo_status samo_adam_step(float *d_p, float *d_m, float *d_v, const float *d_gc, int64_t nnz,

@@ -129,10 +129,20 @@ hipError_t launch_flat_step(int opt, const LaunchSet &ls, const OptK &k, const G
 int64_t stats_workspace_partials(int64_t gather_wgs);
 hipError_t launch_stats_finalize(StatPartial *partials, int64_t gather_wgs, samo_grad_stats *out, hipStream_t s);
 
-// Weight gradient dY^T X of a linear layer gathered at the index (out_kind: kOutF32 or kOutF16).
-hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
-                        const int32_t *idx, const int32_t *seg_ptr, int64_t nnz, void *gc, float inv_scale,
-                        int accumulate, hipStream_t s);
+// Weight gradients dY^T X of up to kWgradMaxJobs linear layers, each gathered at its layer's index, in
+// one launch (out_kind: kOutF32 or kOutF16; gc of that type).
+constexpr int kWgradMaxJobs = SAMO_WGRAD_MAX_JOBS;
+struct WgradJob {
+    const _Float16 *dy;      // tokens x out
+    const _Float16 *x;       // tokens x in
+    int64_t tokens;
+    int out, in;
+    const int32_t *idx;
+    const int32_t *seg_ptr;
+    int64_t nnz;
+    void *gc;
+};
+hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 

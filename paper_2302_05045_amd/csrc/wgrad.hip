@@ -54,6 +54,7 @@ constexpr int kLdsBytes = kStages * kStageBytes;     // 139264: one workgroup pe
 constexpr int kBigTile = 256, kBigTokens = 32;       // tokens per stage: one per LDS row
 constexpr int kSmallTile = 128, kSmallTokens = 64;   // two per LDS row
 
+// What a workgroup knows of the layer its tile belongs to.
 struct WgradArgs {
     const _Float16 *dy;      // tokens x out
     const _Float16 *x;       // tokens x in
@@ -65,11 +66,21 @@ struct WgradArgs {
     void *gc;                // fp32 or fp16, by the kernel's OUT
     float inv_scale;
     int accumulate;
-    // the workgroups of a launch take tiles first .. first + count - 1 of the layer's tiles_out x
-    // tiles_in tiles of tile x tile; with quadrants set, those are 256 x 256 tiles and every four
-    // workgroups take the 128 x 128 quarters of one
-    int tile, tiles_out, tiles_in, quadrants;
-    int64_t first, count;
+};
+
+// A launch: the 256 x 256 tiles of up to kWgradMaxJobs layers in one list, layer after layer
+// (layer j owns tiles first_tile[j] .. first_tile[j+1] - 1, tiles_out[j] x tiles_in[j] of them);
+// the launch's workgroups take tiles first .. first + tiles - 1 of that list, or, with quadrants
+// set, four workgroups take the 128 x 128 quarters of each.
+struct WgradBatch {
+    WgradJob job[kWgradMaxJobs];
+    int tiles_out[kWgradMaxJobs], tiles_in[kWgradMaxJobs];
+    int64_t first_tile[kWgradMaxJobs + 1];
+    int jobs;
+    float inv_scale;
+    int accumulate;
+    int quadrants;
+    int64_t first, tiles;
 };
 
 __device__ __attribute__((aligned(16))) const unsigned char wgrad_zero_row[16] = {0};
@@ -107,21 +118,29 @@ __device__ __forceinline__ int tr_lane_offset(int lane)
 // at a time then share about 4 + 8 operand panels rather than 1 + 32.
 // Returns false for a workgroup with nothing to do: the surplus of the last round, or a quarter
 // that lies outside the matrix.
-__device__ __forceinline__ bool tile_origin(const WgradArgs &A, int &row0, int &col0)
+__device__ __forceinline__ bool tile_origin(const WgradBatch &B, WgradArgs &A, int &row0, int &col0)
 {
-    const int64_t blocks = A.quadrants ? A.count * 4 : A.count;
+    const int64_t blocks = B.quadrants ? B.tiles * 4 : B.tiles;
     const int64_t per_xcd = (blocks + 7) / 8;
     const int64_t local = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (local >= blocks) return false;
-    const int64_t tile = A.first + (A.quadrants ? local >> 2 : local);
-    const int group = (int)(tile / (4 * A.tiles_in));
-    const int in_group = (int)(tile - (int64_t)group * 4 * A.tiles_in);
-    const int group_rows = A.tiles_out - group * 4 < 4 ? A.tiles_out - group * 4 : 4;
-    row0 = (group * 4 + in_group % group_rows) * A.tile;   // first row of dW (feature of dY)
-    col0 = (in_group / group_rows) * A.tile;               // first column of dW (feature of X)
-    if (A.quadrants) {
-        row0 += (int)(local & 1) * (A.tile / 2);
-        col0 += (int)((local >> 1) & 1) * (A.tile / 2);
+    const int64_t listed = B.first + (B.quadrants ? local >> 2 : local);
+    int j = 0;
+    while (j + 1 < B.jobs && listed >= B.first_tile[j + 1]) ++j;
+    const WgradJob &J = B.job[j];
+    A.dy = J.dy; A.x = J.x; A.tokens = J.tokens; A.out = J.out; A.in = J.in;
+    A.idx = J.idx; A.seg_ptr = J.seg_ptr; A.nnz = J.nnz; A.gc = J.gc;
+    A.inv_scale = B.inv_scale; A.accumulate = B.accumulate;
+    const int64_t tile = listed - B.first_tile[j];
+    const int tiles_out = B.tiles_out[j], tiles_in = B.tiles_in[j];
+    const int group = (int)(tile / (4 * tiles_in));
+    const int in_group = (int)(tile - (int64_t)group * 4 * tiles_in);
+    const int group_rows = tiles_out - group * 4 < 4 ? tiles_out - group * 4 : 4;
+    row0 = (group * 4 + in_group % group_rows) * kBigTile;   // first row of dW (feature of dY)
+    col0 = (in_group / group_rows) * kBigTile;               // first column of dW (feature of X)
+    if (B.quadrants) {
+        row0 += (int)(local & 1) * kSmallTile;
+        col0 += (int)((local >> 1) & 1) * kSmallTile;
     }
     return row0 < A.out && col0 < A.in;
 }
@@ -257,13 +276,14 @@ __device__ __forceinline__ void gather_pass(const WgradArgs &A, const _Float16 *
 
 // 256 x 256 tile.  LDS row j of a stage: token j as 256 X features then 256 dY features.
 template <int OUT>
-__global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradArgs A)
+__global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradBatch B)
 {
     constexpr int kTile = kBigTile, kEpiPitch = kTile + 8;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int bounds[2 * kTile];
+    WgradArgs A;
     int row0, col0;
-    if (!tile_origin(A, row0, col0)) return;
+    if (!tile_origin(B, A, row0, col0)) return;
 
     const int t = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
@@ -339,14 +359,15 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_big_kernel(const WgradArg
 // 128 x 128 tile.  LDS row j of a stage: token j and token j + 32, each as 128 X features then
 // 128 dY features; wave group g multiplies the tokens in slot g of the rows.
 template <int OUT>
-__global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradArgs A)
+__global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradBatch B)
 {
     constexpr int kTile = kSmallTile, kEpiPitch = kTile + 8, kSumPitch = kTile + 4;
     static_assert(kTile * kSumPitch * 4 + kTile * kEpiPitch * 2 <= kLdsBytes, "group 1's sums and the image reuse the stages");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int bounds[2 * kTile];
+    WgradArgs A;
     int row0, col0;
-    if (!tile_origin(A, row0, col0)) return;
+    if (!tile_origin(B, A, row0, col0)) return;
 
     const int t = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
@@ -469,17 +490,26 @@ hipError_t configure_once(int *cus)
 
 }  // namespace
 
-hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int64_t tokens, int64_t out, int64_t in,
-                        const int32_t *idx, const int32_t *seg_ptr, int64_t nnz, void *gc, float inv_scale,
-                        int accumulate, hipStream_t s)
+hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s)
 {
-    if (out <= 0 || in <= 0 || nnz <= 0) return hipSuccess;
+    WgradBatch b;
+    b.jobs = 0; b.inv_scale = inv_scale; b.accumulate = accumulate;
+    b.first_tile[0] = 0;
+    for (int j = 0; j < count && b.jobs < kWgradMaxJobs; ++j) {
+        if (jobs[j].out <= 0 || jobs[j].in <= 0 || jobs[j].nnz <= 0) continue;     // nothing to write
+        const int k = b.jobs++;
+        b.job[k] = jobs[j];
+        b.tiles_out[k] = (int)ceil_div(jobs[j].out, kBigTile);
+        b.tiles_in[k] = (int)ceil_div(jobs[j].in, kBigTile);
+        b.first_tile[k + 1] = b.first_tile[k] + (int64_t)b.tiles_out[k] * b.tiles_in[k];
+    }
+    if (b.jobs == 0) return hipSuccess;
+    for (int k = b.jobs; k < kWgradMaxJobs; ++k) {
+        b.job[k] = b.job[0]; b.tiles_out[k] = b.tiles_in[k] = 1; b.first_tile[k + 1] = b.first_tile[b.jobs];
+    }
     int cus = 0;
     if (hipError_t e = configure_once(&cus)) return e;
-    WgradArgs a;
-    a.dy = dy; a.x = x; a.tokens = tokens; a.out = (int)out; a.in = (int)in;
-    a.idx = idx; a.seg_ptr = seg_ptr; a.nnz = nnz; a.gc = gc; a.inv_scale = inv_scale; a.accumulate = accumulate;
-    const int64_t big_out = ceil_div(out, kBigTile), big_in = ceil_div(in, kBigTile), big_tiles = big_out * big_in;
+    const int64_t big_tiles = b.first_tile[b.jobs];
     const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128 or 256
     const int force = forced ? atoi(forced) : 0;
     if (const char *round = getenv("SAMO_WGRAD_ROUND"))        // test aid: tiles per round in place of the CU count
@@ -496,20 +526,19 @@ hipError_t launch_wgrad(int out_kind, const _Float16 *dy, const _Float16 *x, int
     auto launch = [&](bool small, unsigned blocks) {
         const unsigned grid = (blocks + 7) / 8 * 8;             // whole rounds of the 8 XCDs; the surplus exits at once
         if (small) {
-            if (out_kind == kOutF32) wgrad_small_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
-            else wgrad_small_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+            if (out_kind == kOutF32) wgrad_small_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(b);
+            else wgrad_small_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(b);
         } else {
-            if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
-            else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(a);
+            if (out_kind == kOutF32) wgrad_big_kernel<kOutF32><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(b);
+            else wgrad_big_kernel<kOutF16><<<dim3(grid), dim3(kWgThreads), kLdsBytes, s>>>(b);
         }
     };
-    a.tile = kBigTile; a.tiles_out = (int)big_out; a.tiles_in = (int)big_in;
     if (as_big > 0) {
-        a.quadrants = 0; a.first = 0; a.count = as_big;
+        b.quadrants = 0; b.first = 0; b.tiles = as_big;
         launch(false, (unsigned)as_big);
     }
     if (as_small > 0) {
-        a.quadrants = 1; a.first = as_big; a.count = as_small;
+        b.quadrants = 1; b.first = as_big; b.tiles = as_small;
         launch(true, (unsigned)(as_small * 4));
     }
     return hipGetLastError();

@@ -79,6 +79,24 @@ int main(void)
     EXPECT(samo_wgrad_gather(fake, fake, 4, 8, 16, fake, fake, 0, 1.0f, NULL, NULL), SAMO_OK);              /* nothing kept: nothing to do */
     EXPECT(samo_wgrad_gather_fp16(fake, fake, 4, 8, 16, fake, fake, 90, NULL, 0, NULL), SAMO_ERR_NULL);
     EXPECT(samo_wgrad_gather_fp16(fake, fake, 4, 8, 16, fake, fake, 129, fake, 1, NULL), SAMO_ERR_SIZE);
+    {
+        samo_wgrad_job jobs[SAMO_WGRAD_MAX_JOBS + 1];
+        for (int j = 0; j <= SAMO_WGRAD_MAX_JOBS; ++j) {
+            samo_wgrad_job ok = {fake, fake, 4, 8, 16, fake, fake, 0, NULL};     /* nothing kept: skipped */
+            jobs[j] = ok;
+        }
+        EXPECT(samo_wgrad_gather_batched(0, NULL, 1.0f, NULL), SAMO_OK);
+        EXPECT(samo_wgrad_gather_batched(SAMO_WGRAD_MAX_JOBS, jobs, 1.0f, NULL), SAMO_OK);
+        EXPECT(samo_wgrad_gather_batched(SAMO_WGRAD_MAX_JOBS + 1, jobs, 1.0f, NULL), SAMO_ERR_SIZE);
+        EXPECT(samo_wgrad_gather_batched(-1, jobs, 1.0f, NULL), SAMO_ERR_SIZE);
+        EXPECT(samo_wgrad_gather_batched(2, NULL, 1.0f, NULL), SAMO_ERR_NULL);
+        EXPECT(samo_wgrad_gather_batched(2, jobs, 0.0f, NULL), SAMO_ERR_ARG);
+        jobs[1].in = 12;                                                        /* one bad job rejects the call */
+        EXPECT(samo_wgrad_gather_batched(2, jobs, 1.0f, NULL), SAMO_ERR_SIZE);
+        EXPECT(samo_wgrad_gather_fp16_batched(2, jobs, 0, NULL), SAMO_ERR_SIZE);
+        jobs[1].in = 16; jobs[1].nnz = 90;                                      /* kept entries but no output */
+        EXPECT(samo_wgrad_gather_fp16_batched(2, jobs, 0, NULL), SAMO_ERR_NULL);
+    }
 
     {
         samo_layer layers[2];

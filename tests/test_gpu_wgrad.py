@@ -189,6 +189,60 @@ def test_overflow_rounds_to_infinity_and_specials_propagate(tile):
     assert np.array_equal(got[ok], want[ok])                         # 40 * 4096 > 65504: +inf; column 5: +inf
 
 
+def test_several_layers_in_one_call_share_the_tile_list(tile):
+    """Five layers of different shapes, token counts and masks in one batched call, one of them with
+    nothing kept and one without an index: each layer's result against the oracle; with the round of
+    4 tiles the 14 large tiles of the list are three rounds of large ones and two as small quarters,
+    and layer boundaries fall inside rounds."""
+    layers = [(64, 384, 264, "bernoulli10"), (33, 136, 264, "rows"), (70, 24, 40, "none"), (130, 520, 264, "bernoulli50"),
+              (45, 264, 8, "dense")]
+    jobs16, jobs32, checks = [], [], []
+    inv = np.float32(1.0 / si.LOSS_SCALE)
+    for j, (tokens, out_f, in_f, kind) in enumerate(layers):
+        n = out_f * in_f
+        dy = si.output_grads_fp16(tokens, out_f, 40 + j)
+        x = si.activations_fp16(tokens, in_f, 40 + j)
+        d_dy = dev_f16_bits(dy).view(tokens, out_f)
+        d_x = dev_f16_bits(x).view(tokens, in_f)
+        if kind == "none":
+            idx = np.zeros(0, dtype=np.int32)
+        elif kind == "dense":
+            idx = np.arange(n, dtype=np.int32)
+        else:
+            idx = oracle.build_index(_mask(kind, out_f, in_f, 40 + j))
+        nnz = idx.shape[0]
+        d_idx = None if kind == "dense" else dev_i32(idx)
+        d_seg = None if kind == "dense" else dev_i32(ref_seg_ptr(idx, n))
+        gc16 = torch.full((nnz + 8,), float("nan"), dtype=torch.float16, device=DEV)
+        gc = torch.full((nnz + 8,), float("nan"), dtype=torch.float32, device=DEV)
+        jobs16.append((d_dy, d_x, d_idx, d_seg, gc16[:nnz]))
+        jobs32.append((d_dy, d_x, d_idx, d_seg, gc[:nnz]))
+        checks.append((dy, x, tokens, out_f, in_f, idx, gc16, gc))
+    samo.samo_wgrad_gather_fp16_batched(jobs16)
+    samo.samo_wgrad_gather_batched(jobs32, float(inv))
+    torch.cuda.synchronize()
+    for dy, x, tokens, out_f, in_f, idx, gc16, gc in checks:
+        nnz = idx.shape[0]
+        assert torch.isnan(gc16[nnz:]).all() and torch.isnan(gc[nnz:]).all(), "wrote past a layer's compressed gradient"
+        if nnz == 0:
+            continue
+        lo, hi = _bracket(dy, x, tokens, out_f, in_f, idx)
+        got = host_bits(gc16[:nnz])
+        _check_f16(got, lo, hi, oracle.wgrad_compress(dy, x, tokens, out_f, in_f, idx), "batched gc16 %dx%d" % (out_f, in_f))
+        assert np.array_equal(gc[:nnz].cpu().numpy().view(np.uint32), (got.view(np.float16).astype(np.float32) * inv).view(np.uint32))
+    # second micro-batch: accumulate into the same buffers, all layers at once
+    before = [host_bits(c[6][:c[5].shape[0]]).view(np.float16).copy() for c in checks]
+    samo.samo_wgrad_gather_fp16_batched(jobs16, accumulate=True)
+    torch.cuda.synchronize()
+    for c, h in zip(checks, before):
+        nnz = c[5].shape[0]
+        if nnz:
+            assert np.array_equal(host_bits(c[6][:nnz]), (h + h).astype(np.float16).view(np.uint16)), "accumulate: twice the first result"
+    samo.samo_wgrad_gather_batched([], 1.0)                  # no jobs: nothing to do
+    with pytest.raises(RuntimeError):
+        samo.samo_wgrad_gather_batched(jobs32 + jobs32, 1.0)  # ten jobs
+
+
 def test_rejections():
     dy = torch.zeros((4, 8), dtype=torch.float16, device=DEV)
     x = torch.zeros((4, 12), dtype=torch.float16, device=DEV)
