@@ -252,7 +252,8 @@ def main():
             mfma_entry("library GEMM + samo_gather_grads, %d tokens" % long_tokens, time_entry(library_path))
             del dy, xa
             flops = 2.0 * tokens * out_f * in_f
-            # the same two routes over the pruned matrices of the first transformer layer, launched back to back
+            # the same two routes over the pruned matrices of the first transformer layer, launched back to
+            # back, and the fused route as one batched call
             block = cand[:4]
             ops = []
             for j in block:
@@ -273,6 +274,9 @@ def main():
             mfma_entries["block"] = "%s: %d matrices, %.1f M elements, %d tokens" % (
                 ", ".join(specs[j].name for j in block), len(block), sum(Lj.n for Lj, _, _ in ops) / 1e6, tokens)
             mfma_entry("samo_wgrad_gather over the block", time_entry(fused_block))
+            jobs = [(dyj, xj, Lj.idx, Lj.seg_ptr, Lj.gc) for Lj, dyj, xj in ops]
+            mfma_entry("samo_wgrad_gather_batched over the block", time_entry(lambda: samo.samo_wgrad_gather_batched(jobs, inv)))
+            del jobs
             mfma_entry("library GEMM + samo_gather_grads over the block", time_entry(library_block))
             del ops
 

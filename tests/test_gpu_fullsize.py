@@ -396,3 +396,50 @@ def test_gpt2p7b_weight_gradient_compressed_in_the_backward_kernel(layer, tokens
     slack = (tokens + 2) * 2.0 ** -23 * norm_dy[idx // in_f] * norm_x[idx % in_f]
     ulp = np.maximum(np.abs(b), 2.0 ** -14) * 2.0 ** -10
     assert np.all(np.abs(a.astype(np.float64) - b) <= ulp + 2 * slack), "further from the library GEMM's result than two roundings allow"
+
+
+def test_gpt2p7b_layer_weight_gradients_in_one_batched_call():
+    """The four pruned matrices of one transformer layer of the 2.7B model (QKV, projection, FC1, FC2:
+    1200 tiles of 256 x 256 as one list) in one samo_wgrad_gather_fp16_batched call at 2048 tokens,
+    the configuration bench.py times: sampled outputs of every matrix against the oracle, and every
+    output against the one-call-per-matrix result (the same products; a tile may be summed by the
+    other kernel, so in another order)."""
+    tokens = 2048
+    specs = si.config("gpt2.7b", 0.9, layers=1)
+    jobs, single, keep = [], [], []
+    for spec in specs:
+        out_f, in_f = spec.rows, spec.cols
+        data = si.make_layer(spec)
+        idx = oracle.build_index(data.mask)
+        dy = si.output_grads_fp16(tokens, out_f, spec.seed)
+        x = si.activations_fp16(tokens, in_f, spec.seed)
+        d_dy = torch.from_numpy(dy.view(np.int16)).to(DEV).view(torch.float16).view(tokens, out_f)
+        d_x = torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.float16).view(tokens, in_f)
+        ix = samo.samo_build_index(torch.from_numpy(data.mask).to(DEV))
+        assert ix.nnz == idx.shape[0]
+        gc16 = torch.full((ix.nnz,), float("nan"), dtype=torch.float16, device=DEV)
+        one = torch.full((ix.nnz,), float("nan"), dtype=torch.float16, device=DEV)
+        jobs.append((d_dy, d_x, ix.idx, ix.seg_ptr, gc16))
+        single.append(one)
+        keep.append((spec, idx, dy, x, ix))
+    samo.samo_wgrad_gather_fp16_batched(jobs)
+    for (d_dy, d_x, idx_d, seg_d, _), one in zip(jobs, single):
+        samo.samo_wgrad_gather_fp16(d_dy, d_x, idx_d, seg_d, one)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(21)
+    for (spec, idx, dy, x, _), (_, _, _, _, gc16), one in zip(keep, jobs, single):
+        out_f, in_f, nnz = spec.rows, spec.cols, idx.shape[0]
+        got = host_bits(gc16).view(np.float16)
+        ks = np.unique(np.concatenate([[0, nnz - 1], rng.integers(0, nnz, 1500)]))
+        exact, mag = oracle.wgrad_at(dy, x, tokens, out_f, in_f, idx[ks])
+        slack = (tokens + 2) * 2.0 ** -23 * mag
+        lo, hi = (exact - slack).astype(np.float16), (exact + slack).astype(np.float16)
+        assert np.all((got[ks] >= lo) & (got[ks] <= hi)), spec.name + ": sampled outputs outside the rounding bracket of the exact sums"
+        a, b = got.astype(np.float32), host_bits(one).view(np.float16).astype(np.float32)
+        assert (a == b).mean() > 0.995, spec.name
+        norm_dy = np.sqrt((dy.reshape(tokens, out_f).astype(np.float64) ** 2).sum(axis=0))
+        norm_x = np.sqrt((x.reshape(tokens, in_f).astype(np.float64) ** 2).sum(axis=0))
+        bound = (tokens + 2) * 2.0 ** -23 * norm_dy[idx // in_f] * norm_x[idx % in_f]
+        ulp = np.maximum(np.abs(b), 2.0 ** -14) * 2.0 ** -10
+        assert np.all(np.abs(a.astype(np.float64) - b) <= ulp + 2 * bound), spec.name + ": batched and single results further apart than two roundings allow"
+
