@@ -331,7 +331,7 @@ samo_status samo_wgrad_gather_fp16(const uint16_t *d_dy, const uint16_t *d_x, in
 /* The same for several layers in one call: the tiles of all the jobs' layers are dealt to the
  * compute units as one list, so that a layer whose own tiles would end in a partly filled round
  * shares that round with the next layer (the four matrices of a GPT-3 2.7B transformer layer at
- * 2048 tokens: 0.37 ms in one call against 0.45 ms in four).  The caller holds dY and X of all
+ * 2048 tokens: 0.35 ms in one call against 0.42 ms in four).  The caller holds dY and X of all
  * the jobs' layers until the call — it trades that memory for the time.  Each job is one layer
  * with the arguments of samo_wgrad_gather / samo_wgrad_gather_fp16 (d_gc: fp32 for
  * samo_wgrad_gather_batched, fp16 for samo_wgrad_gather_fp16_batched; tokens may differ between
