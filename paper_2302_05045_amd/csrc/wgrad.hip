@@ -216,7 +216,10 @@ __device__ __forceinline__ int bound_settle(const WgradArgs &A, Bound b, const W
 
 // The main loop both kernels share.  At the top of stage s the copies of stages s+1 and s+2 may
 // still be outstanding (8 per wave), those of stage s may not; the barrier also tells every wave
-// that the slot of stage s-1 has been read and may take stage s+3.
+// that the slot of stage s-1 has been read and may take stage s+3.  The 8 loads of bound_window
+// sit between the copies of stages 2 and 3 in the same counter: they are older than every stage
+// whose wait could mistake them for its own copies, so they can only make the waits of stages 0
+// to 2 longer than needed, never shorter.
 template <typename Issue, typename Multiply>
 __device__ __forceinline__ void run_stages(int64_t stages, unsigned char *lds, Issue issue_stage, Multiply multiply_stage)
 {
@@ -235,8 +238,9 @@ __device__ __forceinline__ void run_stages(int64_t stages, unsigned char *lds, I
 }
 
 // Epilogue over the ROWS rows of a tile held as an fp16 image in LDS: each of the 16 half-waves
-// takes every 16th row, all of them at once; per row, idx between the row's two bounds is read coalesced, the values are picked
-// from the image and the compressed gradient is written coalesced.
+// takes every 16th row, all of them at once; per row, idx between the row's two bounds is read
+// coalesced, the values are picked from the image and the compressed gradient is written
+// coalesced.
 template <int OUT, int ROWS>
 __device__ __forceinline__ void gather_pass(const WgradArgs &A, const _Float16 *img, int pitch, const int *first, const int *last,
                                             int first_row, int col0)
