@@ -379,6 +379,22 @@ def wgrad_at(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_f
     return val, mag
 
 
+def wgrad_rows(dy: np.ndarray, x: np.ndarray, tokens: int, out_features: int, in_features: int,
+               rows: np.ndarray) -> tuple:
+    """linear_weight_grad and its magnitude sum for whole rows of dW (the output features in
+    `rows`): returns two fp64 arrays of len(rows) x in_features, entry [r][i] =
+    sum_t dY[t][rows[r]] * X[t][i] and sum_t |dY[t][rows[r]] * X[t][i]| — the same definition as
+    linear_weight_grad, one fp64 matrix product over the chosen output features only, so that a
+    few hundred thousand outputs of a full-size layer can be checked without forming all of dW."""
+    a = _arr(dy, np.uint16).view(np.float16).reshape(tokens, out_features)
+    b = _arr(x, np.uint16).view(np.float16).reshape(tokens, in_features).astype(np.float64)
+    rows = np.asarray(rows, np.int64)
+    if rows.size and (rows.min() < 0 or rows.max() >= out_features):
+        raise ValueError("row outside the weight matrix")
+    u = a[:, rows].astype(np.float64)                       # tokens x len(rows)
+    return u.T @ b, np.abs(u).T @ np.abs(b)
+
+
 def _check_index(idx: np.ndarray, n: int) -> None:
     if idx.shape[0] == 0:
         return

@@ -109,6 +109,33 @@ def test_sampled_positions_agree_with_the_dense_product():
         oracle.wgrad_at(dy, x, tokens, out_f, in_f, [out_f * in_f])
 
 
+def test_whole_rows_agree_with_triple_loops_and_the_per_position_routine():
+    """wgrad_rows against explicit loops on small integers with out != in (every sum exact, so a
+    transposed operand or a wrong row shows as a different integer), against the per-position
+    routine on random halves, and the magnitude sum against its definition."""
+    tokens, out_f, in_f = 5, 4, 3
+    rng = np.random.default_rng(5)
+    a = rng.integers(-6, 7, (tokens, out_f))
+    b = rng.integers(-6, 7, (tokens, in_f))
+    rows = np.array([3, 0, 2])
+    val, mag = oracle.wgrad_rows(_halves(a), _halves(b), tokens, out_f, in_f, rows)
+    assert val.shape == mag.shape == (3, in_f)
+    for r, o in enumerate(rows):
+        for i in range(in_f):
+            assert val[r, i] == sum(int(a[t, o]) * int(b[t, i]) for t in range(tokens))
+            assert mag[r, i] == sum(abs(int(a[t, o]) * int(b[t, i])) for t in range(tokens))
+    tokens, out_f, in_f = 50, 17, 23
+    dy, x, _ = _problem(tokens, out_f, in_f, 11)
+    rows = np.array([16, 0, 7, 7])
+    val, mag = oracle.wgrad_rows(dy, x, tokens, out_f, in_f, rows)
+    pos = (rows[:, None] * in_f + np.arange(in_f)[None, :]).reshape(-1)
+    v1, m1 = oracle.wgrad_at(dy, x, tokens, out_f, in_f, pos)
+    assert np.allclose(val.reshape(-1), v1, rtol=1e-13, atol=1e-15) and np.allclose(mag.reshape(-1), m1, rtol=1e-13)
+    assert np.allclose(val.reshape(-1), oracle.linear_weight_grad(dy, x, tokens, out_f, in_f)[pos], rtol=1e-13, atol=1e-15)
+    with pytest.raises(ValueError):
+        oracle.wgrad_rows(dy, x, tokens, out_f, in_f, [out_f])
+
+
 def test_input_recipe_gives_gradients_of_the_usual_spread():
     tokens, out_f, in_f = 512, 32, 48
     dy, x, _ = _problem(tokens, out_f, in_f, 2)
