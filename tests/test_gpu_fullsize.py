@@ -2,6 +2,7 @@
 a model processed by ONE batched launch, compared with the CPU oracle element by element
 (the C oracle finishes a 2.7B-shape step in a few seconds, so nothing is sampled)."""
 import os
+import sys
 
 import numpy as np
 import pytest
@@ -15,21 +16,43 @@ from gpu_util import DEV, INV, OCFG, assert_close, host_bits
 pytestmark = pytest.mark.gpu
 
 
+def note(text):
+    """A progress line that reaches the terminal through pytest's capture (long tests stay visibly alive)."""
+    sys.__stdout__.write("  [%s]\n" % text)
+    sys.__stdout__.flush()
+
+
 class Model:
     """All layers of a configuration on the GPU (index built by the library) and on the host
-    (index built by the oracle)."""
+    (index built by the oracle).
 
-    def __init__(self, specs, with_gc=False, workers=12, with_gc16=False):
+    steps_ahead = k: the oracle's k optimizer steps (the same gradient every step, as in
+    oracle_step) are taken while the layers stream through the generator, and only the oracle's
+    index and final p, m, v stay on the host — 16 bytes per kept element instead of 3 more per
+    dense one — so that the largest configurations are checked whole with bounded host memory."""
+
+    def __init__(self, specs, with_gc=False, workers=12, with_gc16=False, steps_ahead=0):
         self.specs = specs
         self.host = []      # [spec, mask, idx, p, m, v, g16]
         masks = []
+        on_dev = []          # (p, g) of every layer, on the GPU, until the arena exists
 
         def consume(i, data):
             spec = data.spec
             ref_idx = oracle.build_index(data.mask)
             p_host = np.ascontiguousarray(data.w32[ref_idx])
             masks.append(None if spec.mask_kind == "dense" else torch.from_numpy(data.mask).to(DEV))
-            self.host.append([spec, data.mask, ref_idx, p_host, np.zeros_like(p_host), np.zeros_like(p_host), data.g16])
+            h = [spec, data.mask, ref_idx, p_host, np.zeros_like(p_host), np.zeros_like(p_host), data.g16]
+            if steps_ahead:
+                on_dev.append((torch.from_numpy(p_host).to(DEV),
+                               torch.from_numpy(data.g16.view(np.int16)).to(DEV).view(torch.float16)))
+                h[3] = p_host.copy()
+                for t in range(1, steps_ahead + 1):
+                    oracle.step(data.g16, spec.n, ref_idx, h[3], h[4], h[5], INV, OCFG, t)
+                h[1] = h[6] = None
+                if i % 16 == 15:
+                    note("%d of %d matrices generated, oracle %d steps ahead" % (i + 1, len(specs), steps_ahead))
+            self.host.append(h)
 
         si.generate(specs, consume, workers=workers)
         # same set-up as bench.py: batched index build, one layer-major allocation, one plan
@@ -43,8 +66,14 @@ class Model:
                 assert np.array_equal(ix.idx.cpu().numpy(), h[2]), h[0].name          # bit-exact index
                 L.idx.copy_(ix.idx)
                 L.seg_ptr.copy_(ix.seg_ptr)
-            L.p.copy_(torch.from_numpy(h[3]))
-            L.g.copy_(torch.from_numpy(h[6].view(np.int16)).view(torch.float16))
+            if steps_ahead:
+                d_p, d_g = on_dev.pop(0)
+                L.p.copy_(d_p)
+                L.g.copy_(d_g)
+                del d_p, d_g
+            else:
+                L.p.copy_(torch.from_numpy(h[3]))
+                L.g.copy_(torch.from_numpy(h[6].view(np.int16)).view(torch.float16))
             L.w.fill_(float("nan"))
             if with_gc:
                 L.gc.fill_(float("nan"))
@@ -160,33 +189,49 @@ def test_gpt2p7b_single_precision_slice():
     plan.close()
 
 
-@pytest.mark.parametrize("sparsity", [0.8, 0.95])
-def test_gpt2p7b_sparsity_sweep_slice(sparsity):
-    """Eight layers (32 matrices) of the 2.7B shape at the other sparsities of the sweep."""
-    model = Model(si.config("gpt2.7b", sparsity, layers=8))
-    n_total, nnz_total = model.plan.totals()
-    assert nnz_total == sum(si.kept_count(s.n, sparsity) for s in model.specs)
-    model.poison_w()
-    model.plan.samo_fused_step_batched(INV, samo.adam_cfg(1, **si.ADAM))
-    model.oracle_step(1)
-    model.check(1)
-
-
-def test_gpt6p7b_row_clustered_slice_with_dense_embedding():
-    """Config 5 structure: per-matrix sparsity in [0.8, 0.97], row-clustered masks, plus the dense
-    50304x4096 embedding; SAMO_TEST_6P7B_LAYERS transformer layers (default 2) of the 32."""
-    nl = int(os.environ.get("SAMO_TEST_6P7B_LAYERS", "2"))
-    specs = si.config("gpt6.7b", layers=nl)
-    assert specs[-1].mask_kind == "dense" and specs[-1].n == 50304 * 4096
-    model = Model(specs, workers=6)
+def _whole_model_two_fused_steps(specs, workers=12):
+    """Two fused steps of ONE batched launch each over every matrix of `specs`, then every element
+    of p, m, v and w against the oracle (which took its two steps while the layers were generated)."""
+    model = Model(specs, workers=workers, steps_ahead=2)
+    note("%d matrices resident, N = %d, nnz = %d" % ((len(specs),) + model.plan.totals()))
     for t in (1, 2):
         model.poison_w()
         model.plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
-        model.oracle_step(t)
-        model.check(t)
+    torch.cuda.synchronize()
+    note("two batched steps done, comparing")
+    model.check(2)
+    return model
+
+
+def test_gpt1p3b_fused_full_size():
+    """BASELINE configuration 3: 24 layers x 4 matrices, hidden 2048, 90 % magnitude-pruned."""
+    model = _whole_model_two_fused_steps(si.config("gpt1.3b", 0.9))
+    assert model.plan.totals() == (1_207_959_552, 120_795_960)
+
+
+@pytest.mark.parametrize("sparsity", [0.8, 0.95])
+def test_gpt2p7b_sparsity_sweep_full_size(sparsity):
+    """All 32 layers (128 matrices) of the 2.7B shape at the other sparsities of the sweep."""
+    model = _whole_model_two_fused_steps(si.config("gpt2.7b", sparsity))
+    n_total, nnz_total = model.plan.totals()
+    assert n_total == 2_516_582_400
+    assert nnz_total == sum(si.kept_count(s.n, sparsity) for s in model.specs) == round((1 - sparsity) * n_total)
+
+
+def test_gpt6p7b_row_clustered_full_size_with_dense_embedding():
+    """BASELINE configuration 5 whole: 32 layers x 4 matrices with 128 different per-matrix sparsities
+    in [0.8, 0.97], row-clustered masks, plus the dense 50304x4096 embedding.
+    SAMO_TEST_6P7B_LAYERS caps the number of transformer layers (default: all 32)."""
+    nl = min(32, int(os.environ.get("SAMO_TEST_6P7B_LAYERS", "32")))
+    specs = si.config("gpt6.7b", layers=nl)
+    assert specs[-1].mask_kind == "dense" and specs[-1].n == 50304 * 4096
+    if nl == 32:
+        ps = [s.sparsity for s in specs[:-1]]
+        assert len(set(ps)) == 128 and 0.8 <= min(ps) < 0.81 and 0.96 < max(ps) <= 0.97
+    model = _whole_model_two_fused_steps(specs, workers=8)
     # hot rows are ~10x denser than cold rows: tiles differ widely in their compressed slice
-    spec, mask, idx = model.host[0][0], model.host[0][1], model.host[0][2]
-    per_row = mask.reshape(spec.rows, spec.cols).sum(axis=1)
+    spec, idx = model.host[0][0], model.host[0][2]
+    per_row = np.bincount(idx // spec.cols, minlength=spec.rows)
     assert per_row.max() > 5 * np.median(per_row)
 
 
@@ -343,6 +388,41 @@ def test_index_build_statistics_and_guarded_split_step_under_hip_graph_replay():
         assert_close(L.v.cpu().numpy(), v, "v")
 
 
+def _check_rows_against_oracle(got, idx, dy, x, tokens, out_f, in_f, at_least, seed, name=""):
+    """Every kept output in a set of whole rows of dW against the oracle's rounding bracket:
+    the exact sum s and the magnitude sum S in fp64; any fp32 summation order lands within
+    (tokens + 2) * 2^-23 * S of s, and rounding to fp16 is monotonic."""
+    rng = np.random.default_rng(seed)
+    edges = [r for b in range(0, out_f + 1, 128) for r in (b - 1, b) if 0 <= r < out_f]
+    bounds = np.searchsorted(idx, np.arange(out_f + 1, dtype=np.int64) * in_f, side="left")
+    per_row = np.diff(bounds)                                            # kept outputs in every row of dW
+    chosen = np.zeros(out_f, bool)
+    chosen[[0, out_f - 1] + edges] = True
+    for r in rng.permutation(out_f):                                     # random rows until enough outputs are covered
+        if per_row[chosen].sum() >= at_least:
+            break
+        chosen[r] = True
+    rows = np.flatnonzero(chosen).astype(np.int64)
+    checked, exact_hits = 0, 0
+    for r0 in range(0, rows.shape[0], 64):                              # 64 rows per fp64 product
+        block = rows[r0:r0 + 64]
+        val, mag = oracle.wgrad_rows(dy, x, tokens, out_f, in_f, block)
+        lo_k = np.searchsorted(idx, block * in_f, side="left")
+        hi_k = np.searchsorted(idx, (block + 1) * in_f, side="left")
+        for r in range(block.shape[0]):
+            ks = np.arange(lo_k[r], hi_k[r])
+            cols = idx[ks] - block[r] * in_f
+            s_, S_ = val[r, cols], mag[r, cols]
+            slack = (tokens + 2) * 2.0 ** -23 * S_
+            g = got[ks]
+            lo, hi = (s_ - slack).astype(np.float16), (s_ + slack).astype(np.float16)
+            assert np.all((g >= lo) & (g <= hi)), "%s row %d: outputs outside the rounding bracket of the exact sums" % (name, block[r])
+            exact_hits += int((g == s_.astype(np.float16)).sum())
+            checked += ks.shape[0]
+    assert checked >= at_least, (checked, at_least)
+    assert exact_hits > 0.98 * checked
+
+
 @pytest.mark.parametrize("layer,tokens", [("fc1", 2048), ("fc1", 4096 + 24), ("qkv", 2048)])
 def test_gpt2p7b_weight_gradient_compressed_in_the_backward_kernel(layer, tokens):
     """Full-size layers of the 2.7B model, magnitude-pruned to 10 %: FC1 (dW 2560 x 10240, 400 tiles
@@ -368,16 +448,9 @@ def test_gpt2p7b_weight_gradient_compressed_in_the_backward_kernel(layer, tokens
     samo.samo_wgrad_gather(d_dy, d_x, ix.idx, ix.seg_ptr, INV, gc)
     torch.cuda.synchronize()
     got = host_bits(gc16)
-    # sampled outputs: first and last kept element, the ends of tiles, and 3000 random ones
-    rng = np.random.default_rng(12)
-    ks = np.unique(np.concatenate([[0, nnz - 1], rng.integers(0, nnz, 3000),
-                                   np.searchsorted(idx, np.arange(0, out_f * in_f, 256 * in_f // 8))[:200].clip(0, nnz - 1)]))
-    exact, mag = oracle.wgrad_at(dy, x, tokens, out_f, in_f, idx[ks])
-    slack = (tokens + 2) * 2.0 ** -23 * mag
-    lo, hi = (exact - slack).astype(np.float16), (exact + slack).astype(np.float16)
-    g = got[ks].view(np.float16)
-    assert np.all((g >= lo) & (g <= hi)), "sampled outputs outside the rounding bracket of the exact sums"
-    assert (g == exact.astype(np.float16)).mean() > 0.98
+    # the oracle on whole rows of dW: the first and last row, rows on both sides of every 128-row
+    # and 256-row tile boundary, and random ones, until at least 200 000 kept outputs are covered
+    _check_rows_against_oracle(got.view(np.float16), idx, dy, x, tokens, out_f, in_f, at_least=200_000, seed=12)
     # fp32 output = the fp16 one widened, times 1/loss scale
     assert np.array_equal(gc.cpu().numpy().view(np.uint32),
                           (got.view(np.float16).astype(np.float32) * np.float32(INV)).view(np.uint32))
@@ -430,11 +503,7 @@ def test_gpt2p7b_layer_weight_gradients_in_one_batched_call():
     for (spec, idx, dy, x, _), (_, _, _, _, gc16), one in zip(keep, jobs, single):
         out_f, in_f, nnz = spec.rows, spec.cols, idx.shape[0]
         got = host_bits(gc16).view(np.float16)
-        ks = np.unique(np.concatenate([[0, nnz - 1], rng.integers(0, nnz, 1500)]))
-        exact, mag = oracle.wgrad_at(dy, x, tokens, out_f, in_f, idx[ks])
-        slack = (tokens + 2) * 2.0 ** -23 * mag
-        lo, hi = (exact - slack).astype(np.float16), (exact + slack).astype(np.float16)
-        assert np.all((got[ks] >= lo) & (got[ks] <= hi)), spec.name + ": sampled outputs outside the rounding bracket of the exact sums"
+        _check_rows_against_oracle(got, idx, dy, x, tokens, out_f, in_f, at_least=200_000, seed=21, name=spec.name)
         a, b = got.astype(np.float32), host_bits(one).view(np.float16).astype(np.float32)
         assert (a == b).mean() > 0.995, spec.name
         norm_dy = np.sqrt((dy.reshape(tokens, out_f).astype(np.float64) ** 2).sum(axis=0))
