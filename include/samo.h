@@ -29,12 +29,17 @@
  *
  * Conventions common to every entry point
  *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller
- *     owns every buffer.  The library allocates device memory only inside
- *     samo_plan_create (small tables, freed by samo_plan_destroy).
+ *     owns every buffer, workspaces included.  The library is stateless: it
+ *     allocates nothing, frees nothing and copies nothing between host and
+ *     device; host tables (layer descriptors, job lists) reach the device inside
+ *     kernel arguments.
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
- *     Calls only enqueue work and return; there is no hidden synchronisation
- *     (samo_plan_create, a set-up call without a stream argument, excepted).
+ *     Every call only enqueues kernels on `stream` and returns; nothing
+ *     synchronises, nothing runs on another stream, so every entry point that
+ *     takes a stream can be captured into a HIP graph (after one samo_init).
  *     Outputs (including *d_nnz) are valid once the stream reaches that point.
+ *   - No exceptions cross this boundary, nothing is printed, errno is untouched and
+ *     no environment variable is read.
  *   - Arguments are validated on the host BEFORE anything is enqueued.  On a
  *     negative status nothing was launched and no output was touched.
  *   - Sizes: 0 <= N <= 2^31 - 1 per layer (the index is 32-bit, Section III-B);
@@ -58,7 +63,7 @@
 extern "C" {
 #endif
 
-#define SAMO_ABI_VERSION 3
+#define SAMO_ABI_VERSION 4
 #define SAMO_SEG_ELEMS 1024 /* dense elements per seg_ptr entry */
 
 typedef int32_t samo_status;
@@ -67,14 +72,23 @@ enum {
     SAMO_ERR_NULL = -1,  /* a required pointer is NULL */
     SAMO_ERR_SIZE = -2,  /* N or nnz out of range, or capacity/length too small */
     SAMO_ERR_ARG = -3,   /* invalid hyper-parameter or scale */
-    SAMO_ERR_ALIGN = -4, /* pointer not 16-byte aligned */
-    SAMO_ERR_HIP = -5,   /* HIP runtime reported an error on launch/alloc */
-    SAMO_ERR_PLAN = -6   /* plan lacks a buffer this entry point needs */
+    SAMO_ERR_WORKSPACE = -4, /* workspace NULL or smaller than the *_workspace_bytes call reports */
+    SAMO_ERR_ALIGN = -5, /* pointer not 16-byte aligned */
+    SAMO_ERR_INDEX = -6, /* never returned by a call (the index is checked on the device only): the
+                            value a caller reports when *d_nnz reads -1 after an index build, or
+                            *d_ok reads 0 after samo_validate_index */
+    SAMO_ERR_HIP = -7,   /* HIP runtime reported an error on launch */
+    SAMO_ERR_PLAN = -8   /* plan lacks a buffer this entry point needs */
 };
 
 /* Static string for a status code (never NULL). */
 const char *samo_status_string(samo_status s);
 int32_t samo_abi_version(void);
+/* Optional set-up for the CURRENT device, outside stream capture: sets the HIP function
+ * attributes the weight-gradient kernels need.  Entry points do the same on their first call on a
+ * device, which must then not be a captured one; after samo_init every call is pure kernel
+ * launches.  Idempotent. */
+samo_status samo_init(void);
 /* ceil(n / SAMO_SEG_ELEMS) + 1, the required length of seg_ptr; -1 if n is out of range. */
 int64_t samo_seg_ptr_len(int64_t n);
 
@@ -121,6 +135,12 @@ typedef struct {
  * The pruning algorithm's output is taken as a byte mask over the flattened
  * layer: mask[j] != 0 means element j is unpruned.
  *
+ * The construction needs one device workspace per layer, and that workspace is
+ * seg_ptr itself: samo_index_workspace_bytes reports 4 * samo_seg_ptr_len(n).
+ * Unlike an ordinary workspace its contents are an output (the table above) that
+ * the expansion and step entries read later, so the entries name it d_seg_ptr
+ * and give it its element type.
+ *
  * samo_count_nonzero: fills d_seg_ptr[0 .. samo_seg_ptr_len(n)) and *d_nnz.
  * samo_build_index:   the same, and writes the ascending positions to d_idx.
  *   If nnz > idx_capacity only the first idx_capacity positions are stored;
@@ -133,6 +153,7 @@ typedef struct {
  * *d_nnz is set to -1 and d_seg_ptr / d_idx are incomplete.  While the call is in
  * flight d_seg_ptr and *d_nnz hold intermediate values; the outputs of different
  * jobs of one call must not overlap. */
+samo_status samo_index_workspace_bytes(int64_t n, size_t *bytes);
 samo_status samo_count_nonzero(const uint8_t *d_mask, int64_t n, int32_t *d_seg_ptr,
                                int64_t *d_nnz, void *stream);
 samo_status samo_build_index(const uint8_t *d_mask, int64_t n, int32_t *d_idx,
@@ -225,18 +246,35 @@ samo_status samo_fused_step_fp32(const float *d_g32, float *d_w32, int64_t n, co
 
 /* ---------------------------------------------------------------- whole-model (batched) forms
  * One launch covers every layer, so small layers do not pay a launch and a
- * tail each.  A plan is built once per pruning from a HOST array of layer
- * descriptors holding DEVICE pointers; it copies the descriptors to the device
- * and builds its workgroup-to-work maps there.  The maps split every pruned
- * layer into runs of segments that move about equal numbers of bytes, which
- * they read off seg_ptr: the index of every layer (seg_ptr's contents) must be
- * final when the plan is created, and a plan is rebuilt after re-pruning.
- * samo_plan_create synchronises the device (before reading seg_ptr and before it
- * returns); it is the only entry point that does.  The plan does not own the
- * layers' buffers, which must stay valid while the plan is used.  A descriptor with
- * idx == NULL (then seg_ptr == NULL and nnz == n) is a dense layer.  Buffers an
- * entry point does not use may be NULL in the descriptor (e.g. gc for the
- * fused step); an entry point that needs a missing one returns SAMO_ERR_PLAN. */
+ * tail each.  A plan describes the model to those launches: the layer
+ * descriptors and the workgroup-to-work maps, all of them in a device workspace
+ * the CALLER provides.  The maps split every pruned layer into runs of segments
+ * that move about equal numbers of bytes, which they read off seg_ptr.
+ *
+ * samo_plan_workspace_bytes: the workspace size for these layers (host
+ *   arithmetic on n, nnz and on whether seg_ptr is NULL; nothing is dereferenced).
+ * samo_plan_init: validates h_layers (a HOST array of descriptors holding
+ *   DEVICE pointers), then enqueues on `stream` the kernels that write the
+ *   tables into d_workspace (the descriptors travel in kernel arguments, a few
+ *   launches of up to 24 layers each) and fills *plan, a small host struct the
+ *   caller owns.  Nothing is allocated, copied or synchronised; nothing has to be
+ *   destroyed.  The kernels read every layer's seg_ptr in stream order, so an
+ *   index build enqueued on the same stream just before is seen complete, and
+ *   the whole sequence build index -> init plan -> step can sit in one HIP graph.
+ *   *plan is usable by later calls on the same stream as soon as this returns
+ *   (by calls on other streams once they wait for this one); it stays valid while
+ *   the workspace and the layers' buffers are, until the index changes.
+ * nnz of a descriptor is the CAPACITY of the layer's compressed arrays, and the
+ *   launch sizes follow from it.  The number of kept elements the kernels use is
+ *   what the layer's seg_ptr holds in its last entry when samo_plan_init's
+ *   kernels run: the same number, unless the index was rebuilt with fewer kept
+ *   elements (a captured graph replayed after re-pruning), which is valid.  An
+ *   index with more kept elements than the capacity is cut off there.
+ * A descriptor with idx == NULL (then seg_ptr == NULL and nnz == n) is a dense
+ * layer.  Buffers an entry point does not use may be NULL in the descriptor
+ * (e.g. gc for the fused step); an entry point that needs a missing one returns
+ * SAMO_ERR_PLAN.  After re-pruning: rebuild the index, call samo_plan_init again
+ * (the same workspace can be reused once earlier work on it has finished). */
 typedef struct {
     int64_t n, nnz;
     const int32_t *idx;
@@ -250,15 +288,24 @@ typedef struct {
     const float *g32;  /* single-precision SAMO: dense fp32 gradient */
 } samo_layer;
 
-typedef struct samo_plan samo_plan;
+/* Filled by samo_plan_init; read-only for the caller.  Plain data: copy it freely, no call frees it. */
+typedef struct {
+    const void *d_layers;   /* device: samo_layer[num_layers], nnz as found in seg_ptr */
+    const void *d_tiles;    /* device: one record per workgroup of the tile kernels */
+    const void *d_chunks;   /* device: one record per workgroup of the flat kernels */
+    int64_t num_tiles, num_chunks;
+    int64_t n_total, nnz_total;   /* sums over the descriptors as given */
+    int32_t num_layers;
+    uint32_t buffers;       /* bit set: which arrays every layer of the plan provides */
+} samo_plan;
 
-samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, samo_plan **out);
-samo_status samo_plan_destroy(samo_plan *plan); /* NULL is accepted */
-/* Sum over layers, as given at creation. */
-samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *nnz_total);
+samo_status samo_plan_workspace_bytes(const samo_layer *h_layers, int32_t num_layers, size_t *bytes);
+samo_status samo_plan_init(const samo_layer *h_layers, int32_t num_layers, void *d_workspace,
+                           size_t workspace_bytes, void *stream, samo_plan *plan);
 
 /* Gradient statistics need one (sum, flag) partial per workgroup: *bytes is the size of the
- * device workspace the entry points with a d_stats argument require for this plan. */
+ * device workspace the entry points with a d_stats argument require for this plan
+ * (SAMO_ERR_WORKSPACE if it is missing or smaller). */
 samo_status samo_plan_stats_workspace_bytes(const samo_plan *plan, size_t *bytes);
 
 samo_status samo_decompress_batched(const samo_plan *plan, void *stream);
@@ -317,8 +364,9 @@ samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_facto
  * describe the layer of n = out * in elements as everywhere else; d_idx may be
  * NULL only when nnz == out * in (unpruned layer), d_seg_ptr is required
  * whenever d_idx is given.  Nothing is written when nnz == 0.
- * The first call in a process configures the kernel's LDS size (a HIP function
- * attribute): make it outside stream capture; later calls only enqueue. */
+ * The first call on a device configures the kernels' LDS size (a HIP function
+ * attribute): call samo_init, or make that first call, outside stream capture;
+ * later calls only enqueue. */
 samo_status samo_wgrad_gather(const uint16_t *d_dy, const uint16_t *d_x, int64_t tokens,
                               int64_t out, int64_t in, const int32_t *d_idx,
                               const int32_t *d_seg_ptr, int64_t nnz, float inv_loss_scale,
@@ -367,21 +415,37 @@ samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper
  * rate and calibrates hardware byte counters.  Not part of the method. */
 samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void *stream);
 
-/* ---------------------------------------------------------------- environment (tuning and testing aids)
- * Read by the library, never required:
- *   SAMO_OCC_TILE_STEP, SAMO_OCC_TILE_STEP32, SAMO_OCC_TILE_DECOMP, SAMO_OCC_FLAT_GATHER,
- *   SAMO_OCC_FLAT_STATS, SAMO_OCC_FLAT_STEP
- *                        workgroups (waves for the flat kernels) resident per compute unit that a
- *                        launch of that kind aims at, overriding the built-in target; 0 = no cap.
- *                        Read once per process.
- *   SAMO_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it gives
- *                        up (default 2^20); 0 makes the give-up path reachable in tests.  Read per call.
- *   SAMO_WGRAD_TILE        128 or 256: forces the tile shape of samo_wgrad_gather / _fp16 (default: 128 x 128
- *                        for layers of at most 128 tiles of 256 x 256, which would leave compute units
- *                        idle, else 256 x 256 in whole rounds of the compute units and 128 x 128 for a
- *                        remainder of at most half a round).  Read per call.
- *   SAMO_WGRAD_ROUND       test aid: the number of tiles taken as one round in that rule, in place of
- *                        the device's compute-unit count.  Read per call. */
+/* ---------------------------------------------------------------- tuning and testing aids
+ * Process-wide knobs, set from the host; the entry points read no environment variable.  A knob
+ * keeps its value until it is set again; SAMO_KNOB_DEFAULT as the value restores the built-in
+ * choice.  Not needed for normal use: the defaults are the measured optima.
+ *   SAMO_KNOB_OCC_TILE_STEP, _OCC_TILE_STEP32, _OCC_TILE_DECOMP, _OCC_TILE_C16 (workgroups) and
+ *   SAMO_KNOB_OCC_FLAT_GATHER, _OCC_FLAT_STATS, _OCC_FLAT_STEP (waves)
+ *                        resident per compute unit that a launch of that kind aims at; 0 = no cap.
+ *   SAMO_KNOB_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it
+ *                        gives up (default 2^20); 0 makes the give-up path reachable in tests.
+ *   SAMO_KNOB_WGRAD_TILE   128 or 256: forces the tile shape of the weight-gradient entries
+ *                        (default: 128 x 128 for layers of at most 128 tiles of 256 x 256, which
+ *                        would leave compute units idle, else 256 x 256 in whole rounds of the
+ *                        compute units and 128 x 128 for a remainder of at most half a round).
+ *   SAMO_KNOB_WGRAD_ROUND  test aid: the number of tiles taken as one round in that rule, in
+ *                        place of the device's compute-unit count.
+ * Returns SAMO_ERR_ARG for an unknown knob. */
+enum {
+    SAMO_KNOB_OCC_TILE_STEP = 0,
+    SAMO_KNOB_OCC_TILE_STEP32 = 1,
+    SAMO_KNOB_OCC_TILE_DECOMP = 2,
+    SAMO_KNOB_OCC_TILE_C16 = 3,
+    SAMO_KNOB_OCC_FLAT_GATHER = 4,
+    SAMO_KNOB_OCC_FLAT_STATS = 5,
+    SAMO_KNOB_OCC_FLAT_STEP = 6,
+    SAMO_KNOB_INDEX_SPIN_LIMIT = 7,
+    SAMO_KNOB_WGRAD_TILE = 8,
+    SAMO_KNOB_WGRAD_ROUND = 9,
+    SAMO_KNOB_COUNT = 10
+};
+#define SAMO_KNOB_DEFAULT (-1)
+samo_status samo_debug_set(int32_t knob, int32_t value);
 
 #ifdef __cplusplus
 }

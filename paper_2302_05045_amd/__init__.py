@@ -22,8 +22,16 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SAMO_LIBRARY_PATH") or os.path.join(_PKG, "libsamo.so")
 SEG_ELEMS = 1024
 
+ABI_VERSION = 4
+
 SAMO_OK = 0
-SAMO_ERR_NULL, SAMO_ERR_SIZE, SAMO_ERR_ARG, SAMO_ERR_ALIGN, SAMO_ERR_HIP, SAMO_ERR_PLAN = -1, -2, -3, -4, -5, -6
+(SAMO_ERR_NULL, SAMO_ERR_SIZE, SAMO_ERR_ARG, SAMO_ERR_WORKSPACE, SAMO_ERR_ALIGN, SAMO_ERR_INDEX, SAMO_ERR_HIP,
+ SAMO_ERR_PLAN) = -1, -2, -3, -4, -5, -6, -7, -8
+
+# samo_debug_set knobs
+(KNOB_OCC_TILE_STEP, KNOB_OCC_TILE_STEP32, KNOB_OCC_TILE_DECOMP, KNOB_OCC_TILE_C16, KNOB_OCC_FLAT_GATHER,
+ KNOB_OCC_FLAT_STATS, KNOB_OCC_FLAT_STEP, KNOB_INDEX_SPIN_LIMIT, KNOB_WGRAD_TILE, KNOB_WGRAD_ROUND) = range(10)
+KNOB_DEFAULT = -1
 
 
 class SamoError(RuntimeError):
@@ -46,6 +54,14 @@ class LayerDesc(ctypes.Structure):
                 ("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("w", ctypes.c_void_p), ("g", ctypes.c_void_p), ("gc", ctypes.c_void_p),
                 ("gc16", ctypes.c_void_p), ("w32", ctypes.c_void_p), ("g32", ctypes.c_void_p)]
+
+
+class PlanDesc(ctypes.Structure):
+    """samo_plan"""
+    _fields_ = [("d_layers", ctypes.c_void_p), ("d_tiles", ctypes.c_void_p), ("d_chunks", ctypes.c_void_p),
+                ("num_tiles", ctypes.c_int64), ("num_chunks", ctypes.c_int64),
+                ("n_total", ctypes.c_int64), ("nnz_total", ctypes.c_int64),
+                ("num_layers", ctypes.c_int32), ("buffers", ctypes.c_uint32)]
 
 
 class SgdCfg(ctypes.Structure):
@@ -79,7 +95,10 @@ _lib = None
 _SIGNATURES = {
     "samo_status_string": (ctypes.c_char_p, [ctypes.c_int32]),
     "samo_abi_version": (ctypes.c_int32, []),
+    "samo_init": (ctypes.c_int32, []),
+    "samo_debug_set": (ctypes.c_int32, [ctypes.c_int32, ctypes.c_int32]),
     "samo_seg_ptr_len": (ctypes.c_int64, [ctypes.c_int64]),
+    "samo_index_workspace_bytes": (ctypes.c_int32, [ctypes.c_int64, ctypes.POINTER(ctypes.c_size_t)]),
     "samo_count_nonzero": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]),
     "samo_build_index": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
@@ -112,27 +131,27 @@ _SIGNATURES = {
     "samo_fused_step_fp32": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                               ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.c_float, ctypes.POINTER(AdamCfg), ctypes.c_void_p]),
-    "samo_fused_step_fp32_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+    "samo_fused_step_fp32_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.POINTER(AdamCfg),
                                                       ctypes.POINTER(StepGuard), ctypes.c_void_p]),
-    "samo_plan_create": (ctypes.c_int32, [ctypes.POINTER(LayerDesc), ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]),
-    "samo_plan_destroy": (ctypes.c_int32, [ctypes.c_void_p]),
-    "samo_plan_totals": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
-                                          ctypes.POINTER(ctypes.c_int64)]),
-    "samo_plan_stats_workspace_bytes": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)]),
-    "samo_decompress_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p]),
-    "samo_gather_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+    "samo_plan_workspace_bytes": (ctypes.c_int32, [ctypes.POINTER(LayerDesc), ctypes.c_int32,
+                                                   ctypes.POINTER(ctypes.c_size_t)]),
+    "samo_plan_init": (ctypes.c_int32, [ctypes.POINTER(LayerDesc), ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.c_void_p, ctypes.POINTER(PlanDesc)]),
+    "samo_plan_stats_workspace_bytes": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.POINTER(ctypes.c_size_t)]),
+    "samo_decompress_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_void_p]),
+    "samo_gather_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_size_t, ctypes.c_void_p]),
-    "samo_gather_fp16_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+    "samo_gather_fp16_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
-    "samo_grad_stats_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+    "samo_grad_stats_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
                                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
-    "samo_adam_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.POINTER(AdamCfg), ctypes.POINTER(StepGuard),
+    "samo_adam_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.POINTER(AdamCfg), ctypes.POINTER(StepGuard),
                                            ctypes.c_void_p]),
-    "samo_fused_step_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+    "samo_fused_step_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.POINTER(AdamCfg),
                                                  ctypes.POINTER(StepGuard), ctypes.c_void_p]),
-    "samo_adam_expand_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(AdamCfg),
+    "samo_adam_expand_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.POINTER(AdamCfg),
                                                   ctypes.POINTER(StepGuard), ctypes.c_void_p]),
-    "samo_fused_sgd_step_batched": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_float, ctypes.POINTER(SgdCfg),
+    "samo_fused_sgd_step_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.POINTER(SgdCfg),
                                                      ctypes.POINTER(StepGuard), ctypes.c_void_p]),
     "samo_memory_model": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
@@ -162,10 +181,26 @@ def lib() -> ctypes.CDLL:
             fn = getattr(handle, name)
             fn.restype = res
             fn.argtypes = args
-        if handle.samo_abi_version() != 3:
+        if handle.samo_abi_version() != ABI_VERSION:
             raise ImportError("libsamo.so has an unexpected ABI version")
         _lib = handle
     return _lib
+
+
+def samo_init() -> None:
+    """Per-device set-up outside stream capture (function attributes)."""
+    _check(lib().samo_init(), "samo_init")
+
+
+def samo_debug_set(knob: int, value: int = KNOB_DEFAULT) -> None:
+    """Tuning / testing knob of the library (KNOB_*); KNOB_DEFAULT restores the built-in choice."""
+    _check(lib().samo_debug_set(int(knob), int(value)), "samo_debug_set")
+
+
+def samo_index_workspace_bytes(n: int) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().samo_index_workspace_bytes(int(n), ctypes.byref(out)), "samo_index_workspace_bytes")
+    return out.value
 
 
 def status_string(status: int) -> str:
@@ -234,7 +269,7 @@ def samo_build_index(mask: torch.Tensor) -> Index:
     samo_count_nonzero(mask, seg_ptr, nnz_out)
     nnz = int(nnz_out.item())
     if nnz < 0:
-        raise SamoError(SAMO_ERR_HIP, "samo_count_nonzero (the device-side scan gave up)")
+        raise SamoError(SAMO_ERR_INDEX, "samo_count_nonzero (the device-side scan gave up)")
     idx = torch.empty(nnz, dtype=torch.int32, device=mask.device)
     samo_build_index_into(mask, idx, seg_ptr, nnz_out)
     return Index(idx, seg_ptr, nnz, n)
@@ -292,7 +327,7 @@ def samo_build_index_many(masks: Sequence[torch.Tensor]) -> list:
     samo_build_index_batched(masks, [None] * len(masks), seg_ptrs, nnz_out)
     counts = nnz_out.cpu().tolist()
     if any(c < 0 for c in counts):
-        raise SamoError(SAMO_ERR_HIP, "samo_build_index_batched (the device-side scan gave up)")
+        raise SamoError(SAMO_ERR_INDEX, "samo_build_index_batched (the device-side scan gave up)")
     idxs = [torch.empty(c, dtype=torch.int32, device=dev) for c in counts]
     samo_build_index_batched(masks, idxs, seg_ptrs, nnz_out)
     return [Index(i, s, c, m.numel()) for i, s, c, m in zip(idxs, seg_ptrs, counts, masks)]
@@ -565,15 +600,15 @@ def alloc_model_fp32(shapes: Sequence[tuple], device, align: int = 256) -> list:
 
 
 class Plan:
-    """samo_plan: one launch per entry point over all layers of a model."""
+    """samo_plan: one launch per entry point over all layers of a model.  The plan's device tables
+    live in a workspace allocated here through torch (the library itself allocates nothing)."""
 
-    def __init__(self, layers: Sequence[Layer]):
-        self._handle = ctypes.c_void_p()
+    def __init__(self, layers: Sequence[Layer], workspace: Optional[torch.Tensor] = None):
         self._layers = list(layers)          # keeps the tensors alive
         self.device = next(((L.p if L.p is not None else L.m).device for L in self._layers),
                            torch.device("cuda", torch.cuda.current_device()))
-        descs = (LayerDesc * max(len(self._layers), 1))()
-        for d, L in zip(descs, self._layers):
+        self._descs = (LayerDesc * max(len(self._layers), 1))()
+        for d, L in zip(self._descs, self._layers):
             nnz = (L.p if L.p is not None else L.m).numel()      # a single-precision layer has no compressed p
             d.n, d.nnz = int(L.n), nnz
             d.idx = _dev(L.idx, torch.int32, "idx", nnz)
@@ -587,23 +622,33 @@ class Plan:
             d.gc16 = _dev(L.gc16, _F16, "gc16", nnz)
             d.w32 = _dev(L.w32, torch.float32, "w32", L.n)
             d.g32 = _dev(L.g32, torch.float32, "g32", L.n)
-        _check(lib().samo_plan_create(descs, len(self._layers), ctypes.byref(self._handle)), "samo_plan_create")
+        need = ctypes.c_size_t()
+        _check(lib().samo_plan_workspace_bytes(self._descs, len(self._layers), ctypes.byref(need)),
+               "samo_plan_workspace_bytes")
+        self.workspace_bytes = need.value
+        if workspace is None:
+            workspace = torch.empty(max(need.value, 1), dtype=torch.uint8, device=self.device)
+        self.workspace = workspace
+        self._plan = PlanDesc()
+        self.init()
+
+    def init(self) -> None:
+        """samo_plan_init on the current stream: (re)writes the plan's tables from the layers' seg_ptr as
+        they are at that point of the stream.  Call again after the index has been rebuilt."""
+        _check(lib().samo_plan_init(self._descs, len(self._layers), self.workspace.data_ptr(),
+                                    self.workspace.numel(), _stream(), ctypes.byref(self._plan)), "samo_plan_init")
+
+    @property
+    def _handle(self):
+        return ctypes.byref(self._plan)
 
     def close(self) -> None:
-        if self._handle:
-            lib().samo_plan_destroy(self._handle)
-            self._handle = ctypes.c_void_p()
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
+        """Nothing to release in the library; drops the references to the workspace and the layers."""
+        self.workspace = None
+        self._layers = []
 
     def totals(self):
-        n, nnz = ctypes.c_int64(), ctypes.c_int64()
-        _check(lib().samo_plan_totals(self._handle, ctypes.byref(n), ctypes.byref(nnz)), "samo_plan_totals")
-        return n.value, nnz.value
+        return self._plan.n_total, self._plan.nnz_total
 
     def stats_workspace_bytes(self) -> int:
         out = ctypes.c_size_t()

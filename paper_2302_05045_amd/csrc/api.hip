@@ -1,28 +1,33 @@
 // C ABI of libsamo: host-side argument validation, plan management, launches.
 // Every entry point validates on the host first and enqueues only if all
 // arguments are acceptable, so the error paths can be exercised without a GPU.
+#include <atomic>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
-#include <new>
-#include <vector>
 
 #include "common.h"
 
 using namespace samo;
 
-struct samo_plan {
-    std::vector<samo_layer> layers;   // host copy
-    samo_layer *d_layers = nullptr;
-    WgRec *d_tiles = nullptr;
-    WgRec *d_chunks = nullptr;
-    int64_t ntiles = 0, nchunks = 0;
-    int64_t n_total = 0, nnz_total = 0;
-    bool has_p = true, has_m = true, has_v = true, has_w = true, has_g = true, has_gc = true, has_gc16 = true;
-    bool has_w32 = true, has_g32 = true;
-};
+namespace samo {
+namespace {
+std::atomic<int> g_knobs[SAMO_KNOB_COUNT] = {};       // value + 1; 0 = built-in choice
+}
+int knob(int which, int dflt)
+{
+    const int v = g_knobs[which].load(std::memory_order_relaxed);
+    return v > 0 ? v - 1 : dflt;
+}
+}  // namespace samo
 
 namespace {
+
+// Which arrays every layer of a plan provides (samo_plan::buffers).
+enum : uint32_t {
+    kHasP = 1u << 0, kHasM = 1u << 1, kHasV = 1u << 2, kHasW = 1u << 3, kHasG = 1u << 4, kHasGc = 1u << 5,
+    kHasGc16 = 1u << 6, kHasW32 = 1u << 7, kHasG32 = 1u << 8, kHasAll = (1u << 9) - 1u
+};
+inline bool has(const samo_plan *plan, uint32_t bits) { return (plan->buffers & bits) == bits; }
 
 constexpr int64_t kMaxN = 2147483647LL;   // the per-layer index is 32-bit (Section III-B)
 
@@ -98,7 +103,9 @@ const char *samo_status_string(samo_status s)
     case SAMO_ERR_NULL: return "a required pointer is NULL";
     case SAMO_ERR_SIZE: return "size out of range (0 <= nnz <= n <= 2^31-1) or capacity too small";
     case SAMO_ERR_ARG: return "invalid hyper-parameter or loss scale";
+    case SAMO_ERR_WORKSPACE: return "workspace missing or too small";
     case SAMO_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case SAMO_ERR_INDEX: return "the index is not valid (build gave up, or not strictly ascending within the layer)";
     case SAMO_ERR_HIP: return "HIP runtime error";
     case SAMO_ERR_PLAN: return "plan lacks a buffer this entry point needs";
     default: return "unknown status";
@@ -106,6 +113,27 @@ const char *samo_status_string(samo_status s)
 }
 
 int32_t samo_abi_version(void) { return SAMO_ABI_VERSION; }
+
+samo_status samo_init(void)
+{
+    int cus = 0;
+    return hip_status(wgrad_configure(&cus));
+}
+
+samo_status samo_debug_set(int32_t which, int32_t value)
+{
+    if (which < 0 || which >= SAMO_KNOB_COUNT) return SAMO_ERR_ARG;
+    g_knobs[which].store(value < 0 ? 0 : value + 1, std::memory_order_relaxed);
+    return SAMO_OK;
+}
+
+samo_status samo_index_workspace_bytes(int64_t n, size_t *bytes)
+{
+    if (!bytes) return SAMO_ERR_NULL;
+    if (n < 0 || n > kMaxN) return SAMO_ERR_SIZE;
+    *bytes = (size_t)(ceil_div(n, kSeg) + 1) * sizeof(int32_t);
+    return SAMO_OK;
+}
 
 int64_t samo_seg_ptr_len(int64_t n)
 {
@@ -129,8 +157,7 @@ samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_j
         IndexBatch batch;
         std::memset(&batch, 0, sizeof(batch));
         // testing aid: a tiny limit makes the give-up path (nnz = -1) reachable from the host
-        const char *limit = std::getenv("SAMO_INDEX_SPIN_LIMIT");
-        batch.spin_limit = limit ? std::atoi(limit) : kIndexSpinLimit;
+        batch.spin_limit = knob(SAMO_KNOB_INDEX_SPIN_LIMIT, kIndexSpinLimit);
         bool fill = false;
         int64_t wgs = 0;
         int k = 0;
@@ -437,113 +464,136 @@ samo_status samo_fused_sgd_step(const uint16_t *d_g, uint16_t *d_w, int64_t n, c
 }
 
 // ------------------------------------------------------------------------------ plan
-samo_status samo_plan_create(const samo_layer *h_layers, int32_t num_layers, samo_plan **out)
+}  // extern "C"
+
+namespace {
+
+inline size_t round_up_256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+// Sizes of a plan's tables; validates the descriptors when `check` is set.
+struct PlanSizes {
+    int64_t ntiles = 0, nchunks = 0, n_total = 0, nnz_total = 0;
+    uint32_t buffers = kHasAll;
+    size_t off_tile_start = 0, off_chunk_start = 0, off_tiles = 0, off_chunks = 0, bytes = 0;
+};
+
+samo_status plan_sizes(const samo_layer *h_layers, int32_t num_layers, bool check, PlanSizes *out)
 {
-    if (!out) return SAMO_ERR_NULL;
-    *out = nullptr;
     if (num_layers < 0) return SAMO_ERR_SIZE;
     if (num_layers > 0 && !h_layers) return SAMO_ERR_NULL;
-
-    samo_plan *plan = new (std::nothrow) samo_plan;
-    if (!plan) return SAMO_ERR_HIP;
-    samo_status st = SAMO_OK;
-    for (int32_t l = 0; l < num_layers && st == SAMO_OK; ++l) {
-        const samo_layer &L = h_layers[l];
-        st = check_sizes(L.n, L.nnz);
-        if (st == SAMO_OK) st = check_index_args(L.idx, L.seg_ptr, L.n, L.nnz, /*allow_dense=*/true);
-        if (st == SAMO_OK && !L.p && !L.w32 && L.nnz > 0) st = SAMO_ERR_NULL;      // parameters in one form at least
-        if (st == SAMO_OK && (misaligned(L.p) || misaligned(L.m) || misaligned(L.v) || misaligned(L.w) ||
-                              misaligned(L.g) || misaligned(L.gc) || misaligned(L.gc16) || misaligned(L.w32) ||
-                              misaligned(L.g32)))
-            st = SAMO_ERR_ALIGN;
-        if (st != SAMO_OK) break;
-        if (L.nnz > 0) {
-            plan->has_p &= L.p != nullptr;
-            plan->has_m &= L.m != nullptr;
-            plan->has_v &= L.v != nullptr;
-            plan->has_gc &= L.gc != nullptr;
-            plan->has_gc16 &= L.gc16 != nullptr;
-        }
-        if (L.n > 0) {
-            plan->has_w &= L.w != nullptr;
-            plan->has_g &= L.g != nullptr;
-            plan->has_w32 &= L.w32 != nullptr;
-            plan->has_g32 &= L.g32 != nullptr;
-        }
-        plan->n_total += L.n;
-        plan->nnz_total += L.nnz;
-        plan->ntiles += tile_records(L);
-        plan->nchunks += ceil_div(L.nnz, kChunk);
-    }
-    if (st == SAMO_OK && (plan->ntiles > kMaxN || plan->nchunks > kMaxN)) st = SAMO_ERR_SIZE;
-    if (st != SAMO_OK) {
-        delete plan;
-        return st;
-    }
-    plan->layers.assign(h_layers, h_layers + num_layers);
-
-    std::vector<WgRec> chunks((size_t)plan->nchunks);
-    std::vector<int64_t> tile_start((size_t)num_layers + 1, 0);
-    size_t ci = 0;
+    PlanSizes z;
     for (int32_t l = 0; l < num_layers; ++l) {
-        const int64_t nc = ceil_div(h_layers[l].nnz, kChunk);
-        for (int64_t c = 0; c < nc; ++c) chunks[ci++] = WgRec{l, (uint32_t)c};
-        tile_start[(size_t)l + 1] = tile_start[(size_t)l] + tile_records(h_layers[l]);
-    }
-
-    // Everything the layers' seg_ptr tables depend on must have finished: the tile records are
-    // computed from their contents.
-    hipError_t e = plan->ntiles > 0 ? hipDeviceSynchronize() : hipSuccess;
-    auto upload = [&e](const void *src, size_t bytes, void **dst) {
-        if (e != hipSuccess || bytes == 0) return;
-        e = hipMalloc(dst, bytes);
-        if (e == hipSuccess) e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
-    };
-    upload(plan->layers.data(), plan->layers.size() * sizeof(samo_layer), reinterpret_cast<void **>(&plan->d_layers));
-    upload(chunks.data(), chunks.size() * sizeof(WgRec), reinterpret_cast<void **>(&plan->d_chunks));
-    if (e == hipSuccess && plan->ntiles > 0) {
-        int64_t *d_tile_start = nullptr;
-        upload(tile_start.data(), tile_start.size() * sizeof(int64_t), reinterpret_cast<void **>(&d_tile_start));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&plan->d_tiles), (size_t)plan->ntiles * sizeof(WgRec));
-        if (e == hipSuccess)
-            e = launch_build_tile_recs(plan->d_layers, d_tile_start, num_layers, plan->ntiles, plan->d_tiles, nullptr);
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (d_tile_start) {
-            const hipError_t e2 = hipFree(d_tile_start);
-            if (e == hipSuccess) e = e2;
+        const samo_layer &L = h_layers[l];
+        if (samo_status s = check_sizes(L.n, L.nnz)) return s;
+        if (check) {
+            if (samo_status s = check_index_args(L.idx, L.seg_ptr, L.n, L.nnz, /*allow_dense=*/true)) return s;
+            if (!L.p && !L.w32 && L.nnz > 0) return SAMO_ERR_NULL;      // parameters in one form at least
+            if (misaligned(L.p) || misaligned(L.m) || misaligned(L.v) || misaligned(L.w) || misaligned(L.g) ||
+                misaligned(L.gc) || misaligned(L.gc16) || misaligned(L.w32) || misaligned(L.g32))
+                return SAMO_ERR_ALIGN;
+            if (L.nnz > 0) {
+                if (!L.p) z.buffers &= ~kHasP;
+                if (!L.m) z.buffers &= ~kHasM;
+                if (!L.v) z.buffers &= ~kHasV;
+                if (!L.gc) z.buffers &= ~kHasGc;
+                if (!L.gc16) z.buffers &= ~kHasGc16;
+            }
+            if (L.n > 0) {
+                if (!L.w) z.buffers &= ~kHasW;
+                if (!L.g) z.buffers &= ~kHasG;
+                if (!L.w32) z.buffers &= ~kHasW32;
+                if (!L.g32) z.buffers &= ~kHasG32;
+            }
         }
+        z.n_total += L.n;
+        z.nnz_total += L.nnz;
+        z.ntiles += tile_records(L);
+        z.nchunks += ceil_div(L.nnz, kChunk);
     }
-    if (e != hipSuccess) {
-        samo_plan_destroy(plan);
-        return SAMO_ERR_HIP;
-    }
-    *out = plan;
+    if (z.ntiles > kMaxN || z.nchunks > kMaxN) return SAMO_ERR_SIZE;
+    size_t at = round_up_256((size_t)num_layers * sizeof(samo_layer));
+    z.off_tile_start = at;
+    at += round_up_256(((size_t)num_layers + 1) * sizeof(int64_t));
+    z.off_chunk_start = at;
+    at += round_up_256(((size_t)num_layers + 1) * sizeof(int64_t));
+    z.off_tiles = at;
+    at += round_up_256((size_t)z.ntiles * sizeof(WgRec));
+    z.off_chunks = at;
+    at += round_up_256((size_t)z.nchunks * sizeof(WgRec));
+    z.bytes = at;
+    *out = z;
     return SAMO_OK;
 }
 
-samo_status samo_plan_destroy(samo_plan *plan)
+}  // namespace
+
+extern "C" {
+
+samo_status samo_plan_workspace_bytes(const samo_layer *h_layers, int32_t num_layers, size_t *bytes)
 {
-    if (!plan) return SAMO_OK;
-    hipError_t e = hipSuccess;
-    if (plan->d_layers) e = hipFree(plan->d_layers);
-    if (plan->d_tiles) { hipError_t e2 = hipFree(plan->d_tiles); if (e == hipSuccess) e = e2; }
-    if (plan->d_chunks) { hipError_t e2 = hipFree(plan->d_chunks); if (e == hipSuccess) e = e2; }
-    delete plan;
-    return hip_status(e);
+    if (!bytes) return SAMO_ERR_NULL;
+    PlanSizes z;
+    if (samo_status s = plan_sizes(h_layers, num_layers, /*check=*/false, &z)) return s;
+    *bytes = z.bytes;
+    return SAMO_OK;
 }
 
-samo_status samo_plan_totals(const samo_plan *plan, int64_t *n_total, int64_t *nnz_total)
+samo_status samo_plan_init(const samo_layer *h_layers, int32_t num_layers, void *d_workspace, size_t workspace_bytes,
+                           void *stream, samo_plan *plan)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (n_total) *n_total = plan->n_total;
-    if (nnz_total) *nnz_total = plan->nnz_total;
+    PlanSizes z;
+    if (samo_status s = plan_sizes(h_layers, num_layers, /*check=*/true, &z)) return s;
+    if (!d_workspace || workspace_bytes < z.bytes) return SAMO_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return SAMO_ERR_ALIGN;
+
+    unsigned char *ws = reinterpret_cast<unsigned char *>(d_workspace);
+    PlanTables t;
+    t.layers = reinterpret_cast<samo_layer *>(ws);
+    t.tile_start = reinterpret_cast<int64_t *>(ws + z.off_tile_start);
+    t.chunk_start = reinterpret_cast<int64_t *>(ws + z.off_chunk_start);
+    t.tiles = reinterpret_cast<WgRec *>(ws + z.off_tiles);
+    t.chunks = reinterpret_cast<WgRec *>(ws + z.off_chunks);
+
+    // the layer table, kPlanBatchLayers descriptors per launch (a plan without layers still gets
+    // its two start entries)
+    int64_t tile_at = 0, chunk_at = 0;
+    int32_t l = 0;
+    do {
+        PlanBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.first = l;
+        int k = 0;
+        for (; k < kPlanBatchLayers && l < num_layers; ++k, ++l) {
+            b.layer[k] = h_layers[l];
+            b.tile_start[k] = tile_at;
+            b.chunk_start[k] = chunk_at;
+            tile_at += tile_records(h_layers[l]);
+            chunk_at += ceil_div(h_layers[l].nnz, kChunk);
+        }
+        b.count = k;
+        b.tile_start[k] = tile_at;
+        b.chunk_start[k] = chunk_at;
+        if (launch_plan_write(b, t, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
+    } while (l < num_layers);
+    if (launch_plan_records(t, num_layers, z.ntiles, z.nchunks, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
+
+    plan->d_layers = t.layers;
+    plan->d_tiles = t.tiles;
+    plan->d_chunks = t.chunks;
+    plan->num_tiles = z.ntiles;
+    plan->num_chunks = z.nchunks;
+    plan->n_total = z.n_total;
+    plan->nnz_total = z.nnz_total;
+    plan->num_layers = num_layers;
+    plan->buffers = z.buffers;
     return SAMO_OK;
 }
 
 samo_status samo_plan_stats_workspace_bytes(const samo_plan *plan, size_t *bytes)
 {
     if (!plan || !bytes) return SAMO_ERR_NULL;
-    *bytes = (size_t)stats_workspace_partials(plan->nchunks) * sizeof(StatPartial);
+    *bytes = (size_t)stats_workspace_partials(plan->num_chunks) * sizeof(StatPartial);
     return SAMO_OK;
 }
 
@@ -555,9 +605,9 @@ LaunchSet tiles_of(const samo_plan *plan)
 {
     LaunchSet ls;
     std::memset(&ls, 0, sizeof(ls));
-    ls.layers = plan->d_layers;
-    ls.recs = plan->d_tiles;
-    ls.wgs = plan->ntiles;
+    ls.layers = reinterpret_cast<const samo_layer *>(plan->d_layers);
+    ls.recs = reinterpret_cast<const WgRec *>(plan->d_tiles);
+    ls.wgs = plan->num_tiles;
     ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
     return ls;
@@ -567,9 +617,9 @@ LaunchSet chunks_of(const samo_plan *plan)
 {
     LaunchSet ls;
     std::memset(&ls, 0, sizeof(ls));
-    ls.layers = plan->d_layers;
-    ls.recs = plan->d_chunks;
-    ls.wgs = plan->nchunks;
+    ls.layers = reinterpret_cast<const samo_layer *>(plan->d_layers);
+    ls.recs = reinterpret_cast<const WgRec *>(plan->d_chunks);
+    ls.wgs = plan->num_chunks;
     ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
     return ls;
@@ -579,11 +629,11 @@ LaunchSet chunks_of(const samo_plan *plan)
 samo_status check_stats_args(const samo_plan *plan, const samo_grad_stats *d_stats, const void *ws, size_t ws_bytes)
 {
     if (!d_stats) return SAMO_OK;
-    if (!ws) return SAMO_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(d_stats) & 7u) || misaligned(ws)) return SAMO_ERR_ALIGN;
     size_t need = 0;
     samo_plan_stats_workspace_bytes(plan, &need);
-    return ws_bytes >= need ? SAMO_OK : SAMO_ERR_SIZE;
+    if (!ws || ws_bytes < need) return SAMO_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(d_stats) & 7u) || misaligned(ws)) return SAMO_ERR_ALIGN;
+    return SAMO_OK;
 }
 
 // Gather-type launch over the plan's chunks, followed by the reduction of the partials.
@@ -593,7 +643,7 @@ samo_status run_gather(const samo_plan *plan, int out, int src, float inv_scale,
     StatPartial *partials = d_stats ? reinterpret_cast<StatPartial *>(ws) : nullptr;
     if (launch_gather(out, src, chunks_of(plan), inv_scale, accumulate, partials, s) != hipSuccess)
         return SAMO_ERR_HIP;
-    if (d_stats) return hip_status(launch_stats_finalize(partials, plan->nchunks, d_stats, s));
+    if (d_stats) return hip_status(launch_stats_finalize(partials, plan->num_chunks, d_stats, s));
     return SAMO_OK;
 }
 
@@ -604,7 +654,7 @@ extern "C" {
 samo_status samo_decompress_batched(const samo_plan *plan, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_w || !plan->has_p) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasW | kHasP)) return SAMO_ERR_PLAN;
     OptK k;
     std::memset(&k, 0, sizeof(k));
     return hip_status(launch_tile(kModeDecompress, kGradDense, kOptAdam, tiles_of(plan), 1.f, k, kNoGuard,
@@ -615,7 +665,7 @@ samo_status samo_gather_batched(const samo_plan *plan, float inv_loss_scale, sam
                                 void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_g || !plan->has_gc) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasG | kHasGc)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
     return run_gather(plan, kOutF32, kGradDense, inv_loss_scale, 0, d_stats, d_workspace, as_stream(stream));
@@ -626,7 +676,7 @@ samo_status samo_gather_fp16_batched(const samo_plan *plan, int32_t accumulate, 
                                      void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_g || !plan->has_gc16) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasG | kHasGc16)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
     return run_gather(plan, kOutF16, kGradDense, inv_loss_scale, accumulate != 0, d_stats, d_workspace,
@@ -639,8 +689,8 @@ samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float
 {
     if (!plan || !d_stats) return SAMO_ERR_NULL;
     if (source < 0 || source > 3) return SAMO_ERR_ARG;
-    if ((source == kGradDense && !plan->has_g) || (source == kGradC16 && !plan->has_gc16) ||
-        (source == kGradC32 && !plan->has_gc) || (source == kGradDense32 && !plan->has_g32))
+    if ((source == kGradDense && !has(plan, kHasG)) || (source == kGradC16 && !has(plan, kHasGc16)) ||
+        (source == kGradC32 && !has(plan, kHasGc)) || (source == kGradDense32 && !has(plan, kHasG32)))
         return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
@@ -651,7 +701,7 @@ samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg,
                               void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_gc) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasP | kHasM | kHasV | kHasGc)) return SAMO_ERR_PLAN;
     OptK k;
     GuardK guard;
     if (samo_status s = make_adam_opt(h_cfg, &k)) return s;
@@ -663,7 +713,7 @@ samo_status samo_fused_step_batched(const samo_plan *plan, float inv_loss_scale,
                                     const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasP | kHasM | kHasV | kHasW | kHasG)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -677,7 +727,7 @@ samo_status samo_adam_expand_batched(const samo_plan *plan, float inv_loss_scale
                                      const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_p || !plan->has_m || !plan->has_v || !plan->has_w || !plan->has_gc16) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasP | kHasM | kHasV | kHasW | kHasGc16)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -691,7 +741,7 @@ samo_status samo_fused_sgd_step_batched(const samo_plan *plan, float inv_loss_sc
                                         const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_p || !plan->has_m || !plan->has_w || !plan->has_g) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasP | kHasM | kHasW | kHasG)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     OptK k;
     GuardK guard;
@@ -730,7 +780,7 @@ samo_status samo_fused_step_fp32_batched(const samo_plan *plan, float grad_facto
                                          const samo_step_guard *h_guard, void *stream)
 {
     if (!plan) return SAMO_ERR_NULL;
-    if (!plan->has_m || !plan->has_v || !plan->has_w32 || !plan->has_g32) return SAMO_ERR_PLAN;
+    if (!has(plan, kHasM | kHasV | kHasW32 | kHasG32)) return SAMO_ERR_PLAN;
     if (samo_status s = check_scale(grad_factor)) return s;
     OptK k;
     GuardK guard;

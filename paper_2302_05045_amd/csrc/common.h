@@ -78,6 +78,9 @@ struct StatPartial {
     int64_t nonfinite;
 };
 
+// Process-wide tuning and testing knobs (samo_debug_set); `dflt` where a knob holds SAMO_KNOB_DEFAULT.
+int knob(int which, int dflt);
+
 // Up to kIndexBatchJobs index-build jobs, passed to the kernels by value (kernel argument segment).
 constexpr int kIndexBatchJobs = 48;
 constexpr int kIndexSpinLimit = 1 << 20;   // about a second of polling
@@ -117,9 +120,25 @@ struct LaunchSet {
 };
 // Segments per tile of a single-layer launch, from the layer's average density.
 int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense);
-// Fills recs[rec_start[l] + k] for every layer l of a plan (device tables; reads the layers' seg_ptr).
-hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_rec_start, int num_layers,
-                                  int64_t total, WgRec *d_recs, hipStream_t s);
+// Up to kPlanBatchLayers layer descriptors of a plan with the starts of their tile and chunk records,
+// passed to plan_write_kernel by value: the host table reaches the device without a copy.
+constexpr int kPlanBatchLayers = 24;
+struct PlanBatch {
+    int first, count;                                 // layers [first, first + count) of the plan
+    samo_layer layer[kPlanBatchLayers];
+    int64_t tile_start[kPlanBatchLayers + 1];         // entry `count` is the start of layer first + count
+    int64_t chunk_start[kPlanBatchLayers + 1];
+};
+static_assert(sizeof(PlanBatch) <= 3072, "the layer table must fit the kernel argument segment");
+// Device tables of a plan inside the caller's workspace.
+struct PlanTables {
+    samo_layer *layers;
+    int64_t *tile_start, *chunk_start;                // num_layers + 1 entries each
+    WgRec *tiles, *chunks;
+};
+hipError_t launch_plan_write(const PlanBatch &batch, const PlanTables &t, hipStream_t s);
+// Fills the tile and chunk records of every layer (reads the tables plan_write_kernel wrote and the layers' seg_ptr).
+hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, hipStream_t s);
 hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
                        const GuardK &guard, hipStream_t s);
 hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s);
@@ -143,6 +162,8 @@ struct WgradJob {
     void *gc;
 };
 hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s);
+// Function attributes of the weight-gradient kernels and the compute-unit count of the current device (once per device).
+hipError_t wgrad_configure(int *cus);
 
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 

@@ -136,6 +136,14 @@ __device__ __forceinline__ void pick_tile(const LaunchSet &ls, samo_layer *L, in
     }
 }
 
+// seg_ptr[s] kept inside the compressed arrays: an index that holds more kept elements than the
+// arrays have room for (or a table that is no prefix sum) must not carry an access past their end.
+__device__ __forceinline__ int slice_bound(const samo_layer &L, int s)
+{
+    const int64_t c = L.seg_ptr[s];
+    return (int)(c < 0 ? 0 : (c > L.nnz ? L.nnz : c));
+}
+
 // ------------------------------------------------------------------ tile kernels
 // Dense (unpruned) layer: identity index, plain elementwise pass over the tile (one segment, so
 // one trip).  A thread takes four consecutive elements — one 16-byte vector of each fp32 array,
@@ -203,13 +211,13 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nse
     uint4 *l4 = reinterpret_cast<uint4 *>(lds_w);
     for (int o = tid; o < (len + 7) / 8; o += T) l4[o] = make_uint4(0u, 0u, 0u, 0u);
 
-    const int c0 = L.seg_ptr[s0];
-    const int c1 = L.seg_ptr[s0 + nsegs];
+    const int c0 = slice_bound(L, s0);
+    const int c1 = slice_bound(L, s0 + nsegs);
     __syncthreads();
 
     // the tile's slice of the compressed arrays; at most kMaxTile elements, so slice-relative
     // offsets fit an int even when c0 is close to 2^31
-    const int cnt = c1 - c0;
+    const int cnt = c1 > c0 ? c1 - c0 : 0;
     const int32_t *__restrict__ IDX = L.idx + c0;
     float *__restrict__ P = L.p + c0;
     float *__restrict__ M = L.m + c0;
@@ -331,11 +339,11 @@ __device__ __forceinline__ void sparse_tile_fp32(const samo_layer &L, int s0, in
     const int tid = threadIdx.x;
     float4 *l4 = reinterpret_cast<float4 *>(lds_f);
     for (int o = tid; o < (len + 3) / 4; o += T) l4[o] = make_float4(0.f, 0.f, 0.f, 0.f);
-    const int c0 = L.seg_ptr[s0];
-    const int c1 = L.seg_ptr[s0 + nsegs];
+    const int c0 = slice_bound(L, s0);
+    const int c1 = slice_bound(L, s0 + nsegs);
     __syncthreads();
 
-    const int cnt = c1 - c0;
+    const int cnt = c1 > c0 ? c1 - c0 : 0;
     const int32_t *__restrict__ IDX = L.idx + c0;
     float *__restrict__ M = L.m + c0;
     float *__restrict__ V = L.v + c0;
@@ -741,6 +749,43 @@ build_tile_recs_kernel(const samo_layer *__restrict__ layers, const int64_t *__r
     recs[t].local = (uint32_t)first | ((uint32_t)count << kRecSegShift);
 }
 
+// Chunk records of the flat kernels: record t is chunk t - rec_start[l] of the layer l that holds it.
+__global__ void __launch_bounds__(kThreads)
+build_chunk_recs_kernel(const int64_t *__restrict__ rec_start, int num_layers, int64_t total, WgRec *__restrict__ recs)
+{
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= total) return;
+    int lo = 0, hi = num_layers;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (rec_start[mid] <= t) lo = mid; else hi = mid;
+    }
+    recs[t].layer = lo;
+    recs[t].local = (uint32_t)(t - rec_start[lo]);
+}
+
+// The plan's layer table: descriptors and record starts arrive in the kernel arguments and are
+// written to the caller's workspace.  nnz of a pruned layer becomes what its index holds now — the
+// last entry of seg_ptr — capped by the capacity the host gave.
+__global__ void __launch_bounds__(64)
+plan_write_kernel(const PlanBatch batch, const PlanTables t)
+{
+    const int k = threadIdx.x;
+    if (k < batch.count) {
+        samo_layer L = batch.layer[k];
+        if (L.seg_ptr != nullptr) {
+            const int64_t nseg = (L.n + kSeg - 1) / kSeg;
+            const int64_t have = L.seg_ptr[nseg];
+            L.nnz = have < 0 ? 0 : (have < L.nnz ? have : L.nnz);
+        }
+        t.layers[batch.first + k] = L;
+    }
+    if (k <= batch.count) {
+        t.tile_start[batch.first + k] = batch.tile_start[k];
+        t.chunk_start[batch.first + k] = batch.chunk_start[k];
+    }
+}
+
 // ------------------------------------------------------------------ diagnostic copy
 // 16 bytes per thread, 4 KiB per workgroup: the fastest plain-copy shape measured on MI355X.
 __global__ void __launch_bounds__(kThreads)
@@ -752,18 +797,12 @@ copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t nvec
 
 }  // namespace
 
-static int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
 // Occupancy targets.  MI355X streams fastest with a bounded amount of traffic in flight per
 // compute unit; one workgroup too many per CU and bandwidth drops by 5-15 % (measured: the fused
 // step at 90 % sparsity reaches 6.2 TB/s with 6 workgroups per CU, 5.5 with 7).  Tile workgroups
 // all move about kTileCost bytes, so one target serves every density; it is enforced by padding
 // the LDS request: a workgroup that asks for a size between LDS/(target+1) and LDS/target fits
-// exactly `target` times.  SAMO_OCC_* environment variables override the targets (tuning aid;
-// 0 = no cap).
+// exactly `target` times.  samo_debug_set overrides the targets (tuning aid; 0 = no cap).
 constexpr int kLdsPerCu = 160 * 1024;
 static int lds_pad_for(int target_wgs, int static_bytes)
 {
@@ -774,25 +813,22 @@ static int lds_pad_for(int target_wgs, int static_bytes)
 
 static int occ_tile_step(int gsrc, int opt)
 {
-    static const int forced = env_int("SAMO_OCC_TILE_STEP", -1);
-    if (forced >= 0) return forced;
     // a step that reads the dense gradient keeps whole dense lines in flight: 6 workgroups per CU;
     // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling
-    return gsrc == kGradDense ? 6 : 0;
+    return gsrc == kGradDense ? knob(SAMO_KNOB_OCC_TILE_STEP, 6) : knob(SAMO_KNOB_OCC_TILE_C16, 0);
 }
 
 static int occ_tile_decompress()
 {
-    static const int forced = env_int("SAMO_OCC_TILE_DECOMP", -1);
-    return forced >= 0 ? forced : 0;
+    return knob(SAMO_KNOB_OCC_TILE_DECOMP, 0);
 }
 
 // Flat gather: one wave holds 1 KiB of indices and about 512 / keep bytes of dense lines in
 // flight; aim at ~75 KiB per CU.
 static int occ_flat_gather(int src, float keep, bool with_stats)
 {
-    static const int forced = env_int("SAMO_OCC_FLAT_GATHER", -1);
-    static const int forced_stats = env_int("SAMO_OCC_FLAT_STATS", -1);
+    const int forced = knob(SAMO_KNOB_OCC_FLAT_GATHER, -1);
+    const int forced_stats = knob(SAMO_KNOB_OCC_FLAT_STATS, -1);
     if (with_stats && forced_stats >= 0) return forced_stats;
     if (!with_stats && forced >= 0) return forced;
     if (src != kGradDense && src != kGradDense32) return with_stats ? 20 : 12;
@@ -807,8 +843,7 @@ static int occ_flat_gather(int src, float keep, bool with_stats)
 
 static int occ_flat_step()
 {
-    static const int forced = env_int("SAMO_OCC_FLAT_STEP", -1);
-    return forced >= 0 ? forced : 13;       // a narrow optimum: 12-15 waves per CU by size of the arrays, 16 loses 7 %
+    return knob(SAMO_KNOB_OCC_FLAT_STEP, 13);     // a narrow optimum: 12-15 waves per CU by size of the arrays, 16 loses 7 %
 }
 
 #define SAMO_LAUNCH_TILE(M, G, O)                                                                          \
@@ -843,19 +878,26 @@ int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense)
     return segs < 1 ? 1 : (segs > kMaxTileSegs ? kMaxTileSegs : segs);
 }
 
-hipError_t launch_build_tile_recs(const samo_layer *d_layers, const int64_t *d_rec_start, int num_layers,
-                                  int64_t total, WgRec *d_recs, hipStream_t s)
+hipError_t launch_plan_write(const PlanBatch &batch, const PlanTables &t, hipStream_t s)
 {
-    if (total <= 0) return hipSuccess;
-    build_tile_recs_kernel<<<dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, s>>>(d_layers, d_rec_start,
-                                                                                              num_layers, total, d_recs);
+    plan_write_kernel<<<dim3(1), dim3(64), 0, s>>>(batch, t);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, hipStream_t s)
+{
+    if (ntiles > 0)
+        build_tile_recs_kernel<<<dim3((unsigned)ceil_div(ntiles, kThreads)), dim3(kThreads), 0, s>>>(
+            t.layers, t.tile_start, num_layers, ntiles, t.tiles);
+    if (nchunks > 0)
+        build_chunk_recs_kernel<<<dim3((unsigned)ceil_div(nchunks, kThreads)), dim3(kThreads), 0, s>>>(
+            t.chunk_start, num_layers, nchunks, t.chunks);
     return hipGetLastError();
 }
 
 static int occ_tile_step_fp32()
 {
-    static const int forced = env_int("SAMO_OCC_TILE_STEP32", -1);
-    return forced >= 0 ? forced : 3;          // a tile carries twice the dense bytes of the fp16 path: half the workgroups
+    return knob(SAMO_KNOB_OCC_TILE_STEP32, 3);        // a tile carries twice the dense bytes of the fp16 path: half the workgroups
                                               // (measured at 90 %: 6.1 TB/s with 3 per CU, 5.6 with 2, 5.0 with 4)
 }
 

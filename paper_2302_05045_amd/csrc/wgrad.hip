@@ -494,6 +494,8 @@ hipError_t configure_once(int *cus)
 
 }  // namespace
 
+hipError_t wgrad_configure(int *cus) { return configure_once(cus); }
+
 hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s)
 {
     WgradBatch b;
@@ -514,10 +516,9 @@ hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv
     int cus = 0;
     if (hipError_t e = configure_once(&cus)) return e;
     const int64_t big_tiles = b.first_tile[b.jobs];
-    const char *forced = getenv("SAMO_WGRAD_TILE");           // tuning and test aid, read per call: 128 or 256
-    const int force = forced ? atoi(forced) : 0;
-    if (const char *round = getenv("SAMO_WGRAD_ROUND"))        // test aid: tiles per round in place of the CU count
-        if (atoi(round) > 0) cus = atoi(round);
+    const int force = knob(SAMO_KNOB_WGRAD_TILE, 0);           // tuning and test aid: 128 or 256
+    const int round = knob(SAMO_KNOB_WGRAD_ROUND, 0);          // test aid: tiles per round in place of the CU count
+    if (round > 0) cus = round;
     // Large tiles in whole rounds of the compute units; what is left over after the last whole
     // round goes to the small shape when that is the quicker way to finish it: up to half a round
     // of large tiles is at most two rounds of small ones, and a small round takes 0.4 of a large.

@@ -24,10 +24,10 @@ int main(void)
     samo_sgd_cfg bad_sgd = {0.1f, 1.5f, 0.0f};
     int64_t a = 0, b = 0, c = 0;
     size_t bytes = 0;
-    samo_plan *plan = NULL;
+    samo_plan plan;
 
     if (samo_abi_version() != SAMO_ABI_VERSION) { printf("abi version\n"); ++failures; }
-    for (int s = 1; s >= -8; --s) if (!samo_status_string(s) || !strlen(samo_status_string(s))) ++failures;
+    for (int s = 1; s >= -10; --s) if (!samo_status_string(s) || !strlen(samo_status_string(s))) ++failures;
     if (samo_seg_ptr_len(0) != 1 || samo_seg_ptr_len(1025) != 3 || samo_seg_ptr_len(-1) != -1) ++failures;
     EXPECT(samo_memory_model(1000, 100, &a, &b, &c), SAMO_OK);
     if (a != 20000 || b != 4400 || c != 3600) { printf("memory model\n"); ++failures; }
@@ -101,20 +101,47 @@ int main(void)
     {
         samo_layer layers[2];
         memset(layers, 0, sizeof(layers));
+        memset(&plan, 0, sizeof(plan));
         layers[0].n = 10; layers[0].nnz = 11;
-        EXPECT(samo_plan_create(layers, 1, &plan), SAMO_ERR_SIZE);
+        EXPECT(samo_plan_workspace_bytes(layers, 1, &bytes), SAMO_ERR_SIZE);
+        EXPECT(samo_plan_init(layers, 1, fake, 1u << 20, NULL, &plan), SAMO_ERR_SIZE);
         layers[0].nnz = 5; layers[0].idx = fake;                      /* seg_ptr missing */
-        EXPECT(samo_plan_create(layers, 1, &plan), SAMO_ERR_NULL);
+        EXPECT(samo_plan_init(layers, 1, fake, 1u << 20, NULL, &plan), SAMO_ERR_NULL);
         layers[0].seg_ptr = fake;                                     /* no parameters in either form */
-        EXPECT(samo_plan_create(layers, 1, &plan), SAMO_ERR_NULL);
+        EXPECT(samo_plan_init(layers, 1, fake, 1u << 20, NULL, &plan), SAMO_ERR_NULL);
         layers[0].p = (float *)odd;
-        EXPECT(samo_plan_create(layers, 1, &plan), SAMO_ERR_ALIGN);
-        EXPECT(samo_plan_create(layers, -1, &plan), SAMO_ERR_SIZE);
-        EXPECT(samo_plan_create(layers, 1, NULL), SAMO_ERR_NULL);
-        if (plan != NULL) { printf("plan must stay NULL\n"); ++failures; }
+        EXPECT(samo_plan_init(layers, 1, fake, 1u << 20, NULL, &plan), SAMO_ERR_ALIGN);
+        layers[0].p = (float *)fake;
+        EXPECT(samo_plan_workspace_bytes(layers, 1, &bytes), SAMO_OK);
+        if (bytes == 0 || bytes % 256 != 0) { printf("plan workspace size\n"); ++failures; }
+        EXPECT(samo_plan_init(layers, 1, NULL, bytes, NULL, &plan), SAMO_ERR_WORKSPACE);
+        EXPECT(samo_plan_init(layers, 1, fake, bytes - 1, NULL, &plan), SAMO_ERR_WORKSPACE);
+        EXPECT(samo_plan_init(layers, 1, odd, bytes, NULL, &plan), SAMO_ERR_ALIGN);
+        EXPECT(samo_plan_init(layers, -1, fake, bytes, NULL, &plan), SAMO_ERR_SIZE);
+        EXPECT(samo_plan_init(layers, 1, fake, bytes, NULL, NULL), SAMO_ERR_NULL);
+        EXPECT(samo_plan_workspace_bytes(layers, 1, NULL), SAMO_ERR_NULL);
+        EXPECT(samo_plan_workspace_bytes(NULL, 1, &bytes), SAMO_ERR_NULL);
+        EXPECT(samo_plan_workspace_bytes(NULL, 0, &bytes), SAMO_OK);
+        if (plan.d_layers != NULL || plan.num_layers != 0) { printf("a rejected plan must stay untouched\n"); ++failures; }
+        /* a plan that lacks what an entry needs: rejected before anything is enqueued */
+        plan.num_layers = 1; plan.num_tiles = 1; plan.num_chunks = 1; plan.n_total = 10; plan.nnz_total = 5;
+        plan.d_layers = plan.d_tiles = plan.d_chunks = fake; plan.buffers = 0;
+        EXPECT(samo_fused_step_batched(&plan, 1.0f, &adam, NULL, NULL), SAMO_ERR_PLAN);
+        EXPECT(samo_decompress_batched(&plan, NULL), SAMO_ERR_PLAN);
+        plan.buffers = ~0u;
+        EXPECT(samo_fused_step_batched(&plan, 0.0f, &adam, NULL, NULL), SAMO_ERR_ARG);
+        EXPECT(samo_grad_stats_batched(&plan, 0, 1.0f, fake, NULL, 0, NULL), SAMO_ERR_WORKSPACE);
+        EXPECT(samo_grad_stats_batched(&plan, 0, 1.0f, fake, fake, 64, NULL), SAMO_ERR_WORKSPACE);
+        EXPECT(samo_grad_stats_batched(&plan, 7, 1.0f, fake, fake, 1u << 20, NULL), SAMO_ERR_ARG);
     }
-    EXPECT(samo_plan_destroy(NULL), SAMO_OK);
-    EXPECT(samo_plan_totals(NULL, &a, &b), SAMO_ERR_NULL);
+    EXPECT(samo_index_workspace_bytes(1025, &bytes), SAMO_OK);
+    if (bytes != 12) { printf("index workspace size\n"); ++failures; }
+    EXPECT(samo_index_workspace_bytes(-1, &bytes), SAMO_ERR_SIZE);
+    EXPECT(samo_index_workspace_bytes(10, NULL), SAMO_ERR_NULL);
+    EXPECT(samo_debug_set(SAMO_KNOB_COUNT, 1), SAMO_ERR_ARG);
+    EXPECT(samo_debug_set(-1, 1), SAMO_ERR_ARG);
+    EXPECT(samo_debug_set(SAMO_KNOB_WGRAD_TILE, 128), SAMO_OK);
+    EXPECT(samo_debug_set(SAMO_KNOB_WGRAD_TILE, SAMO_KNOB_DEFAULT), SAMO_OK);
     EXPECT(samo_plan_stats_workspace_bytes(NULL, &bytes), SAMO_ERR_NULL);
     EXPECT(samo_decompress_batched(NULL, NULL), SAMO_ERR_NULL);
     EXPECT(samo_gather_batched(NULL, 1.0f, NULL, NULL, 0, NULL), SAMO_ERR_NULL);

@@ -30,9 +30,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_abi_version_and_strings():
     L = samo.lib()
-    assert L.samo_abi_version() == 3
+    assert L.samo_abi_version() == 4
     assert samo.status_string(0) == "ok"
-    for s in range(-6, 0):
+    for s in range(-8, 0):
         assert samo.status_string(s) not in ("ok", "unknown status")
     assert samo.status_string(-99) == "unknown status"
 
@@ -131,17 +131,51 @@ def test_null_cfg_and_plan():
     L = samo.lib()
     assert L.samo_adam_step(FAKE, FAKE, FAKE, FAKE, 4, None, None) == samo.SAMO_ERR_NULL
     assert L.samo_fused_step_batched(None, 1.0, ctypes.byref(_cfg()), None, None) == samo.SAMO_ERR_NULL
-    assert L.samo_plan_destroy(None) == samo.SAMO_OK
-    out = ctypes.c_void_p()
+    out = samo.PlanDesc()
+    ws, ws_bytes = FAKE, 1 << 20
     bad = (samo.LayerDesc * 1)()
     bad[0].n, bad[0].nnz = 8, 9
-    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_SIZE
+    assert L.samo_plan_init(bad, 1, ws, ws_bytes, None, ctypes.byref(out)) == samo.SAMO_ERR_SIZE
     bad[0].nnz = 4
     bad[0].idx, bad[0].seg_ptr = FAKE, FAKE
-    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_NULL      # p missing
+    assert L.samo_plan_init(bad, 1, ws, ws_bytes, None, ctypes.byref(out)) == samo.SAMO_ERR_NULL      # p missing
     bad[0].p = FAKE + 8
-    assert L.samo_plan_create(bad, 1, ctypes.byref(out)) == samo.SAMO_ERR_ALIGN
-    assert not out.value
+    assert L.samo_plan_init(bad, 1, ws, ws_bytes, None, ctypes.byref(out)) == samo.SAMO_ERR_ALIGN
+    bad[0].p = FAKE
+    assert L.samo_plan_init(bad, 1, ws, 16, None, ctypes.byref(out)) == samo.SAMO_ERR_WORKSPACE
+    assert L.samo_plan_init(bad, 1, None, ws_bytes, None, ctypes.byref(out)) == samo.SAMO_ERR_WORKSPACE
+    assert not out.d_layers and out.num_layers == 0
+
+
+def test_plan_workspace_size_follows_the_layer_sizes():
+    """Host arithmetic only: descriptors (104 bytes each), two start tables, one 8-byte record per
+    tile and per 256-element chunk, every table padded to 256 bytes."""
+    L = samo.lib()
+    need = ctypes.c_size_t()
+    d = (samo.LayerDesc * 2)()
+    d[0].n, d[0].nnz, d[0].idx, d[0].seg_ptr = 1 << 20, 100_000, FAKE, FAKE          # pruned
+    d[1].n, d[1].nnz = 5000, 5000                                                     # dense: one tile per segment
+    assert L.samo_plan_workspace_bytes(d, 2, ctypes.byref(need)) == samo.SAMO_OK
+    tiles = -(-(6144 * 1024 + 24 * 100_000) // 32768) + 5
+    chunks = -(-100_000 // 256) + -(-5000 // 256)
+    pad = lambda x: -(-x // 256) * 256
+    assert need.value == pad(2 * ctypes.sizeof(samo.LayerDesc)) + 2 * pad(3 * 8) + pad(8 * tiles) + pad(8 * chunks)
+    assert L.samo_plan_workspace_bytes(d, 0, ctypes.byref(need)) == samo.SAMO_OK and need.value == 2 * 256
+    assert samo.samo_index_workspace_bytes(1025) == 12
+
+
+def test_library_is_stateless_no_allocation_copy_or_synchronisation():
+    """The shared library imports no HIP call that allocates, frees, copies or synchronises, and reads
+    no environment variable: every entry point only launches kernels on the caller's stream."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--undefined-only", samo.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    imported = set(line.split()[-1].split("@")[0] for line in out.splitlines() if line.strip())
+    assert "hipLaunchKernel" in imported or any(s.startswith("hipLaunchKernel") or s.startswith("__hipPushCallConfiguration")
+                                                for s in imported)
+    banned = [s for s in imported if re.match(r"hip(Malloc|Free|Memcpy|Memset|DeviceSynchronize|StreamSynchronize|"
+                                              r"HostMalloc|HostFree|EventSynchronize|StreamCreate|ExtMalloc)", s)]
+    assert not banned, banned
+    assert "getenv" not in imported and "secure_getenv" not in imported
 
 
 def test_memory_model_matches_paper_formulas(golden_dir):

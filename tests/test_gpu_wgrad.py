@@ -73,16 +73,17 @@ def _problem(tokens, out_f, in_f, kind, seed):
 
 
 @pytest.fixture(params=["128", "256", "mixed"])
-def tile(request, monkeypatch):
+def tile(request):
     """Both kernels (128 x 128 tiles by two wave groups that split each stage's tokens, 256 x 256
     tiles) on every case, and the library's own rule with a round of 4 tiles, so that layers of 5,
     6 or 9 large tiles here are split between the two as a layer of 300 is on 256 compute units."""
     if request.param == "mixed":
-        monkeypatch.delenv("SAMO_WGRAD_TILE", raising=False)
-        monkeypatch.setenv("SAMO_WGRAD_ROUND", "4")
+        samo.samo_debug_set(samo.KNOB_WGRAD_ROUND, 4)
     else:
-        monkeypatch.setenv("SAMO_WGRAD_TILE", request.param)
-    return request.param
+        samo.samo_debug_set(samo.KNOB_WGRAD_TILE, int(request.param))
+    yield request.param
+    samo.samo_debug_set(samo.KNOB_WGRAD_TILE)
+    samo.samo_debug_set(samo.KNOB_WGRAD_ROUND)
 
 
 @pytest.mark.parametrize("kind", ["bernoulli10", "bernoulli50", "rows", "edges", "dense_idx"])
