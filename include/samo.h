@@ -85,9 +85,9 @@ enum {
 const char *samo_status_string(samo_status s);
 int32_t samo_abi_version(void);
 /* Optional set-up for the CURRENT device, outside stream capture: sets the HIP function
- * attributes the weight-gradient kernels need.  Entry points do the same on their first call on a
- * device, which must then not be a captured one; after samo_init every call is pure kernel
- * launches.  Idempotent. */
+ * attributes the weight-gradient kernels need and resolves the device address of the library's
+ * static scratch array.  Entry points do the same on their first call on a device, which must then
+ * not be a captured one; after samo_init every call is pure kernel launches.  Idempotent. */
 samo_status samo_init(void);
 /* ceil(n / SAMO_SEG_ELEMS) + 1, the required length of seg_ptr; -1 if n is out of range. */
 int64_t samo_seg_ptr_len(int64_t n);
@@ -324,6 +324,19 @@ samo_status samo_gather_fp16_batched(const samo_plan *plan, int32_t accumulate, 
 samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float inv_loss_scale,
                                     samo_grad_stats *d_stats, void *d_workspace, size_t workspace_bytes,
                                     void *stream);
+/* samo_grad_stats_batched for callers that cannot allocate or hand over a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the partials go to a
+ * static array in the library's own device image (samo_static_scratch_bytes() = 16 MiB, held by
+ * every GPU the library runs on until the process ends) instead of a caller workspace.  The call
+ * allocates and frees nothing.  A plan whose samo_plan_stats_workspace_bytes exceeds that size
+ * (more than about 268 M kept elements) is rejected with SAMO_ERR_SIZE before anything is enqueued.
+ * Results are bit-equal to samo_grad_stats_batched.  All calls on one GPU share the one array:
+ * calls that overlap in time on the same GPU (different streams) race and must be ordered by the
+ * caller.  The array's device address is looked up on the first call on a device (or by
+ * samo_init); make that call outside stream capture. */
+size_t samo_static_scratch_bytes(void);
+samo_status samo_grad_stats_batched_static(const samo_plan *plan, int32_t source, float inv_loss_scale,
+                                           samo_grad_stats *d_stats, void *stream);
 /* Optimizer entries; h_guard may be NULL. */
 samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg,
                               const samo_step_guard *h_guard, void *stream);

@@ -145,6 +145,9 @@ _SIGNATURES = {
                                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "samo_grad_stats_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
                                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "samo_static_scratch_bytes": (ctypes.c_size_t, []),
+    "samo_grad_stats_batched_static": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_int32, ctypes.c_float,
+                                                        ctypes.c_void_p, ctypes.c_void_p]),
     "samo_adam_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.POINTER(AdamCfg), ctypes.POINTER(StepGuard),
                                            ctypes.c_void_p]),
     "samo_fused_step_batched": (ctypes.c_int32, [ctypes.POINTER(PlanDesc), ctypes.c_float, ctypes.POINTER(AdamCfg),
@@ -188,7 +191,7 @@ def lib() -> ctypes.CDLL:
 
 
 def samo_init() -> None:
-    """Per-device set-up outside stream capture (function attributes)."""
+    """Per-device set-up outside stream capture (function attributes, static scratch address)."""
     _check(lib().samo_init(), "samo_init")
 
 
@@ -680,6 +683,11 @@ class Plan:
     def samo_grad_stats_batched(self, source: int, inv_loss_scale: float, stats: GradStats) -> None:
         _check(lib().samo_grad_stats_batched(self._handle, int(source), float(inv_loss_scale),
                                              *self._stats_args(stats), _stream()), "samo_grad_stats_batched")
+
+    def samo_grad_stats_batched_static(self, source: int, inv_loss_scale: float, stats: GradStats) -> None:
+        """The same with the partials in the library's static scratch array (no workspace, no allocation)."""
+        _check(lib().samo_grad_stats_batched_static(self._handle, int(source), float(inv_loss_scale), stats.ptr,
+                                                    _stream()), "samo_grad_stats_batched_static")
 
     def samo_adam_batched(self, cfg: AdamCfg, guard: Optional[StepGuard] = None) -> None:
         _check(lib().samo_adam_batched(self._handle, ctypes.byref(cfg), self._guard_arg(guard), _stream()),

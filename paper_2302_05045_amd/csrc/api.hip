@@ -29,6 +29,30 @@ enum : uint32_t {
 };
 inline bool has(const samo_plan *plan, uint32_t bits) { return (plan->buffers & bits) == bits; }
 
+// The static scratch array of the entry points that may not allocate: device memory that belongs
+// to the library's code object, one copy per GPU at that GPU's own address.  In host code its name
+// is only a handle for hipGetSymbolAddress; kernels get the resolved address as an argument.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device, then cached).
+hipError_t static_scratch(void **ptr)
+{
+    int device = 0;
+    if (hipError_t e = hipGetDevice(&device)) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
 constexpr int64_t kMaxN = 2147483647LL;   // the per-layer index is 32-bit (Section III-B)
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -117,7 +141,9 @@ int32_t samo_abi_version(void) { return SAMO_ABI_VERSION; }
 samo_status samo_init(void)
 {
     int cus = 0;
-    return hip_status(wgrad_configure(&cus));
+    void *p = nullptr;
+    if (wgrad_configure(&cus) != hipSuccess) return SAMO_ERR_HIP;
+    return hip_status(static_scratch(&p));
 }
 
 samo_status samo_debug_set(int32_t which, int32_t value)
@@ -695,6 +721,21 @@ samo_status samo_grad_stats_batched(const samo_plan *plan, int32_t source, float
     if (samo_status s = check_scale(inv_loss_scale)) return s;
     if (samo_status s = check_stats_args(plan, d_stats, d_workspace, workspace_bytes)) return s;
     return run_gather(plan, kOutNone, source, inv_loss_scale, 0, d_stats, d_workspace, as_stream(stream));
+}
+
+size_t samo_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+samo_status samo_grad_stats_batched_static(const samo_plan *plan, int32_t source, float inv_loss_scale,
+                                           samo_grad_stats *d_stats, void *stream)
+{
+    if (!plan || !d_stats) return SAMO_ERR_NULL;
+    size_t need = 0;
+    samo_plan_stats_workspace_bytes(plan, &need);
+    if (need > kStaticScratchBytes) return SAMO_ERR_SIZE;      // checked first: the caller can fall back to its own workspace
+    void *ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return SAMO_ERR_HIP;
+    // every partial the reduction reads is written by this call's own launches first: nothing to clear
+    return samo_grad_stats_batched(plan, source, inv_loss_scale, d_stats, ws, kStaticScratchBytes, stream);
 }
 
 samo_status samo_adam_batched(const samo_plan *plan, const samo_adam_cfg *h_cfg, const samo_step_guard *h_guard,

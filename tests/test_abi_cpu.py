@@ -162,6 +162,7 @@ def test_plan_workspace_size_follows_the_layer_sizes():
     assert need.value == pad(2 * ctypes.sizeof(samo.LayerDesc)) + 2 * pad(3 * 8) + pad(8 * tiles) + pad(8 * chunks)
     assert L.samo_plan_workspace_bytes(d, 0, ctypes.byref(need)) == samo.SAMO_OK and need.value == 2 * 256
     assert samo.samo_index_workspace_bytes(1025) == 12
+    assert L.samo_static_scratch_bytes() == 16 << 20
 
 
 def test_library_is_stateless_no_allocation_copy_or_synchronisation():
