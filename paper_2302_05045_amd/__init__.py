@@ -534,19 +534,31 @@ class GradStats:
         return StepGuard(self.ptr, float(max_grad_norm), int(bool(skip_on_nonfinite)))
 
 
+class ModelBuffers(list):
+    """The list of Layers alloc_model returns, plus `gc16_bucket`: the one contiguous fp16 buffer that
+    holds every layer's compressed gradient when it was asked for (None otherwise)."""
+    gc16_bucket: Optional[torch.Tensor] = None
+
+
 def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, with_gc16: bool = False,
-                align: int = 256) -> list:
+                align: int = 256, bucket_gc16: bool = False) -> "ModelBuffers":
     """Device buffers for a whole model in ONE allocation, layer-major.
 
     shapes: (n, nnz, dense) per layer.  Returns one Layer per entry whose tensors are views of a
     single uint8 arena in the order seg_ptr, idx, p, g, m, v, w[, gc][, gc16] for layer 0, then layer 1, ...
     Keeping a layer's arrays adjacent in the address space is worth ~4 % of the fused step's
     bandwidth on MI355X compared with grouping the arrays by kind across layers (measured on the
-    GPT-3 2.7B shape); m and v start at zero, everything else is uninitialised.  Memory plumbing
-    only: no arithmetic of the method happens here."""
+    GPT-3 2.7B shape); m and v start at zero, everything else is uninitialised.
+
+    bucket_gc16: the compressed fp16 gradients of all layers are laid out back to back in one flat
+    buffer of their own instead (each layer's slice starts on a 16-byte boundary; the padding
+    elements are zero and no kernel touches them) — the single message a data-parallel all-reduce
+    sends (Section IV-A of the paper); it is returned as `.gc16_bucket`.  Memory plumbing only: no
+    arithmetic of the method happens here."""
     def rnd(x):
         return (x + align - 1) // align * align
-    plan, total = [], 0
+    with_gc16 = with_gc16 or bucket_gc16
+    plan, total, bucket_elems = [], 0, 0
     for n, nnz, dense in shapes:
         if dense and nnz != n:
             raise ValueError("a dense layer has nnz == n")
@@ -556,21 +568,25 @@ def alloc_model(shapes: Sequence[tuple], device, with_gc: bool = False, with_gc1
                  ("v", 4 * nnz, torch.float32), ("w", 2 * n, _F16)]
         if with_gc:
             sizes.append(("gc", 4 * nnz, torch.float32))
-        if with_gc16:
+        if with_gc16 and not bucket_gc16:
             sizes.append(("gc16", 2 * nnz, _F16))
         offs = {}
         for name, nb, dt in sizes:
             offs[name] = (total, nb, dt)
             total += rnd(nb)
-        plan.append((n, dense, offs))
+        plan.append((n, nnz, dense, offs, bucket_elems))
+        bucket_elems += (nnz + 7) // 8 * 8                      # 16-byte slices
     arena = torch.empty(max(total, 1), dtype=torch.uint8, device=device)
-    layers = []
-    for n, dense, offs in plan:
+    bucket = torch.zeros(max(bucket_elems, 1), dtype=_F16, device=device) if bucket_gc16 else None
+    layers = ModelBuffers()
+    layers.gc16_bucket = bucket
+    for n, nnz, dense, offs, at in plan:
         t = {name: arena[o:o + nb].view(dt) for name, (o, nb, dt) in offs.items()}
         t["m"].zero_()
         t["v"].zero_()
+        gc16 = bucket[at:at + nnz] if bucket_gc16 else t.get("gc16")
         layers.append(Layer(n, None if dense else t["idx"], None if dense else t["seg_ptr"], t["p"], t["m"], t["v"],
-                            t["w"], t["g"], t.get("gc"), t.get("gc16")))
+                            t["w"], t["g"], t.get("gc"), gc16))
     return layers
 
 

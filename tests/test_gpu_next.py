@@ -203,6 +203,59 @@ def test_statistics_of_many_chunks(n, keep):
     assert stats.read()[1] is True
 
 
+def test_compressed_fp16_gradients_of_all_layers_in_one_flat_bucket():
+    """Section IV-A: the data-parallel all-reduce sends the compressed gradients as one message.
+    alloc_model(bucket_gc16=True) lays every layer's gc16 out back to back in ONE buffer (slices on
+    16-byte boundaries); after the batched gather (two micro-batches, the second accumulated) each
+    slice equals the oracle's compressed gradient bit for bit and the padding is untouched, and the
+    Adam + expand step that follows reads the bucket."""
+    specs = [(3 * 4096, 0.1), (1, 1.0), (5003, 0.21), (4097, 0.3), (100003, 0.05), (40000, 0.97)]
+    hosts = [_layer(n, keep, 950 + i) for i, (n, keep) in enumerate(specs)]
+    built = [samo.samo_build_index(torch.from_numpy(h.mask).to(DEV)) for h in hosts]
+    layers = samo.alloc_model([(h.n, h.idx.shape[0], False) for h in hosts], DEV, bucket_gc16=True)
+    bucket = layers.gc16_bucket
+    # one allocation, slices in layer order, each padded to a multiple of 8 halves
+    at = 0
+    for L, h in zip(layers, hosts):
+        nnz = h.idx.shape[0]
+        assert L.gc16.data_ptr() == bucket.data_ptr() + 2 * at and L.gc16.numel() == nnz
+        assert L.gc16.data_ptr() % 16 == 0
+        at += (nnz + 7) // 8 * 8
+    assert bucket.numel() == at and bucket.is_contiguous()
+    pad = torch.ones(at, dtype=torch.bool, device=DEV)
+    for L in layers:
+        pad[(L.gc16.data_ptr() - bucket.data_ptr()) // 2:][:L.gc16.numel()] = False
+    bucket.view(torch.int16)[pad] = 0x1234                           # recognisable padding
+    for L, h, ix in zip(layers, hosts, built):
+        L.idx.copy_(ix.idx)
+        L.seg_ptr.copy_(ix.seg_ptr)
+        L.p.copy_(dev_f32(h.p))
+    plan = samo.Plan(layers)
+    refs = []
+    for mb in (1, 2):
+        for i, (L, h) in enumerate(zip(layers, hosts)):
+            g = _wide_range_grads(h.n, 70 * mb + i)
+            L.g.copy_(dev_f16_bits(g))
+            if mb == 1:
+                refs.append(oracle.compress_f16(g, h.idx))
+            else:
+                oracle.accumulate_f16(g, h.idx, refs[i])
+        plan.samo_gather_fp16_batched(mb > 1, INV)
+    whole = host_bits(bucket)
+    for L, h, ref in zip(layers, hosts, refs):
+        lo = (L.gc16.data_ptr() - bucket.data_ptr()) // 2
+        assert np.array_equal(whole[lo:lo + ref.shape[0]], ref)
+    assert bool((bucket.view(torch.int16)[pad] == 0x1234).all())
+    plan.samo_adam_expand_batched(INV, samo.adam_cfg(1, **si.ADAM))
+    for L, h, ref in zip(layers, hosts, refs):
+        oracle.adam(h.p, h.m, h.v, oracle.upcast(ref, INV), OCFG, 1)
+        got_p = L.p.cpu().numpy()
+        assert_close(got_p, h.p, "p")
+        assert_close(L.m.cpu().numpy(), h.m, "m")
+        assert_close(L.v.cpu().numpy(), h.v, "v")
+        assert np.array_equal(host_bits(L.w), oracle.decompress(got_p, h.idx, h.n))
+
+
 def test_micro_batch_accumulation_batched():
     hosts, devs, plan = _model()
     refs = [None] * len(hosts)
