@@ -437,6 +437,9 @@ samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void
  *                        resident per compute unit that a launch of that kind aims at; 0 = no cap.
  *   SAMO_KNOB_INDEX_SPIN_LIMIT  polls an index-build workgroup spends on a predecessor before it
  *                        gives up (default 2^20); 0 makes the give-up path reachable in tests.
+ *   SAMO_KNOB_INDEX_PASSES  1, 2 or 4: forces the block size of the index build (64 KiB of mask per pass and
+ *                        workgroup; default: 4 for launches with at least a dozen blocks of that size per
+ *                        compute unit, else 2 or 1).
  *   SAMO_KNOB_WGRAD_TILE   128 or 256: forces the tile shape of the weight-gradient entries
  *                        (default: 128 x 128 for layers of at most 128 tiles of 256 x 256, which
  *                        would leave compute units idle, else 256 x 256 in whole rounds of the
@@ -455,7 +458,8 @@ enum {
     SAMO_KNOB_INDEX_SPIN_LIMIT = 7,
     SAMO_KNOB_WGRAD_TILE = 8,
     SAMO_KNOB_WGRAD_ROUND = 9,
-    SAMO_KNOB_COUNT = 10
+    SAMO_KNOB_INDEX_PASSES = 10,
+    SAMO_KNOB_COUNT = 11
 };
 #define SAMO_KNOB_DEFAULT (-1)
 samo_status samo_debug_set(int32_t knob, int32_t value);

@@ -37,6 +37,20 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
 std::atomic<void *> g_scratch_ptr[kMaxDevices] = {};
 
+// Number of compute units of the current device (looked up once per device; 256 if the query fails).
+int compute_units()
+{
+    static std::atomic<int> cached[kMaxDevices] = {};
+    int device = 0, n = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 256;
+    n = cached[device].load(std::memory_order_relaxed);
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
+        cached[device].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 // Device address of `scratch` on the current device (looked up once per device, then cached).
 hipError_t static_scratch(void **ptr)
 {
@@ -179,30 +193,41 @@ samo_status samo_build_index_batched(const samo_index_job *h_jobs, int32_t num_j
             (reinterpret_cast<uintptr_t>(J.nnz) & 7u))
             return SAMO_ERR_ALIGN;
     }
+    const int cus = compute_units();
     for (int32_t j0 = 0; j0 < num_jobs;) {
         IndexBatch batch;
         std::memset(&batch, 0, sizeof(batch));
         // testing aid: a tiny limit makes the give-up path (nnz = -1) reachable from the host
         batch.spin_limit = knob(SAMO_KNOB_INDEX_SPIN_LIMIT, kIndexSpinLimit);
+        // the jobs of this launch (the grid stays within 2^31 - 1 workgroups whatever the block size),
+        // then the block size the launch's volume of mask calls for
+        int k = 0;
+        int64_t bytes = 0, most = 0;
+        for (; k < kIndexBatchJobs && j0 + k < num_jobs; ++k) {
+            const int64_t w = index_job_workgroups(h_jobs[j0 + k].n, 1);
+            if (k > 0 && most + w > kMaxN) break;
+            most += w;
+            bytes += h_jobs[j0 + k].n;
+        }
+        const int forced = knob(SAMO_KNOB_INDEX_PASSES, 0);
+        batch.passes = (forced == 1 || forced == 2 || forced == 4) ? forced : index_passes_for(bytes, cus);
+        batch.num = k;
         bool fill = false;
         int64_t wgs = 0;
-        int k = 0;
-        for (; k < kIndexBatchJobs && j0 + k < num_jobs; ++k) {
-            const samo_index_job &J = h_jobs[j0 + k];
-            const int64_t w = index_job_workgroups(J.n);
-            if (k > 0 && wgs + w > kMaxN) break;                  // keep the grid within 2^31 - 1 workgroups
-            batch.wg_start[k] = (int)wgs;
-            batch.mask[k] = J.mask;
-            batch.n[k] = J.n;
-            batch.idx[k] = J.idx;
-            batch.cap[k] = J.idx_capacity;
-            batch.seg_ptr[k] = J.seg_ptr;
-            batch.nnz[k] = J.nnz;
+        for (int i = 0; i < k; ++i) {
+            const samo_index_job &J = h_jobs[j0 + i];
+            const int64_t w = index_job_workgroups(J.n, batch.passes);
+            batch.wg_start[i] = (int)wgs;
+            batch.mask[i] = J.mask;
+            batch.n[i] = J.n;
+            batch.idx[i] = J.idx;
+            batch.cap[i] = J.idx_capacity;
+            batch.seg_ptr[i] = J.seg_ptr;
+            batch.nnz[i] = J.nnz;
             fill |= J.idx_capacity > 0;
             if (w > 0) batch.ticket = J.nnz;
             wgs += w;
         }
-        batch.num = k;
         batch.wg_start[k] = (int)wgs;
         if (launch_index_batch(batch, fill, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
         j0 += k;

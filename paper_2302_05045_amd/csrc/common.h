@@ -93,6 +93,7 @@ struct IndexBatch {
     int64_t cap[kIndexBatchJobs];
     int32_t *seg_ptr[kIndexBatchJobs];
     int64_t *nnz[kIndexBatchJobs];
+    int passes;                          // 64 KiB passes a workgroup makes over its block: 1, 2 or 4
     int spin_limit;                      // polls of a missing predecessor before a workgroup gives up
     int64_t *ticket;                     // the nnz of the job that owns the last workgroup: zero before the
                                          // launch, counts the workgroups as they start, final once that one ends
@@ -103,7 +104,8 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) -----------------------
 hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s);
-int64_t index_job_workgroups(int64_t n);
+int64_t index_job_workgroups(int64_t n, int passes);
+int index_passes_for(int64_t mask_bytes, int compute_units);
 hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr,
                                    hipStream_t s);
 hipError_t launch_validate(const int32_t *idx, int64_t nnz, int64_t n, const int32_t *seg_ptr,

@@ -1,16 +1,17 @@
 // Mask -> index construction (the paper's ind_i, Section III and III-B) for gfx950.
 //
 // The pruner's output arrives as a byte mask over the flattened layer.  The mask is read ONCE.
-// A workgroup of eight wavefronts owns 64 consecutive segments of SAMO_SEG_ELEMS = 1024 mask
-// bytes; a wavefront takes eight of them, every lane loading 16 bytes of each, so a segment is
-// one coalesced 1 KiB access and eight are in flight per lane.  The kept bytes are counted per
-// lane (popcount of a 16-bit flag word) and scanned across the wave, which gives every lane its
-// offset within the segment and the segment its total; the number of kept elements in front of
-// the workgroup then comes from a chained scan across workgroups (each publishes its own count at
-// once and the running total as soon as it knows it; a successor sums the counts back to the
-// nearest running total); finally the ascending int32 positions are produced from the flag words
-// still held in registers, collected per segment in LDS and stored as contiguous runs.  All
-// integer work, bound by one read of the mask plus the write of the index.
+// A workgroup of eight wavefronts owns a block of 64, 128 or 256 consecutive segments of
+// SAMO_SEG_ELEMS = 1024 mask bytes, taken in passes of 64; in a pass a wavefront takes eight of
+// them, every lane loading 16 bytes of each, so a segment is one coalesced 1 KiB access and eight
+// are in flight per lane.  The kept bytes are counted per lane (popcount of a 16-bit flag word)
+// and scanned across the wave, which gives every lane its offset within the segment and the
+// segment its total; the number of kept elements in front of the workgroup then comes from a
+// chained scan across workgroups (each publishes its own count at once and the running total as
+// soon as it knows it; a successor sums the counts back to the nearest running total); finally
+// the ascending int32 positions are produced from the flag words still held in registers,
+// collected per segment in LDS and stored as contiguous runs.  All integer work: one read of the
+// mask plus the write of the index, about 134 vector-ALU instructions per segment and wave.
 //
 // The chain lives in seg_ptr itself: seg_ptr[e], e the end of a workgroup's block of segments, is
 // the number of kept elements up to there — exactly the running total the next workgroup needs.
@@ -96,17 +97,17 @@ __device__ __forceinline__ int find_job(const IndexBatch &batch, int wg)
     return lo;
 }
 
-// A wave takes kSegsPerWave consecutive segments, kSegsPerLoad at a time: all its 16-byte loads are
-// in flight before anything is reduced, and the per-lane counts travel through the wave scans
-// packed two to a register — a count is at most 1024, a 16-bit field is enough.
-constexpr int kSegsPerLoad = 4;
-constexpr int kRounds = 2;                // rounds of four segments a wave takes: 64 KiB of mask per workgroup
-                                          // (measured: 16 KiB blocks are twice as slow — the chain is per block;
-                                          // eight waves x 2 rounds need half the registers of four waves x 4 and
-                                          // are 2-3 % faster)
-constexpr int kSegsPerWave = kSegsPerLoad * kRounds;
-constexpr int kSegsPerWg = kSegsPerWave * kWavesPerWg;
-static_assert(kSegsPerWg <= 64, "the block's segment counts are scanned by one wave");
+// A workgroup takes its block in PASSES passes of 64 KiB: in a pass every wave loads eight
+// consecutive segments — all eight 16-byte loads of a lane in flight before anything is reduced —
+// and keeps only their flag words (two to a register) for the fill.  The per-lane counts travel
+// through the wave scans packed two to a register: a count is at most 1024, a 16-bit field is
+// enough.  What a workgroup pays once whatever its block's size — drawing the ticket, waiting for
+// its predecessors in the chain — is a dozen microseconds, against less than two for a pass, so a
+// launch with enough mask to keep the compute units busy takes four passes per workgroup (256 KiB
+// blocks), smaller ones two or one.
+constexpr int kSegsPerPass = 8;           // per wave
+constexpr int kMaxPasses = 4;
+__host__ __device__ constexpr int segs_per_wg(int passes) { return kSegsPerPass * kWavesPerWg * passes; }
 
 // States of a chain entry other than a final running total (which is >= 0).
 constexpr int kEmpty = INT32_MIN;         // nothing published yet
@@ -123,10 +124,10 @@ __device__ __forceinline__ void chain_store(int32_t *p, int v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// seg_ptr position of the chain entry of block b: the end of its segments.
-__device__ __forceinline__ int64_t chain_slot(int64_t b, int64_t nseg)
+// seg_ptr position of the chain entry of block b (blocks of `block_segs` segments): the end of its segments.
+__device__ __forceinline__ int64_t chain_slot(int64_t b, int64_t nseg, int block_segs)
 {
-    const int64_t e = (b + 1) * kSegsPerWg;
+    const int64_t e = (b + 1) * block_segs;
     return e < nseg ? e : nseg;
 }
 
@@ -143,7 +144,7 @@ index_init_kernel(const IndexBatch batch)
     if (t < batch.wg_start[batch.num]) {
         const int job = find_job(batch, t);
         const int64_t nseg = (batch.n[job] + kSeg - 1) / kSeg;
-        batch.seg_ptr[job][chain_slot(t - batch.wg_start[job], nseg)] = kEmpty;
+        batch.seg_ptr[job][chain_slot(t - batch.wg_start[job], nseg, segs_per_wg(batch.passes))] = kEmpty;
     }
 }
 
@@ -151,7 +152,8 @@ index_init_kernel(const IndexBatch batch)
 // sums the published counts of the predecessors back to the nearest running total, 64 chain
 // entries per look (more per look did not pay: measured).  Returns kPoison if a predecessor gave
 // up or never shows.
-__device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t nseg, int blk, int lane, int spin_limit)
+__device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t nseg, int block_segs, int blk, int lane,
+                                                 int spin_limit)
 {
     int prefix = 0;
     int back = blk - 1;                       // nearest predecessor not yet accounted for
@@ -159,7 +161,7 @@ __device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t
     while (back >= 0) {
         const int b = back - lane;            // lane i looks at block back - i
         int v = kEmpty;
-        if (b >= 0) v = chain_load(seg_ptr + chain_slot(b, nseg));
+        if (b >= 0) v = chain_load(seg_ptr + chain_slot(b, nseg, block_segs));
         const unsigned long long m_total = __ballot(b >= 0 && v >= 0);
         const int first_total = m_total ? __ffsll((long long)m_total) - 1 : 64;
         // the lanes in front of the first running total must all hold counts
@@ -179,9 +181,13 @@ __device__ __forceinline__ int kept_before_block(const int32_t *seg_ptr, int64_t
     return prefix;
 }
 
+template <int PASSES>
 __global__ void __launch_bounds__(kIndexThreads)
 index_kernel(const IndexBatch batch, int fill)
 {
+    constexpr int kSegsPerWave = kSegsPerPass * PASSES;
+    constexpr int kSegsPerWg = segs_per_wg(PASSES);
+    constexpr int kPerLane = kSegsPerWg / 64;     // segment counts a lane of wave 0 takes in the block's scan
     __shared__ int sh_ticket;
     __shared__ int sh_seg[kSegsPerWg];        // kept elements per segment, then in front of it within the block
     __shared__ int sh_base;                   // kept elements in front of the block, or kPoison
@@ -197,43 +203,51 @@ index_kernel(const IndexBatch batch, int fill)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t seg0 = ((int64_t)blk * kWavesPerWg + wave) * kSegsPerWave;     // segments beyond nseg read as empty
 
-    uint32_t f[kRounds][kSegsPerLoad];
-    int c01[kRounds], c23[kRounds], i01[kRounds], i23[kRounds];
+    uint32_t fp[PASSES][kSegsPerPass / 2];    // flag words of segments 2j (low half) and 2j + 1 (high half) of a pass
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
+    for (int p = 0; p < PASSES; ++p) {
+        uint32_t f[kSegsPerPass];
 #pragma unroll
-        for (int q = 0; q < kSegsPerLoad; ++q)
-            f[r][q] = lane_flags(batch.mask[job], n, (seg0 + r * kSegsPerLoad + q) * kSeg + lane * 16);
+        for (int q = 0; q < kSegsPerPass; ++q)
+            f[q] = lane_flags(batch.mask[job], n, (seg0 + p * kSegsPerPass + q) * kSeg + lane * 16);
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        c01[r] = __popc(f[r][0]) | (__popc(f[r][1]) << 16);
-        c23[r] = __popc(f[r][2]) | (__popc(f[r][3]) << 16);
-        i01[r] = wave_inclusive_scan(c01[r], lane);
-        i23[r] = wave_inclusive_scan(c23[r], lane);
-        if (lane == 63) {                      // the last lane's inclusive prefixes are the segment totals
-            int *dst = sh_seg + wave * kSegsPerWave + r * kSegsPerLoad;
-            dst[0] = i01[r] & 0xffff;
-            dst[1] = i01[r] >> 16;
-            dst[2] = i23[r] & 0xffff;
-            dst[3] = i23[r] >> 16;
+        for (int j = 0; j < kSegsPerPass / 2; ++j) {
+            const int incl = wave_inclusive_scan(__popc(f[2 * j]) | (__popc(f[2 * j + 1]) << 16), lane);
+            if (lane == 63) {                  // the last lane's inclusive prefixes are the segment totals
+                int *dst = sh_seg + wave * kSegsPerWave + p * kSegsPerPass + 2 * j;
+                dst[0] = incl & 0xffff;
+                dst[1] = incl >> 16;
+            }
+            fp[p][j] = f[2 * j] | (f[2 * j + 1] << 16);
         }
+        asm volatile("" ::: "memory");        // the next pass's loads are requested after this pass's flag words exist
     }
     __syncthreads();
 
-    const int64_t slot = chain_slot(blk, nseg);
+    const int64_t slot = chain_slot(blk, nseg, kSegsPerWg);
     const bool last_block = (blk + 1 == batch.wg_start[job + 1] - batch.wg_start[job]);
     if (wave == 0) {
-        const int c = lane < kSegsPerWg ? sh_seg[lane] : 0;
-        const int incl = wave_inclusive_scan(c, lane);
-        const int total = __shfl(incl, kSegsPerWg - 1, 64);
+        int c[kPerLane], mine = 0;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            c[i] = sh_seg[kPerLane * lane + i];
+            mine += c[i];
+        }
+        const int incl = wave_inclusive_scan(mine, lane);
+        const int total = __shfl(incl, 63, 64);
         if (blk > 0 && lane == 0) chain_store(seg_ptr + slot, encode_count(total));
-        const int before = kept_before_block(seg_ptr, nseg, blk, lane, batch.spin_limit);
+        const int before = kept_before_block(seg_ptr, nseg, kSegsPerWg, blk, lane, batch.spin_limit);
         if (lane == 0) {
             chain_store(seg_ptr + slot, before == kPoison ? kPoison : before + total);
             sh_base = before;
             if (last_block) *batch.nnz[job] = (before == kPoison) ? -1 : (int64_t)before + total;
         }
-        if (lane < kSegsPerWg) sh_seg[lane] = incl - c;
+        int run = incl - mine;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            sh_seg[kPerLane * lane + i] = run;
+            run += c[i];
+        }
     }
     __syncthreads();
     const int base = sh_base;
@@ -241,36 +255,40 @@ index_kernel(const IndexBatch batch, int fill)
 
     // seg_ptr entries strictly inside the block (its first is the predecessor's chain entry)
     const int64_t first_seg = (int64_t)blk * kSegsPerWg;
-    if (threadIdx.x >= 1 && threadIdx.x < kSegsPerWg && first_seg + threadIdx.x < slot)
-        seg_ptr[first_seg + threadIdx.x] = base + sh_seg[threadIdx.x];
+    for (int t = threadIdx.x; t < kSegsPerWg; t += kIndexThreads)
+        if (t >= 1 && first_seg + t < slot) seg_ptr[first_seg + t] = base + sh_seg[t];
 
     const int64_t cap = batch.cap[job];
     if (!fill || cap <= 0 || seg0 >= nseg) return;
     int32_t *__restrict__ idx = batch.idx[job];
     int32_t *stage = sh_stage[wave];           // this wave's own staging area: no workgroup barrier needed
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int e01 = i01[r] - c01[r], e23 = i23[r] - c23[r];     // exclusive lane prefixes, two per register
-        const int excl[kSegsPerLoad] = {e01 & 0xffff, e01 >> 16, e23 & 0xffff, e23 >> 16};
-        const int t01 = __builtin_amdgcn_readlane(i01[r], 63), t23 = __builtin_amdgcn_readlane(i23[r], 63);
-        const int tot[kSegsPerLoad] = {t01 & 0xffff, t01 >> 16, t23 & 0xffff, t23 >> 16};
+    for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
-        for (int q = 0; q < kSegsPerLoad; ++q) {
-            // the segment's positions go to LDS in order, then leave as contiguous 256-byte stores
-            const int sq = r * kSegsPerLoad + q;
-            const int first = (int)((seg0 + sq) * kSeg) + lane * 16;     // a layer's flat size fits int32
-            int at = excl[q];
-            uint32_t bits = f[r][q];
-            while (bits) {
-                const int b = __ffs(bits) - 1;
-                bits &= bits - 1;
-                stage[at++] = first + b;
+        for (int j = 0; j < kSegsPerPass / 2; ++j) {
+            const uint32_t pair[2] = {fp[p][j] & 0xffffu, fp[p][j] >> 16};
+            const int cnt = __popc(pair[0]) | (__popc(pair[1]) << 16);
+            const int incl = wave_inclusive_scan(cnt, lane);          // formed again: cheaper than keeping it
+            const int ex = incl - cnt, tt = __builtin_amdgcn_readlane(incl, 63);
+            const int excl[2] = {ex & 0xffff, ex >> 16}, tot[2] = {tt & 0xffff, tt >> 16};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                // the segment's positions go to LDS in order, then leave as contiguous 256-byte stores
+                const int sq = p * kSegsPerPass + 2 * j + h;
+                const int first = (int)((seg0 + sq) * kSeg) + lane * 16;     // a layer's flat size fits int32
+                int at = excl[h];
+                uint32_t bits = pair[h];
+                while (bits) {
+                    const int b = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    stage[at++] = first + b;
+                }
+                __builtin_amdgcn_wave_barrier();
+                const int64_t out0 = (int64_t)base + sh_seg[wave * kSegsPerWave + sq];
+                for (int o = lane; o < tot[h]; o += 64)
+                    if (out0 + o < cap) idx[out0 + o] = stage[o];
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
-            const int64_t out0 = (int64_t)base + sh_seg[wave * kSegsPerWave + sq];
-            for (int o = lane; o < tot[q]; o += 64)
-                if (out0 + o < cap) idx[out0 + o] = stage[o];
-            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -322,11 +340,26 @@ hipError_t launch_index_batch(const IndexBatch &batch, bool fill, hipStream_t s)
     const int wgs = batch.wg_start[batch.num];
     const int init_threads = wgs > batch.num ? wgs : batch.num;
     index_init_kernel<<<dim3((unsigned)ceil_div(init_threads, kThreads)), dim3(kThreads), 0, s>>>(batch);
-    if (wgs > 0) index_kernel<<<dim3((unsigned)wgs), dim3(kIndexThreads), 0, s>>>(batch, fill ? 1 : 0);
+    if (wgs > 0) {
+        const dim3 grid((unsigned)wgs), block(kIndexThreads);
+        if (batch.passes == 4) index_kernel<4><<<grid, block, 0, s>>>(batch, fill ? 1 : 0);
+        else if (batch.passes == 2) index_kernel<2><<<grid, block, 0, s>>>(batch, fill ? 1 : 0);
+        else index_kernel<1><<<grid, block, 0, s>>>(batch, fill ? 1 : 0);
+    }
     return hipGetLastError();
 }
 
-int64_t index_job_workgroups(int64_t n) { return ceil_div(ceil_div(n, kSeg), kSegsPerWg); }
+int64_t index_job_workgroups(int64_t n, int passes) { return ceil_div(ceil_div(n, kSeg), segs_per_wg(passes)); }
+
+// Passes per workgroup for a launch over `mask_bytes` bytes of mask: the most for which the launch
+// still has four rounds of workgroups (three of them fit a compute unit at a time).
+int index_passes_for(int64_t mask_bytes, int compute_units)
+{
+    const int64_t wanted = (int64_t)compute_units * 3 * 4;
+    for (int passes = kMaxPasses; passes > 1; passes /= 2)
+        if (mask_bytes / ((int64_t)segs_per_wg(passes) * kSeg) >= wanted) return passes;
+    return 1;
+}
 
 hipError_t launch_seg_ptr_from_idx(const int32_t *idx, int64_t nnz, int64_t n, int32_t *seg_ptr, hipStream_t s)
 {

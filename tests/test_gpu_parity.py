@@ -57,6 +57,40 @@ def test_build_index_many_segments(n, keep):
     assert np.array_equal(ix.seg_ptr.cpu().numpy(), ref_seg_ptr(ref, n))
 
 
+@pytest.mark.parametrize("passes", [1, 2, 4])
+def test_build_index_every_block_size(passes):
+    """A workgroup takes 64, 128 or 256 KiB of mask (one, two or four passes; the library picks by the
+    launch's size): each forced here on layers of less than a block, exactly one block, a block and a
+    bit, and many blocks with a ragged end, alone and as one batched call, with an index capacity that
+    is too small on one of them."""
+    block = 65536 * passes
+    sizes = [1, 1025, block - 1, block, block + 1, 3 * block + 17 * 1024 + 5, 40 * block + 123457]
+    masks = [si.bernoulli_mask(n, keep, 40 + i) for i, (n, keep) in enumerate(zip(sizes, [1.0, 0.5, 0.1, 0.03, 0.9, 0.2, 0.1]))]
+    refs = [oracle.build_index(m) for m in masks]
+    samo.samo_debug_set(samo.KNOB_INDEX_PASSES, passes)
+    try:
+        for mask, ref in zip(masks, refs):
+            ix = samo.samo_build_index(dev_u8(mask))
+            assert ix.nnz == ref.shape[0]
+            assert np.array_equal(ix.idx.cpu().numpy(), ref)
+            assert np.array_equal(ix.seg_ptr.cpu().numpy(), ref_seg_ptr(ref, mask.shape[0]))
+        got = samo.samo_build_index_many([dev_u8(m) for m in masks])
+        for ix, mask, ref in zip(got, masks, refs):
+            assert np.array_equal(ix.idx.cpu().numpy(), ref)
+            assert np.array_equal(ix.seg_ptr.cpu().numpy(), ref_seg_ptr(ref, mask.shape[0]))
+        # capacity too small: the count is still the true one, nothing is stored beyond the capacity
+        mask, ref = masks[-2], refs[-2]
+        cap = ref.shape[0] // 2
+        idx = torch.full((cap + 64,), -5, dtype=torch.int32, device=DEV)
+        seg = torch.empty(samo.samo_seg_ptr_len(mask.shape[0]), dtype=torch.int32, device=DEV)
+        nnz = torch.zeros(1, dtype=torch.int64, device=DEV)
+        samo.samo_build_index_into(dev_u8(mask), idx[:cap], seg, nnz)
+        assert int(nnz.item()) == ref.shape[0]
+        assert np.array_equal(idx[:cap].cpu().numpy(), ref[:cap]) and bool((idx[cap:] == -5).all())
+    finally:
+        samo.samo_debug_set(samo.KNOB_INDEX_PASSES)
+
+
 def test_build_index_batched_many_jobs():
     # more jobs than one launch group holds (48), with empty, tiny, ragged and multi-segment layers
     rng = np.random.default_rng(7)
