@@ -203,6 +203,7 @@ def main():
     layers, plan, host = model["layers"], model["plan"], model["host"]
     t_gen = model["seconds"]
     n_total, nnz_total = plan.totals()
+    headline_tiles = plan.num_tiles
     fused_bytes = fused_bytes_of(layers)
     move_bytes = sum(8 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 6 * L.n for L in layers)
 
@@ -331,7 +332,7 @@ def main():
     if headline_is_default:
         ceil_ms, ceil_bytes = (entries["samo_stream_copy(ceiling)"]["ms"], entries["samo_stream_copy(ceiling)"]["algorithmic_GB"] * 1e9) \
             if "samo_stream_copy(ceiling)" in entries else copy_ceiling(fused_bytes)
-        headline_row = (kernel_ms, fused_bytes, n_total, nnz_total, ceil_bytes / ceil_ms / 1e6, len(specs))
+        headline_row = (kernel_ms, fused_bytes, n_total, nnz_total, ceil_bytes / ceil_ms / 1e6, len(specs), headline_tiles)
     plan.close()
     del plan, layers, model
     torch.cuda.empty_cache()
@@ -393,7 +394,7 @@ def main():
         configs = {}
         for key, workload, sparsity in ALL_CONFIGS:
             if workload == "gpt2.7b" and abs(sparsity - 0.9) < 1e-9:
-                k_ms, k_bytes, k_n, k_nnz, ceil_gbs, k_mats = headline_row
+                k_ms, k_bytes, k_n, k_nnz, ceil_gbs, k_mats, k_tiles = headline_row
                 wall_ms = ms_per_step
             else:
                 c_specs = si.config(workload, sparsity)
@@ -405,13 +406,14 @@ def main():
                 c_ms, c_bytes = copy_ceiling(k_bytes)
                 ceil_gbs = c_bytes / c_ms / 1e6
                 k_mats = len(c_specs)
+                k_tiles = cm["plan"].num_tiles
                 cm["plan"].close()
                 del cm
                 torch.cuda.empty_cache()
             paper_default, paper_samo, resident_c = samo.samo_memory_model(k_n, k_nnz)
             c_traffic, c_source = traffic_of(workload, sparsity)
             gbs = k_bytes / k_ms / 1e6
-            configs[key] = {"matrices": k_mats, "N": k_n, "nnz": k_nnz, "sparsity": round(1.0 - k_nnz / max(k_n, 1), 4),
+            configs[key] = {"matrices": k_mats, "workgroups": k_tiles, "N": k_n, "nnz": k_nnz, "sparsity": round(1.0 - k_nnz / max(k_n, 1), 4),
                             "fused_step_ms": round(k_ms, 4), "ms_per_step_wall": round(wall_ms, 4),
                             "nonzero_params_per_s": round(k_nnz / (k_ms * 1e-3), 1),
                             "algorithmic_bytes": k_bytes, "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
@@ -442,6 +444,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "tile_kernel<1, 0, 0, 256> (step, dense gradient, Adam, 256 threads)", "kernel_ms": round(kernel_ms, 4),
+                     "workgroups": headline_tiles,
                      "algorithmic_bytes_per_launch": fused_bytes},
         "cpu_baseline": cpu,
         "cpu_baseline_parallel": cpu_parallel,

@@ -670,6 +670,11 @@ class Plan:
     def totals(self):
         return self._plan.n_total, self._plan.nnz_total
 
+    @property
+    def num_tiles(self) -> int:
+        """Workgroups of a tile-kernel launch over this plan (fused step, expansion)."""
+        return self._plan.num_tiles
+
     def stats_workspace_bytes(self) -> int:
         out = ctypes.c_size_t()
         _check(lib().samo_plan_stats_workspace_bytes(self._handle, ctypes.byref(out)), "samo_plan_stats_workspace_bytes")
