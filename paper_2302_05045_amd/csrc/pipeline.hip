@@ -215,65 +215,210 @@ __device__ __forceinline__ void sparse_tile(const samo_layer &L, int s0, int nse
     const int c1 = slice_bound(L, s0 + nsegs);
     __syncthreads();
 
-    // the tile's slice of the compressed arrays; at most kMaxTile elements, so slice-relative
-    // offsets fit an int even when c0 is close to 2^31
-    const int cnt = c1 > c0 ? c1 - c0 : 0;
-    const int32_t *__restrict__ IDX = L.idx + c0;
-    float *__restrict__ P = L.p + c0;
-    float *__restrict__ M = L.m + c0;
-    float *__restrict__ V = L.v + c0;
-    const uint16_t *__restrict__ G = L.g;
-    const uint16_t *__restrict__ GC16 = L.gc16 + c0;
-    const float *__restrict__ GC = L.gc + c0;
+    // The tile's slice [c0, c1) of the compressed arrays is walked in 16-byte vectors of four
+    // elements, starting at the vector that holds c0: the in-place fp32 streams move a quarter of
+    // the memory instructions of an element-per-lane walk (measured on the flat optimizer kernel:
+    // 0.78 against 0.75 of peak; on this kernel with the compressed fp16 gradient 0.75 against 0.73,
+    // the expansion at 80 % pruning 0.80 against 0.74).  A vector that straddles c0 or c1 is read
+    // whole — its other elements belong to the neighbouring tile and are left alone — and written
+    // element by element.  (Used where nothing is gathered from a dense tensor; the step that reads
+    // the dense gradient is sparse_tile_dense_grad.)
+    const int a0 = c0 & ~3;
+    const int nvec = c1 > c0 ? (c1 - a0 + 3) >> 2 : 0;
+    const int nnz = (int)L.nnz;
     const int ibase = (int)base;             // a layer's flat size fits int32
+    const uint16_t *__restrict__ G = L.g;
 
-    constexpr int U = kTileUnroll;
-    for (int r0 = tid; r0 < cnt; r0 += U * T) {
-        int j[U];
-        float pp[U], mm[U], vv[U], gg[U];
-        uint16_t gb[U];
+    for (int q = tid; q < nvec; q += T) {
+        const int e = a0 + 4 * q;            // first element of the vector: a multiple of 4
+        int j[4];
+        float pp[4], mm[4] = {0.f, 0.f, 0.f, 0.f}, vv[4] = {0.f, 0.f, 0.f, 0.f}, gg[4] = {0.f, 0.f, 0.f, 0.f};
+        uint16_t gb[4] = {0, 0, 0, 0};
+        bool own[4];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * T;
-            j[u] = ibase; pp[u] = 0.f; mm[u] = 0.f; vv[u] = 0.f; gg[u] = 0.f; gb[u] = 0;
-            if (r < cnt) {
-                j[u] = IDX[r];
-                pp[u] = P[r];
-                if (MODE == kModeStep) {
-                    mm[u] = M[r];
-                    if (OPT == kOptAdam) vv[u] = V[r];
-                    if (GSRC == kGradC16) gb[u] = GC16[r];
-                    if (GSRC == kGradC32) gg[u] = GC[r];
+        for (int u = 0; u < 4; ++u) own[u] = e + u >= c0 && e + u < c1;
+        const bool whole = e + 4 <= nnz;     // the vector lies inside the arrays
+        if (whole) {
+            const int4 jq = *reinterpret_cast<const int4 *>(L.idx + e);
+            const float4 pq = *reinterpret_cast<const float4 *>(L.p + e);
+            j[0] = jq.x; j[1] = jq.y; j[2] = jq.z; j[3] = jq.w;
+            pp[0] = pq.x; pp[1] = pq.y; pp[2] = pq.z; pp[3] = pq.w;
+            if (MODE == kModeStep) {
+                const float4 mq = *reinterpret_cast<const float4 *>(L.m + e);
+                mm[0] = mq.x; mm[1] = mq.y; mm[2] = mq.z; mm[3] = mq.w;
+                if (OPT == kOptAdam) {
+                    const float4 vq = *reinterpret_cast<const float4 *>(L.v + e);
+                    vv[0] = vq.x; vv[1] = vq.y; vv[2] = vq.z; vv[3] = vq.w;
+                }
+                if (GSRC == kGradC16) {
+                    const uint2 gq = *reinterpret_cast<const uint2 *>(L.gc16 + e);
+                    gb[0] = (uint16_t)gq.x; gb[1] = (uint16_t)(gq.x >> 16); gb[2] = (uint16_t)gq.y; gb[3] = (uint16_t)(gq.y >> 16);
+                }
+                if (GSRC == kGradC32) {
+                    const float4 gq = *reinterpret_cast<const float4 *>(L.gc + e);
+                    gg[0] = gq.x; gg[1] = gq.y; gg[2] = gq.z; gg[3] = gq.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                j[u] = ibase; pp[u] = 0.f;
+                if (own[u]) {
+                    j[u] = L.idx[e + u];
+                    pp[u] = L.p[e + u];
+                    if (MODE == kModeStep) {
+                        mm[u] = L.m[e + u];
+                        if (OPT == kOptAdam) vv[u] = L.v[e + u];
+                        if (GSRC == kGradC16) gb[u] = L.gc16[e + u];
+                        if (GSRC == kGradC32) gg[u] = L.gc[e + u];
+                    }
                 }
             }
         }
         if (MODE == kModeStep && GSRC == kGradDense) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (r0 + u * T < cnt) gb[u] = __builtin_nontemporal_load(G + j[u]);     // read once: +1 %
+            for (int u = 0; u < 4; ++u)
+                if (own[u]) gb[u] = __builtin_nontemporal_load(G + j[u]);     // read once: +1 %
         }
+        if (MODE == kModeStep) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * T;
-            if (r < cnt) {
-                if (MODE == kModeStep) {
-                    const float g = (GSRC == kGradC32) ? gg[u] * coef
-                                                       : (half_bits_to_float(gb[u]) * inv_scale) * coef;
+            for (int u = 0; u < 4; ++u) {
+                if (own[u]) {
+                    const float g = (GSRC == kGradC32) ? gg[u] * coef : (half_bits_to_float(gb[u]) * inv_scale) * coef;
                     opt_update<OPT>(pp[u], mm[u], vv[u], g, k);
-                    P[r] = pp[u];
-                    M[r] = mm[u];
-                    if (OPT == kOptAdam) V[r] = vv[u];
                 }
-                lds_w[j[u] - ibase] = float_to_half_bits(pp[u]);
+            }
+            if (whole && own[0] && own[3]) {
+                *reinterpret_cast<float4 *>(L.p + e) = make_float4(pp[0], pp[1], pp[2], pp[3]);
+                *reinterpret_cast<float4 *>(L.m + e) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+                if (OPT == kOptAdam) *reinterpret_cast<float4 *>(L.v + e) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (own[u]) {
+                        L.p[e + u] = pp[u];
+                        L.m[e + u] = mm[u];
+                        if (OPT == kOptAdam) L.v[e + u] = vv[u];
+                    }
+                }
             }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (own[u]) lds_w[j[u] - ibase] = float_to_half_bits(pp[u]);
     }
     __syncthreads();
 
     uint16_t *__restrict__ W = L.w + base;
-    const int nvec = len / 8;
-    for (int o = tid; o < nvec; o += T) store16_stream(reinterpret_cast<uint4 *>(W) + o, l4[o]);
-    for (int e = nvec * 8 + tid; e < len; e += T) W[e] = lds_w[e];
+    const int nvecw = len / 8;
+    for (int o = tid; o < nvecw; o += T) store16_stream(reinterpret_cast<uint4 *>(W) + o, l4[o]);
+    for (int e = nvecw * 8 + tid; e < len; e += T) W[e] = lds_w[e];
+}
+
+// The step that gathers the dense gradient, with the compressed arrays walked in 16-byte vectors as in
+// sparse_tile and the gather done element per lane all the same: a wave passes the positions of its 64
+// vectors (256 consecutive compressed elements) through LDS, lane l then reads the gradient at the
+// positions of elements l, l + 64, l + 128, l + 192 of that run — consecutive lanes on consecutive kept
+// positions, a handful of neighbouring lines per instruction — and the values go back through LDS to
+// the lanes that hold the elements' state.  Only the wave's own lanes exchange data: no workgroup barrier.
+// Gathering in vector order instead (lane l at elements 4l .. 4l+3) spreads every gather instruction
+// over four times as many lines: 0.52 of peak against 0.78; against the element-per-lane walk of
+// everything this is level at 90-95 % pruning, 2 % ahead at 80 % and 4 % on the row-clustered 6.7B model.
+template <int OPT, int T>
+__device__ __forceinline__ void sparse_tile_dense_grad(const samo_layer &L, int s0, int nsegs, int64_t base, int len,
+                                                       float inv_scale, float coef, const OptK &k, uint16_t *lds_w,
+                                                       int32_t *xj, uint16_t *xg)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint4 *l4 = reinterpret_cast<uint4 *>(lds_w);
+    for (int o = tid; o < (len + 7) / 8; o += T) l4[o] = make_uint4(0u, 0u, 0u, 0u);
+
+    const int c0 = slice_bound(L, s0);
+    const int c1 = slice_bound(L, s0 + nsegs);
+    __syncthreads();
+
+    const int a0 = c0 & ~3;
+    const int nvec = c1 > c0 ? (c1 - a0 + 3) >> 2 : 0;
+    const int nnz = (int)L.nnz;
+    const int ibase = (int)base;
+    const uint16_t *__restrict__ G = L.g;
+    int32_t *wj = xj + (tid >> 6) * 256;     // this wave's exchange areas
+    uint16_t *wg = xg + (tid >> 6) * 256;
+
+    for (int q0 = 0; q0 < nvec; q0 += T) {   // uniform trip count: every lane takes part in the exchange
+        const int q = q0 + tid;
+        const int e = a0 + 4 * q;
+        int j[4] = {ibase, ibase, ibase, ibase};
+        float pp[4] = {0.f, 0.f, 0.f, 0.f}, mm[4] = {0.f, 0.f, 0.f, 0.f}, vv[4] = {0.f, 0.f, 0.f, 0.f};
+        bool own[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) own[u] = q < nvec && e + u >= c0 && e + u < c1;
+        const bool whole = q < nvec && e + 4 <= nnz;
+        if (whole) {
+            const int4 jq = *reinterpret_cast<const int4 *>(L.idx + e);
+            const float4 pq = *reinterpret_cast<const float4 *>(L.p + e);
+            const float4 mq = *reinterpret_cast<const float4 *>(L.m + e);
+            j[0] = jq.x; j[1] = jq.y; j[2] = jq.z; j[3] = jq.w;
+            pp[0] = pq.x; pp[1] = pq.y; pp[2] = pq.z; pp[3] = pq.w;
+            mm[0] = mq.x; mm[1] = mq.y; mm[2] = mq.z; mm[3] = mq.w;
+            if (OPT == kOptAdam) {
+                const float4 vq = *reinterpret_cast<const float4 *>(L.v + e);
+                vv[0] = vq.x; vv[1] = vq.y; vv[2] = vq.z; vv[3] = vq.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (own[u]) {
+                    j[u] = L.idx[e + u];
+                    pp[u] = L.p[e + u];
+                    mm[u] = L.m[e + u];
+                    if (OPT == kOptAdam) vv[u] = L.v[e + u];
+                }
+            }
+        }
+        // positions to the wave's exchange area in vector order; -1 marks an element that is not this tile's
+        *reinterpret_cast<int4 *>(wj + 4 * lane) = make_int4(own[0] ? j[0] : -1, own[1] ? j[1] : -1, own[2] ? j[2] : -1,
+                                                             own[3] ? j[3] : -1);
+        __builtin_amdgcn_wave_barrier();
+        uint16_t got[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int jj = wj[lane + 64 * u];
+            got[u] = jj >= 0 ? __builtin_nontemporal_load(G + jj) : (uint16_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wg[lane + 64 * u] = got[u];
+        __builtin_amdgcn_wave_barrier();
+        const uint2 gq = *reinterpret_cast<const uint2 *>(wg + 4 * lane);
+        const uint16_t gb[4] = {(uint16_t)gq.x, (uint16_t)(gq.x >> 16), (uint16_t)gq.y, (uint16_t)(gq.y >> 16)};
+        __builtin_amdgcn_wave_barrier();     // the areas are free for the next trip
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (own[u]) opt_update<OPT>(pp[u], mm[u], vv[u], (half_bits_to_float(gb[u]) * inv_scale) * coef, k);
+        if (whole && own[0] && own[3]) {
+            *reinterpret_cast<float4 *>(L.p + e) = make_float4(pp[0], pp[1], pp[2], pp[3]);
+            *reinterpret_cast<float4 *>(L.m + e) = make_float4(mm[0], mm[1], mm[2], mm[3]);
+            if (OPT == kOptAdam) *reinterpret_cast<float4 *>(L.v + e) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (own[u]) {
+                    L.p[e + u] = pp[u];
+                    L.m[e + u] = mm[u];
+                    if (OPT == kOptAdam) L.v[e + u] = vv[u];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (own[u]) lds_w[j[u] - ibase] = float_to_half_bits(pp[u]);
+    }
+    __syncthreads();
+
+    uint16_t *__restrict__ W = L.w + base;
+    const int nvecw = len / 8;
+    for (int o = tid; o < nvecw; o += T) store16_stream(reinterpret_cast<uint4 *>(W) + o, l4[o]);
+    for (int e = nvecw * 8 + tid; e < len; e += T) W[e] = lds_w[e];
 }
 
 template <int MODE, int GSRC, int OPT, int T>
@@ -281,6 +426,9 @@ __global__ void __launch_bounds__(T)
 tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guard)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[kMaxTile];
+    constexpr bool kExchange = MODE == kModeStep && GSRC == kGradDense;
+    __shared__ __attribute__((aligned(16))) int32_t xj[kExchange ? T * 4 : 4];      // per wave: 256 positions on their way to the gather
+    __shared__ __attribute__((aligned(16))) uint16_t xg[kExchange ? T * 4 : 8];     // and the 256 gradient values on their way back
     bool skip;
     const float coef = guard_coef(guard, &skip);
     if (skip) return;                         // uniform: every workgroup of the launch takes it
@@ -293,6 +441,8 @@ tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guar
     const int len = rest < (int64_t)nsegs * kSeg ? (int)rest : nsegs * kSeg;
     if (L.seg_ptr == nullptr)                 // dense (unpruned) layer
         dense_tile<MODE, GSRC, OPT, T>(L, base, len, inv_scale, coef, k);
+    else if (kExchange)
+        sparse_tile_dense_grad<OPT, T>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w, xj, xg);
     else
         sparse_tile<MODE, GSRC, OPT, T>(L, s0, nsegs, base, len, inv_scale, coef, k, lds_w);
 }
@@ -853,8 +1003,10 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
                        const GuardK &guard, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt),
-                                kMaxTile * 2);
+    // static LDS of the kernel: the tile's fp16 image, and for the step that gathers the dense gradient
+    // the waves' exchange areas
+    const int static_lds = kMaxTile * 2 + (mode == kModeStep && gsrc == kGradDense ? kTileThreads * 4 * 6 : 0);
+    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt), static_lds);
     if (mode == kModeDecompress) {
         tile_kernel<kModeDecompress, kGradDense, kOptAdam, kExpandThreads><<<dim3((unsigned)ls.wgs), dim3(kExpandThreads), pad, s>>>(ls, inv_scale, k,
                                                                                                                           guard);
