@@ -648,13 +648,6 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
         } else {
             for (int e = 0; e < cnt; ++e) fv[e] = S[i + e];
         }
-    } else if (src == kGradDense32) {                        // dense fp32 gradient at the kept positions
-        if (cnt == 4) {
-            const int4 j = *reinterpret_cast<const int4 *>(L.idx + i);
-            fv[0] = L.g32[j.x]; fv[1] = L.g32[j.y]; fv[2] = L.g32[j.z]; fv[3] = L.g32[j.w];
-        } else {
-            for (int e = 0; e < cnt; ++e) fv[e] = L.g32[L.idx[i + e]];
-        }
     } else if (src == kGradC16 || identity) {
         const uint16_t *S = (src == kGradC16) ? L.gc16 : L.g;
         if (cnt == 4) {
@@ -664,6 +657,14 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
             for (int e = 0; e < cnt; ++e) hb[e] = S[i + e];
         }
     } else {
+        // A dense gradient read at the kept positions.  The lane's four positions come as one 16-byte
+        // vector, but the gather is done element per lane: the wave passes its 256 positions through
+        // LDS, lane l reads the gradient at those of elements l, l + 64, l + 128, l + 192 — consecutive
+        // lanes on consecutive kept positions, a handful of neighbouring lines per instruction — and the
+        // values come back through LDS in vector order.  One wave per workgroup: no barrier needed.
+        __shared__ __attribute__((aligned(16))) int32_t xj[kChunk];
+        __shared__ __attribute__((aligned(16))) uint32_t xv[kChunk];
+        int j4[4] = {-1, -1, -1, -1};                                // -1: beyond the layer's last kept element
         if (cnt == 4) {
             int4 j;
             if (OUT == kOutF32) {                                // measured: +2 % here, -1.5 % with fp16 output
@@ -672,9 +673,28 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
             } else {
                 j = *reinterpret_cast<const int4 *>(L.idx + i);
             }
-            hb[0] = L.g[j.x]; hb[1] = L.g[j.y]; hb[2] = L.g[j.z]; hb[3] = L.g[j.w];
+            j4[0] = j.x; j4[1] = j.y; j4[2] = j.z; j4[3] = j.w;
         } else {
-            for (int e = 0; e < cnt; ++e) hb[e] = L.g[L.idx[i + e]];
+            for (int e = 0; e < cnt; ++e) j4[e] = L.idx[i + e];
+        }
+        const int lane = threadIdx.x;
+        *reinterpret_cast<int4 *>(xj + 4 * lane) = make_int4(j4[0], j4[1], j4[2], j4[3]);
+        __builtin_amdgcn_wave_barrier();
+        uint32_t got[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int jj = xj[lane + 64 * u];
+            if (src == kGradDense32) got[u] = jj >= 0 ? __float_as_uint(L.g32[jj]) : 0u;
+            else got[u] = jj >= 0 ? (uint32_t)L.g[jj] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xv[lane + 64 * u] = got[u];
+        __builtin_amdgcn_wave_barrier();
+        const uint4 back = *reinterpret_cast<const uint4 *>(xv + 4 * lane);
+        if (src == kGradDense32) {
+            fv[0] = __uint_as_float(back.x); fv[1] = __uint_as_float(back.y); fv[2] = __uint_as_float(back.z); fv[3] = __uint_as_float(back.w);
+        } else {
+            hb[0] = (uint16_t)back.x; hb[1] = (uint16_t)back.y; hb[2] = (uint16_t)back.z; hb[3] = (uint16_t)back.w;
         }
     }
     if (OUT == kOutF16) {
@@ -1066,7 +1086,7 @@ hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale,
 {
     if (ls.wgs <= 0) return hipSuccess;
     const dim3 grid((unsigned)ls.wgs), block(kFlatThreads);
-    const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 64);
+    const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 2 * kChunk * 4);   // static: the exchange areas
     if (out == kOutF32) gather_kernel<kOutF32><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     else if (out == kOutF16) gather_kernel<kOutF16><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     else gather_kernel<kOutNone><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
