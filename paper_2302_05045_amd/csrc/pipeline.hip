@@ -981,11 +981,14 @@ static int lds_pad_for(int target_wgs, int static_bytes)
     return want > static_bytes ? want - static_bytes : 0;
 }
 
-static int occ_tile_step(int gsrc, int opt)
+static int occ_tile_step(int gsrc, int opt, float keep)
 {
     // a step that reads the dense gradient keeps whole dense lines in flight: 6 workgroups per CU;
-    // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling
-    return gsrc == kGradDense ? knob(SAMO_KNOB_OCC_TILE_STEP, 6) : knob(SAMO_KNOB_OCC_TILE_C16, 0);
+    // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling at
+    // 90 % pruning and above (8 workgroups: 0.75 of peak against 0.72 with 6), while at 80 % the
+    // in-place streams are over half the traffic and 6 is the optimum again (0.74 against 0.68 with 8)
+    if (gsrc == kGradDense) return knob(SAMO_KNOB_OCC_TILE_STEP, 6);
+    return knob(SAMO_KNOB_OCC_TILE_C16, keep > 0.15f ? 6 : 0);
 }
 
 static int occ_tile_decompress()
@@ -1026,7 +1029,7 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
     // static LDS of the kernel: the tile's fp16 image, and for the step that gathers the dense gradient
     // the waves' exchange areas
     const int static_lds = kMaxTile * 2 + (mode == kModeStep && gsrc == kGradDense ? kTileThreads * 4 * 6 : 0);
-    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt), static_lds);
+    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt, ls.keep), static_lds);
     if (mode == kModeDecompress) {
         tile_kernel<kModeDecompress, kGradDense, kOptAdam, kExpandThreads><<<dim3((unsigned)ls.wgs), dim3(kExpandThreads), pad, s>>>(ls, inv_scale, k,
                                                                                                                           guard);
