@@ -156,37 +156,52 @@ __device__ __forceinline__ void dense_tile(const samo_layer &L, int64_t base, in
     float4 *__restrict__ P = reinterpret_cast<float4 *>(L.p + base);
     float4 *__restrict__ M = reinterpret_cast<float4 *>(L.m + base);
     float4 *__restrict__ V = reinterpret_cast<float4 *>(L.v + base);
-    uint2 *__restrict__ W = reinterpret_cast<uint2 *>(L.w + base);
-    const int nvec = len / 4;
-    for (int o = tid; o < nvec; o += T) {
-        float4 p = P[o];
+    // Eight consecutive elements per thread: two 16-byte vectors of each fp32 array, one of each
+    // fp16 array (16-byte instead of 8-byte accesses to g and w: 0.72 against 0.70 of peak on the
+    // 50304 x 4096 embedding; the gradient, read exactly once, loaded past the caches: 0.74).
+    const int nvec8 = len / 8;
+    for (int o = tid; o < nvec8; o += T) {
+        float p[8], m[8], v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, g[8];
+        const float4 pa = P[2 * o], pb = P[2 * o + 1];
+        p[0] = pa.x; p[1] = pa.y; p[2] = pa.z; p[3] = pa.w; p[4] = pb.x; p[5] = pb.y; p[6] = pb.z; p[7] = pb.w;
         if (MODE == kModeStep) {
-            float4 m = M[o];
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (OPT == kOptAdam) v = V[o];
-            float4 g;
-            if (GSRC == kGradC32) {
-                g = reinterpret_cast<const float4 *>(L.gc + base)[o];
-                g.x *= coef; g.y *= coef; g.z *= coef; g.w *= coef;
-            } else {
-                const uint2 gq = reinterpret_cast<const uint2 *>((GSRC == kGradDense ? L.g : L.gc16) + base)[o];
-                g.x = (half_bits_to_float((uint16_t)gq.x) * inv_scale) * coef;
-                g.y = (half_bits_to_float((uint16_t)(gq.x >> 16)) * inv_scale) * coef;
-                g.z = (half_bits_to_float((uint16_t)gq.y) * inv_scale) * coef;
-                g.w = (half_bits_to_float((uint16_t)(gq.y >> 16)) * inv_scale) * coef;
+            const float4 ma = M[2 * o], mb = M[2 * o + 1];
+            m[0] = ma.x; m[1] = ma.y; m[2] = ma.z; m[3] = ma.w; m[4] = mb.x; m[5] = mb.y; m[6] = mb.z; m[7] = mb.w;
+            if (OPT == kOptAdam) {
+                const float4 va = V[2 * o], vb = V[2 * o + 1];
+                v[0] = va.x; v[1] = va.y; v[2] = va.z; v[3] = va.w; v[4] = vb.x; v[5] = vb.y; v[6] = vb.z; v[7] = vb.w;
             }
-            opt_update<OPT>(p.x, m.x, v.x, g.x, k);
-            opt_update<OPT>(p.y, m.y, v.y, g.y, k);
-            opt_update<OPT>(p.z, m.z, v.z, g.z, k);
-            opt_update<OPT>(p.w, m.w, v.w, g.w, k);
-            P[o] = p;
-            M[o] = m;
-            if (OPT == kOptAdam) V[o] = v;
+            if (GSRC == kGradC32) {
+                const f32x4 ga = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(L.gc + base) + 2 * o);
+                const f32x4 gb = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(L.gc + base) + 2 * o + 1);
+                g[0] = ga.x; g[1] = ga.y; g[2] = ga.z; g[3] = ga.w; g[4] = gb.x; g[5] = gb.y; g[6] = gb.z; g[7] = gb.w;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g[u] *= coef;
+            } else {
+                const u32x4 gq = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>((GSRC == kGradDense ? L.g : L.gc16) + base) + o);
+                const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    g[u] = (half_bits_to_float((uint16_t)(gw[u >> 1] >> (16 * (u & 1)))) * inv_scale) * coef;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) opt_update<OPT>(p[u], m[u], v[u], g[u], k);
+            P[2 * o] = make_float4(p[0], p[1], p[2], p[3]);
+            P[2 * o + 1] = make_float4(p[4], p[5], p[6], p[7]);
+            M[2 * o] = make_float4(m[0], m[1], m[2], m[3]);
+            M[2 * o + 1] = make_float4(m[4], m[5], m[6], m[7]);
+            if (OPT == kOptAdam) {
+                V[2 * o] = make_float4(v[0], v[1], v[2], v[3]);
+                V[2 * o + 1] = make_float4(v[4], v[5], v[6], v[7]);
+            }
         }
-        const uint32_t lo = (uint32_t)float_to_half_bits(p.x) | ((uint32_t)float_to_half_bits(p.y) << 16);
-        const uint32_t hi = (uint32_t)float_to_half_bits(p.z) | ((uint32_t)float_to_half_bits(p.w) << 16);
-        store8_stream(W + o, make_uint2(lo, hi));
+        uint32_t wq[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            wq[u] = (uint32_t)float_to_half_bits(p[2 * u]) | ((uint32_t)float_to_half_bits(p[2 * u + 1]) << 16);
+        store16_stream(reinterpret_cast<uint4 *>(L.w + base) + o, make_uint4(wq[0], wq[1], wq[2], wq[3]));
     }
+    const int nvec = nvec8 * 2;           // elements handled above, in units of four
     for (int e = nvec * 4 + tid; e < len; e += T) {      // ragged end of the layer
         float pe = L.p[base + e];
         if (MODE == kModeStep) {
