@@ -221,6 +221,31 @@ def test_header_is_plain_c(tmp_path):
                            str(src), "-o", str(tmp_path / "use_samo_cpp.o")])
 
 
+def test_weight_gradient_kernels_touch_m0_only_in_their_lds_copies(tmp_path):
+    """The direct-to-LDS copies of wgrad.hip set M0 from inline assembly, which cannot declare that
+    register clobbered; the kernels are right only as long as the compiler itself never uses M0 in
+    them.  Checked on the generated ISA after every build (so a compiler change shows here and not
+    as wrong numbers): in the whole device code of wgrad.hip, M0 appears only as the destination of
+    `s_mov_b32 m0, <sgpr>`, each followed by `s_nop 0` and `global_load_lds_dwordx4` — exactly the
+    copy helper's three instructions."""
+    import subprocess
+    from paper_2302_05045_amd import _build
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    asm = tmp_path / "wgrad.s"
+    subprocess.check_call([hipcc] + [f for f in _build.FLAGS if f not in ("-shared", "-fPIC")] +
+                          ["-S", "--cuda-device-only", "-I", os.path.join(ROOT, "include"), "-I", _build.CSRC,
+                           os.path.join(_build.CSRC, "wgrad.hip"), "-o", str(asm)],
+                          stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    lines = [ln.split(";")[0].strip() for ln in asm.read_text().splitlines()]
+    code = [ln for ln in lines if ln and not ln.startswith(".") and not ln.endswith(":")]
+    uses = [i for i, ln in enumerate(code) if re.search(r"\bm0\b", ln)]
+    assert len(uses) >= 16, "the copy helper's M0 writes are expected in four kernels"
+    for i in uses:
+        assert re.fullmatch(r"s_mov_b32 m0, s\d+", code[i]), code[i]
+        assert code[i + 1] == "s_nop 0" and code[i + 2].startswith("global_load_lds_dwordx4 "), code[i:i + 3]
+    assert sum(ln.startswith("global_load_lds_dwordx4 ") for ln in code) == len(uses)
+
+
 def test_host_side_of_the_library_under_sanitizers(tmp_path):
     """The library's host code (argument validation, status strings, byte accounting) built with
     AddressSanitizer and UBSan and driven through every entry point with arguments it must reject
