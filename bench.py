@@ -189,6 +189,8 @@ def main():
         src = torch.empty(nb, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
         ms = time_entry(lambda: samo.samo_stream_copy(dst, src))
+        if ms < 1.0:                              # a short copy: as many launches as make ~30 ms
+            ms = time_entry(lambda: samo.samo_stream_copy(dst, src), iters=min(1000, int(30.0 / max(ms, 1e-3))))
         return ms, 2 * nb
 
     specs = si.config(args.workload, args.sparsity, layers=args.layers)
@@ -395,12 +397,20 @@ def main():
         for key, workload, sparsity in ALL_CONFIGS:
             if workload == "gpt2.7b" and abs(sparsity - 0.9) < 1e-9:
                 k_ms, k_bytes, k_n, k_nnz, ceil_gbs, k_mats, k_tiles = headline_row
-                wall_ms = ms_per_step
+                wall_ms, k_steps = ms_per_step, args.steps
             else:
                 c_specs = si.config(workload, sparsity)
                 cm = load_model(c_specs)
                 cm["plan"].samo_decompress_batched()
-                k_ms, wall_ms, _ = time_steps(cm["plan"], max(10, args.steps), args.warmup, 0)
+                # a configuration whose step takes a fraction of a millisecond gets enough launches to run for
+                # ~30 ms before and ~100 ms inside the timed region: the short ones otherwise finish before the
+                # device has left its idle clocks (per-dispatch times of the 350M shape spread 311-357 us in a
+                # 35-launch run)
+                probe_ms, _, t_c = time_steps(cm["plan"], 3, 2, 0)
+                c_warm = max(args.warmup, min(400, int(30.0 / max(probe_ms, 1e-3))))
+                c_steps = max(10, args.steps, min(1000, int(100.0 / max(probe_ms, 1e-3))))
+                k_ms, wall_ms, _ = time_steps(cm["plan"], c_steps, c_warm, t_c)
+                k_steps = c_steps
                 k_bytes = fused_bytes_of(cm["layers"])
                 k_n, k_nnz = cm["plan"].totals()
                 c_ms, c_bytes = copy_ceiling(k_bytes)
@@ -414,7 +424,7 @@ def main():
             c_traffic, c_source = traffic_of(workload, sparsity)
             gbs = k_bytes / k_ms / 1e6
             configs[key] = {"matrices": k_mats, "workgroups": k_tiles, "N": k_n, "nnz": k_nnz, "sparsity": round(1.0 - k_nnz / max(k_n, 1), 4),
-                            "fused_step_ms": round(k_ms, 4), "ms_per_step_wall": round(wall_ms, 4),
+                            "fused_step_ms": round(k_ms, 4), "ms_per_step_wall": round(wall_ms, 4), "timed_steps": k_steps,
                             "nonzero_params_per_s": round(k_nnz / (k_ms * 1e-3), 1),
                             "algorithmic_bytes": k_bytes, "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                             "copy_ceiling_GB/s": round(ceil_gbs, 1), "frac_of_copy_ceiling": round(gbs / ceil_gbs, 4),
