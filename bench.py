@@ -234,6 +234,10 @@ def main():
         entry("samo_adam_expand_batched(clip+skip guard)",
               time_entry(lambda: plan.samo_adam_expand_batched(inv, cfg(t + 1), stats.guard(1e9, True))),
               sum(30 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 28 * L.n for L in layers))
+        entry("samo_gather_fp16_batched", time_entry(lambda: plan.samo_gather_fp16_batched(False, inv)),
+              sum(6 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 4 * L.n for L in layers))
+        # statistics of the compressed fp16 gradient alone: what a data-parallel run calls after its all-reduce
+        entry("samo_grad_stats_batched(gc16)", time_entry(lambda: plan.samo_grad_stats_batched(1, inv, stats)), 2 * nnz_total)
         entry("samo_grad_stats_batched(dense g)", time_entry(lambda: plan.samo_grad_stats_batched(0, inv, stats)),
               sum(4 * L.p.numel() + 2 * L.n if L.seg_ptr is not None else 2 * L.n for L in layers))
         entry("samo_fused_sgd_step_batched", time_entry(lambda: plan.samo_fused_sgd_step_batched(inv, samo.sgd_cfg(1e-4))),

@@ -754,6 +754,115 @@ gather_kernel(const LaunchSet ls, int src, float inv_scale, int accumulate, Stat
     if (partials) write_partial(ss, bad, partials);
 }
 
+// Statistics of a compressed gradient (gc16 or gc) with nothing written: no gather and no store
+// to hide, so one record per wave would leave the launch bound by its own overhead (512 bytes read
+// per wave).  Here a wave takes kStatRun chunk records, kStatAhead at a time with their loads in
+// flight together, and still leaves one partial per record, each reduced as gather_kernel reduces
+// it and stored in the slot gather_kernel would use: the sums that follow, and so the bits of the
+// result, are those of every other way to the same statistics.  The records of a wave are the ones
+// whose slots are consecutive (every eighth record), so lane k stores partial k and the wave
+// writes one run of kStatRun partials.  The loads of a group sit in straight-line code (descriptors read
+// unconditionally at a clamped record, the 4-element vector under a lane predicate); the ragged
+// end of a layer, at most one lane of one record, is read element by element afterwards.
+constexpr int kStatRun = 8;
+constexpr int kStatAhead = 8;        // records whose loads are in flight together
+
+template <int SRC>
+__global__ void __launch_bounds__(kFlatThreads)
+stats_compressed_kernel(const LaunchSet ls, float inv_scale, StatPartial *__restrict__ partials)
+{
+    static_assert(SRC == kGradC16 || SRC == kGradC32, "compressed sources only");
+    static_assert(kStatRun <= kFlatThreads && kStatRun % kStatAhead == 0, "lane k keeps partial k");
+    constexpr int kWords = (SRC == kGradC32) ? 4 : 2;     // 32-bit words of a lane's four elements
+    const unsigned total = (unsigned)ls.wgs;              // records, and workgroups of the launch this one stands for
+    const unsigned per_xcd = (total + 7u) / 8u;
+    const unsigned run = blockIdx.x & 7u;                 // which eighth of the slots
+    const unsigned base = (blockIdx.x >> 3) * kStatRun;   // first slot of the wave within that eighth
+    double mine_ss = 0.0;
+    int mine_bad = 0;
+    bool have = false;
+    typedef const __attribute__((address_space(1))) uint32_t *GlobalWords;     // the arrays live in device memory
+    typedef const __attribute__((address_space(1))) uint16_t *GlobalHalves;
+    typedef unsigned int Words2 __attribute__((ext_vector_type(2)));
+    typedef const __attribute__((address_space(1))) Words2 *GlobalWords2;
+    typedef const __attribute__((address_space(1))) u32x4 *GlobalWords4;
+    for (int r0 = 0; r0 < kStatRun; r0 += kStatAhead) {
+        uint32_t q[kStatAhead][kWords];
+        GlobalWords at[kStatAhead];                        // the lane's first element
+        int cnt[kStatAhead];
+        bool live[kStatAhead];
+        WgRec r[kStatAhead];
+        int64_t nnz[kStatAhead];
+        const void *arr[kStatAhead];
+#pragma unroll
+        for (int u = 0; u < kStatAhead; ++u) {
+            const unsigned rec = run + 8u * (base + r0 + u);
+            live[u] = (base + r0 + u) < per_xcd && rec < total;
+            r[u] = ls.recs[live[u] ? rec : 0u];
+        }
+#pragma unroll
+        for (int u = 0; u < kStatAhead; ++u) {
+            const samo_layer *L = ls.layers + r[u].layer;
+            nnz[u] = L->nnz;
+            arr[u] = (SRC == kGradC32) ? (const void *)L->gc : (const void *)L->gc16;
+        }
+#pragma unroll
+        for (int u = 0; u < kStatAhead; ++u) {
+            // a record beyond the launch counts as one beyond its layer's end: nothing to read
+            const int64_t i = live[u] ? r[u].local * kChunk + (int64_t)threadIdx.x * 4 : INT64_MAX / 2;
+            cnt[u] = (nnz[u] - i >= 4) ? 4 : (nnz[u] - i > 0 ? (int)(nnz[u] - i) : 0);
+            const int64_t off = live[u] ? i : 0;
+            at[u] = (SRC == kGradC32) ? (GlobalWords)((const float *)arr[u] + off)
+                                      : (GlobalWords)((const uint16_t *)arr[u] + off);
+#pragma unroll
+            for (int w = 0; w < kWords; ++w) q[u][w] = 0u;
+            if (cnt[u] == 4) {
+                if (SRC == kGradC32) {
+                    const u32x4 x = *(GlobalWords4)at[u];
+                    q[u][0] = x.x; q[u][1] = x.y; q[u][kWords - 2] = x.z; q[u][kWords - 1] = x.w;
+                } else {
+                    const Words2 x = *(GlobalWords2)at[u];
+                    q[u][0] = x.x; q[u][1] = x.y;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kStatAhead; ++u) {
+            if (cnt[u] > 0 && cnt[u] < 4) {
+#pragma unroll
+                for (int e = 0; e < 3; ++e) {
+                    if (e >= cnt[u]) continue;
+                    if (SRC == kGradC32) q[u][e] = at[u][e];
+                    else q[u][e >> 1] |= (uint32_t)((GlobalHalves)at[u])[e] << (16 * (e & 1));
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kStatAhead; ++u) {
+            double ss = 0.0;
+            int bad = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float raw = (SRC == kGradC32) ? __uint_as_float(q[u][e])
+                                                    : half_bits_to_float((uint16_t)(q[u][e >> 1] >> (16 * (e & 1))));
+                if (e < cnt[u]) {
+                    const float x = raw * inv_scale;
+                    ss += (double)x * (double)x;
+                    bad |= is_nonfinite(x) ? 1 : 0;
+                }
+            }
+            ss = wave_sum_f64(ss);
+            bad = __any(bad) ? 1 : 0;
+            if ((int)threadIdx.x == r0 + u) { mine_ss = ss; mine_bad = bad; have = live[u]; }
+        }
+    }
+    if (have) {
+        const unsigned slot = run * per_xcd + base + threadIdx.x;
+        partials[slot].sum_squares = mine_ss;
+        partials[slot].nonfinite = mine_bad;
+    }
+}
+
 // First level of the reduction: workgroup b sums the contiguous slice [b * per, (b + 1) * per) of
 // the partials into out[b]; thread t of it takes elements t, t + 256, ... of the slice, then a
 // fixed tree.  Every order is fixed by (count, per) alone.
@@ -1103,6 +1212,13 @@ hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale,
                          StatPartial *partials, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
+    if (partials && ls.layers && out == kOutNone && (src == kGradC16 || src == kGradC32)) {
+        const int64_t per_xcd = ceil_div(ls.wgs, (int64_t)8);
+        const dim3 run_grid((unsigned)(8 * ceil_div(per_xcd, (int64_t)kStatRun)));
+        if (src == kGradC16) stats_compressed_kernel<kGradC16><<<run_grid, dim3(kFlatThreads), 0, s>>>(ls, inv_scale, partials);
+        else stats_compressed_kernel<kGradC32><<<run_grid, dim3(kFlatThreads), 0, s>>>(ls, inv_scale, partials);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)ls.wgs), block(kFlatThreads);
     const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 2 * kChunk * 4);   // static: the exchange areas
     if (out == kOutF32) gather_kernel<kOutF32><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
