@@ -11,7 +11,7 @@
 // soon as it knows it; a successor sums the counts back to the nearest running total); finally
 // the ascending int32 positions are produced from the flag words still held in registers,
 // collected per segment in LDS and stored as contiguous runs.  All integer work: one read of the
-// mask plus the write of the index, about 134 vector-ALU instructions per segment and wave.
+// mask plus the write of the index, about 100 vector-ALU instructions per segment and wave.
 //
 // The chain lives in seg_ptr itself: seg_ptr[e], e the end of a workgroup's block of segments, is
 // the number of kept elements up to there — exactly the running total the next workgroup needs.
@@ -46,13 +46,13 @@ __device__ __forceinline__ uint32_t lane_flags(const uint8_t *__restrict__ mask,
         for (int b = 0; b < 16; ++b)
             if (first + b < n) w[b >> 2] |= (uint32_t)mask[first + b] << (8 * (b & 3));
     }
-    uint32_t f = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t t = nonzero_byte_flags(w[q]) >> 7;   // bits 0, 8, 16, 24
-        f |= ((t & 1u) | ((t >> 7) & 2u) | ((t >> 14) & 4u) | ((t >> 21) & 8u)) << (4 * q);
-    }
-    return f;
+    // Every non-zero byte is now 0x80: a dot product of the four bytes of a word with the weights
+    // 1, 2, 4, 8 (16 .. 128 for the next word, accumulated) is 128 times their flag bits in order.
+    uint32_t lo = __builtin_amdgcn_udot4(nonzero_byte_flags(w[0]), 0x08040201u, 0u, false);
+    lo = __builtin_amdgcn_udot4(nonzero_byte_flags(w[1]), 0x80402010u, lo, false);
+    uint32_t hi = __builtin_amdgcn_udot4(nonzero_byte_flags(w[2]), 0x08040201u, 0u, false);
+    hi = __builtin_amdgcn_udot4(nonzero_byte_flags(w[3]), 0x80402010u, hi, false);
+    return (lo >> 7) | (hi << 1);
 }
 
 __device__ __forceinline__ int wave_sum(int x)
