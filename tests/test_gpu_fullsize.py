@@ -123,6 +123,13 @@ def test_gpt2p7b_90pct_every_batched_entry_at_full_size():
     ref_ss = sum(oracle.sum_squares(oracle.gather(h[6], h[2], INV)) for h in model.host)
     ss, bad = stats.read()
     assert not bad and abs(ss - ref_ss) <= 2 * nnz_total * 2.0 ** -53 * ref_ss
+    # the statistics a data-parallel run takes from the reduced compressed gradient (a kernel of its
+    # own, several chunk records per wave) and those of the unscaled fp32 one: same partials, same bits
+    again = samo.GradStats(model.plan)
+    model.plan.samo_grad_stats_batched(1, INV, again)
+    assert again.read() == (ss, bad)
+    model.plan.samo_grad_stats_batched(2, 1.0, again)          # gc as step 3's gather left it: the same gradient
+    assert again.read() == (ss, bad)
     for L, h in zip(model.layers[:8], model.host[:8]):
         assert np.array_equal(host_bits(L.gc16), oracle.compress_f16(h[6], h[2])), h[0].name
     model.oracle_step(4)
