@@ -325,6 +325,19 @@ def main():
             del jobs
             mfma_entry("library GEMM + samo_gather_grads over the block", time_entry(library_block))
             del ops
+            # what the matrix units of this box sustain from registers alone (their clock under that load
+            # included): the in-run ceiling of the contractions, as the plain copy is that of the streams
+            cus = torch.cuda.get_device_properties(dev).multi_processor_count
+            sink = torch.empty(cus, dtype=torch.float32, device=dev)
+            probe_flops = [0.0]
+
+            def probe():
+                probe_flops[0] = samo.samo_mfma_rate_probe(4000, sink)
+            ms = time_entry(probe, iters=5, warm=2)
+            mfma_entries["samo_mfma_rate_probe(ceiling)"] = {
+                "ms": round(ms, 4), "TFLOP/s": round(probe_flops[0] / ms / 1e9, 1),
+                "frac_of_peak": round(probe_flops[0] / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 4)}
+            del sink
 
     achieved = fused_bytes / kernel_ms / 1e6
     traffic, traffic_source = traffic_of(args.workload, args.sparsity)

@@ -427,6 +427,15 @@ samo_status samo_memory_model(int64_t n_total, int64_t nnz_total, int64_t *paper
  * launch shape as the pipeline's kernels: measures the achievable HBM stream
  * rate and calibrates hardware byte counters.  Not part of the method. */
 samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void *stream);
+/* Issues `iters` rounds of eight independent 32x32x16 fp16 matrix instructions per wave from
+ * registers, 8 waves per workgroup, `workgroups` workgroups (one per compute unit fills the
+ * device): measures the matrix rate the device sustains, its clock under that load included,
+ * before any operand is fetched -- the ceiling beside which the weight-gradient kernels are read.
+ * d_sink (device, float[workgroups]) receives one value per workgroup; *flops (host, may be NULL)
+ * the floating-point operations of the launch.  iters <= 2^24, workgroups <= 2^16 (SAMO_ERR_SIZE).
+ * Not part of the method. */
+samo_status samo_mfma_rate_probe(int64_t iters, float *d_sink, int32_t workgroups, double *flops,
+                                 void *stream);
 
 /* ---------------------------------------------------------------- tuning and testing aids
  * Process-wide knobs, set from the host; the entry points read no environment variable.  A knob

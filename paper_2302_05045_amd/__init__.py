@@ -170,6 +170,8 @@ _SIGNATURES = {
     "samo_wgrad_gather_fp16_batched": (ctypes.c_int32, [ctypes.c_int32, ctypes.POINTER(WgradJob), ctypes.c_int32,
                                                         ctypes.c_void_p]),
     "samo_stream_copy": (ctypes.c_int32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
+    "samo_mfma_rate_probe": (ctypes.c_int32, [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32,
+                                              ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
 }
 
 
@@ -738,6 +740,14 @@ def samo_memory_model(n_total: int, nnz_total: int):
     _check(lib().samo_memory_model(int(n_total), int(nnz_total), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
            "samo_memory_model")
     return a.value, b.value, c.value
+
+
+def samo_mfma_rate_probe(iters: int, sink: torch.Tensor) -> float:
+    """Launches the matrix-rate probe with one workgroup per element of sink (float32); returns its flops."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().samo_mfma_rate_probe(int(iters), _dev(sink, torch.float32, "sink"), sink.numel(), ctypes.byref(flops),
+                                      _stream()), "samo_mfma_rate_probe")
+    return flops.value
 
 
 def samo_stream_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

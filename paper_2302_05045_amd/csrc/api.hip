@@ -874,4 +874,13 @@ samo_status samo_stream_copy(void *d_dst, const void *d_src, int64_t bytes, void
     return hip_status(launch_copy(d_dst, d_src, bytes, as_stream(stream)));
 }
 
+samo_status samo_mfma_rate_probe(int64_t iters, float *d_sink, int32_t workgroups, double *flops, void *stream)
+{
+    if (iters < 0 || iters > (1 << 24) || workgroups < 0 || workgroups > (1 << 16)) return SAMO_ERR_SIZE;
+    if (workgroups > 0 && !d_sink) return SAMO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(d_sink) & 3u) return SAMO_ERR_ALIGN;
+    if (flops) *flops = 2.0 * 32 * 32 * 16 * 8 * kMfmaRateWaves * (double)iters * (double)workgroups;
+    return hip_status(launch_mfma_rate(iters, d_sink, workgroups, as_stream(stream)));
+}
+
 }  // extern "C"

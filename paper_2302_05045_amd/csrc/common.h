@@ -166,6 +166,8 @@ struct WgradJob {
 hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s);
 // Function attributes of the weight-gradient kernels and the compute-unit count of the current device (once per device).
 hipError_t wgrad_configure(int *cus);
+constexpr int kMfmaRateWaves = 8;          // waves per workgroup of launch_mfma_rate, 8 MFMAs of 32 x 32 x 16 each per iteration
+hipError_t launch_mfma_rate(int64_t iters, float *sink, int workgroups, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, int64_t bytes, hipStream_t s);
 

@@ -467,6 +467,37 @@ __global__ void __launch_bounds__(kWgThreads, 2) wgrad_small_kernel(const WgradB
     gather_pass<OUT, kTile>(A, img, kEpiPitch, bounds, bounds + kTile, row0, col0);
 }
 
+// What the matrix units sustain with nothing to fetch: every wave issues eight independent
+// 32x32x16 fp16 MFMAs per iteration from registers (128 accumulators, the large tile's share), two
+// waves to a SIMD as in the kernels above.  The operands are ordinary fp16 values (a few set
+// mantissa and exponent bits, varying by lane), because the clock the chip holds under this load,
+// and with it the rate, depends on how many bits toggle.  Each workgroup leaves one float.
+__global__ void __launch_bounds__(kWgThreads, 2) mfma_rate_kernel(int64_t iters, float *__restrict__ sink)
+{
+    f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    half8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (_Float16)(0.37f * (float)((int)(threadIdx.x % 7) + i) - 1.f);
+        b[i] = (_Float16)(0.011f * (float)((int)(threadIdx.x % 5) + 2 * i) - 0.03f);
+    }
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[i][r];
+    sum += __shfl_xor(sum, 32, 64);
+    if (threadIdx.x == 0) sink[blockIdx.x] = sum;
+}
+
 // The LDS size above 64 KiB is a per-device attribute of a kernel: set once per device, where the
 // device's number of compute units is read too.
 hipError_t configure_once(int *cus)
@@ -495,6 +526,12 @@ hipError_t configure_once(int *cus)
 }  // namespace
 
 hipError_t wgrad_configure(int *cus) { return configure_once(cus); }
+
+hipError_t launch_mfma_rate(int64_t iters, float *sink, int workgroups, hipStream_t s)
+{
+    if (workgroups > 0) mfma_rate_kernel<<<dim3((unsigned)workgroups), dim3(kWgThreads), 0, s>>>(iters, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_wgrad(int out_kind, const WgradJob *jobs, int count, float inv_scale, int accumulate, hipStream_t s)
 {

@@ -84,6 +84,9 @@ def test_size_and_null_rejection():
     assert L.samo_gather_grads(FAKE, 8, None, 4, 1.0, FAKE, None) == samo.SAMO_ERR_NULL
     assert L.samo_gather_grads(None, 8, FAKE, 4, 1.0, FAKE, None) == samo.SAMO_ERR_NULL
     assert L.samo_stream_copy(FAKE, FAKE, 24, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_mfma_rate_probe(-1, FAKE, 1, None, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_mfma_rate_probe(1, FAKE, 1 << 17, None, None) == samo.SAMO_ERR_SIZE
+    assert L.samo_mfma_rate_probe(1, None, 1, None, None) == samo.SAMO_ERR_NULL
     assert L.samo_validate_index(FAKE, 4, 8, None, None, None) == samo.SAMO_ERR_NULL
 
 

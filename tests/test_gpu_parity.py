@@ -516,6 +516,19 @@ def test_stream_copy():
     assert torch.equal(dst2, src[:1000])
 
 
+def test_mfma_rate_probe_runs_and_counts_its_flops():
+    """The measurement aid beside the weight-gradient kernels: every workgroup does the same work, the
+    accumulated value grows with the iteration count, and the reported flops are those of the launch."""
+    sink = torch.zeros(5, dtype=torch.float32, device=DEV)
+    assert samo.samo_mfma_rate_probe(1, sink) == 5 * 8 * 8 * 2.0 * 32 * 32 * 16
+    one = sink.cpu().numpy().copy()
+    assert np.all(np.isfinite(one)) and one[0] != 0.0 and np.all(one == one[0])
+    assert samo.samo_mfma_rate_probe(64, sink) == 64 * 5 * 8 * 8 * 2.0 * 32 * 32 * 16
+    many = sink.cpu().numpy()
+    assert np.all(many == many[0]) and abs(many[0] - 64 * one[0]) <= 1e-4 * abs(64 * one[0])
+    assert samo.samo_mfma_rate_probe(0, sink[:0]) == 0.0
+
+
 def test_runs_on_a_side_stream():
     h = _layer(300000, 0.1, 55)
     d = DevLayer(h)
