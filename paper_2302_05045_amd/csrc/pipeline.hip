@@ -1122,20 +1122,23 @@ static int occ_tile_decompress()
 
 // Flat gather: one wave holds 1 KiB of indices and about 512 / keep bytes of dense lines in
 // flight; aim at ~75 KiB per CU.
-static int occ_flat_gather(int src, float keep, bool with_stats)
+static int occ_flat_gather(int out, int src, float keep, bool with_stats)
 {
     const int forced = knob(SAMO_KNOB_OCC_FLAT_GATHER, -1);
     const int forced_stats = knob(SAMO_KNOB_OCC_FLAT_STATS, -1);
     if (with_stats && forced_stats >= 0) return forced_stats;
     if (!with_stats && forced >= 0) return forced;
     if (src != kGradDense && src != kGradDense32) return with_stats ? 20 : 12;
-    const float per_wave = 1024.f + 512.f / (keep > 0.01f ? keep : 0.01f);
-    float t = 75.f * 1024.f / per_wave;
-    if (t < 13.f) t = 13.f;
+    // Waves per compute unit.  A wave's share of the dense gradient grows as the kept fraction
+    // falls, and with it the lines a wave has in flight; the measured optima on the GPT-3 2.7B
+    // masks are narrow (10 at 5 % kept, 14-15 at 10 %, 22-24 at 20 %: two waves off cost 5-8 %).
+    float t = 5.7f + 87.f * keep;
+    if (t < 10.f) t = 10.f;
     // the statistics add an arithmetic tail during which a wave has no memory traffic in flight:
-    // more waves have to be resident for the same traffic in flight
-    if (with_stats) t *= 1.6f;
-    return t > 32.f ? 0 : (int)(t + 0.5f);
+    // more waves have to be resident for the same traffic in flight, most when the wave also
+    // has a store to retire (optima: 15 / 24 / 28 with the fp16 store, 11 / 16 / 27 without)
+    if (with_stats) t *= (out == kOutNone) ? 1.3f : 1.5f;
+    return t > 30.f ? 0 : (int)(t + 0.5f);
 }
 
 static int occ_flat_step()
@@ -1220,7 +1223,7 @@ hipError_t launch_gather(int out, int src, const LaunchSet &ls, float inv_scale,
         return hipGetLastError();
     }
     const dim3 grid((unsigned)ls.wgs), block(kFlatThreads);
-    const int pad = lds_pad_for(occ_flat_gather(src, ls.keep, partials != nullptr), 2 * kChunk * 4);   // static: the exchange areas
+    const int pad = lds_pad_for(occ_flat_gather(out, src, ls.keep, partials != nullptr), 2 * kChunk * 4);   // static: the exchange areas
     if (out == kOutF32) gather_kernel<kOutF32><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     else if (out == kOutF16) gather_kernel<kOutF16><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
     else gather_kernel<kOutNone><<<grid, block, pad, s>>>(ls, src, inv_scale, accumulate, partials);
