@@ -1197,16 +1197,18 @@ hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntil
     return hipGetLastError();
 }
 
-static int occ_tile_step_fp32()
+static int occ_tile_step_fp32(float keep)
 {
-    return knob(SAMO_KNOB_OCC_TILE_STEP32, 3);        // a tile carries twice the dense bytes of the fp16 path: half the workgroups
-                                              // (measured at 90 %: 6.1 TB/s with 3 per CU, 5.6 with 2, 5.0 with 4)
+    // a tile carries twice the dense bytes of the fp16 path: half the workgroups (measured at 90 %:
+    // 6.1 TB/s with 3 per CU, 5.6 with 2, 5.0 with 4; at 95 %, where a tile is larger still, 6.3 with 2
+    // against 6.0 with 3)
+    return knob(SAMO_KNOB_OCC_TILE_STEP32, keep < 0.07f ? 2 : 3);
 }
 
 hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    const int pad = lds_pad_for(occ_tile_step_fp32(), kMaxTile * 4);
+    const int pad = lds_pad_for(occ_tile_step_fp32(ls.keep), kMaxTile * 4);
     tile_fp32_kernel<kTileThreads><<<dim3((unsigned)ls.wgs), dim3(kTileThreads), pad, s>>>(ls, factor, k, guard);
     return hipGetLastError();
 }
