@@ -74,12 +74,12 @@ inline samo_status hip_status(hipError_t e) { return e == hipSuccess ? SAMO_OK :
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 // Tile records of a layer in a plan: one per segment of an unpruned layer; for a pruned layer as
-// many as its total weight holds tiles of weight kTileCost.
-int64_t tile_records(const samo_layer &L)
+// many as its total weight holds tiles of weight tile_cost.
+int64_t tile_records(const samo_layer &L, int64_t tile_cost)
 {
     const int64_t nseg = ceil_div(L.n, kSeg);
     if (nseg == 0 || !L.seg_ptr) return nseg;
-    return ceil_div(kSegCost * nseg + kNnzCost * L.nnz, kTileCost);
+    return ceil_div(kSegCost * nseg + kNnzCost * L.nnz, tile_cost);
 }
 
 samo_status check_sizes(int64_t n, int64_t nnz)
@@ -278,6 +278,7 @@ LaunchSet single(const samo_layer &L, int64_t wgs)
     ls.wgs = wgs;
     ls.segs_per_tile = 1;
     ls.keep = L.n > 0 ? (float)((double)L.nnz / (double)L.n) : 1.f;
+    ls.max_segs = 1;
     return ls;
 }
 
@@ -288,6 +289,7 @@ LaunchSet single_tiles(const samo_layer &L)
     const int segs = single_layer_tile_segs(L.n, L.nnz, L.seg_ptr == nullptr);
     LaunchSet ls = single(L, ceil_div(ceil_div(L.n, kSeg), segs));
     ls.segs_per_tile = segs;
+    ls.max_segs = segs;
     return ls;
 }
 
@@ -523,7 +525,7 @@ inline size_t round_up_256(size_t x) { return (x + 255u) & ~(size_t)255u; }
 
 // Sizes of a plan's tables; validates the descriptors when `check` is set.
 struct PlanSizes {
-    int64_t ntiles = 0, nchunks = 0, n_total = 0, nnz_total = 0;
+    int64_t ntiles = 0, nchunks = 0, n_total = 0, nnz_total = 0, tile_cost = kTileCost;
     uint32_t buffers = kHasAll;
     size_t off_tile_start = 0, off_chunk_start = 0, off_tiles = 0, off_chunks = 0, bytes = 0;
 };
@@ -558,9 +560,10 @@ samo_status plan_sizes(const samo_layer *h_layers, int32_t num_layers, bool chec
         }
         z.n_total += L.n;
         z.nnz_total += L.nnz;
-        z.ntiles += tile_records(L);
         z.nchunks += ceil_div(L.nnz, kChunk);
     }
+    z.tile_cost = tile_cost_for(z.n_total, z.nnz_total);     // one tile weight for the whole plan, by its kept fraction
+    for (int32_t l = 0; l < num_layers; ++l) z.ntiles += tile_records(h_layers[l], z.tile_cost);
     if (z.ntiles > kMaxN || z.nchunks > kMaxN) return SAMO_ERR_SIZE;
     size_t at = round_up_256((size_t)num_layers * sizeof(samo_layer));
     z.off_tile_start = at;
@@ -619,7 +622,7 @@ samo_status samo_plan_init(const samo_layer *h_layers, int32_t num_layers, void 
             b.layer[k] = h_layers[l];
             b.tile_start[k] = tile_at;
             b.chunk_start[k] = chunk_at;
-            tile_at += tile_records(h_layers[l]);
+            tile_at += tile_records(h_layers[l], z.tile_cost);
             chunk_at += ceil_div(h_layers[l].nnz, kChunk);
         }
         b.count = k;
@@ -627,7 +630,7 @@ samo_status samo_plan_init(const samo_layer *h_layers, int32_t num_layers, void 
         b.chunk_start[k] = chunk_at;
         if (launch_plan_write(b, t, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
     } while (l < num_layers);
-    if (launch_plan_records(t, num_layers, z.ntiles, z.nchunks, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
+    if (launch_plan_records(t, num_layers, z.ntiles, z.nchunks, z.tile_cost, as_stream(stream)) != hipSuccess) return SAMO_ERR_HIP;
 
     plan->d_layers = t.layers;
     plan->d_tiles = t.tiles;
@@ -661,6 +664,7 @@ LaunchSet tiles_of(const samo_plan *plan)
     ls.wgs = plan->num_tiles;
     ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
+    ls.max_segs = tile_cost_segs(tile_cost_for(plan->n_total, plan->nnz_total));   // as samo_plan_init cut the tiles
     return ls;
 }
 

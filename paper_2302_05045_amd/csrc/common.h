@@ -12,7 +12,8 @@ namespace samo {
 // whole segments of a layer of about equal weight kTileCost, where a segment weighs kSegCost plus
 // kNnzCost per kept element: at 90-95 % pruning that is about 4 segments (4096 dense elements, 16
 // per thread — 8 or 32 per thread lose 10-15 %), 3 at 80 %, 2 at 50 %, 5-6 where nothing is kept,
-// one segment per workgroup in an unpruned layer.  The weights follow the fused step's traffic
+// one segment per workgroup in an unpruned layer; a model that keeps under 7 % is cut with one and a
+// half times the weight (kTileCostSparse), 6-7 segments at 95 % pruning.  The weights follow the fused step's traffic
 // (4 bytes per dense element, 28 per kept one) with the dense side weighted up: swept over
 // (4096..16384, 8..28, 20K..64K) on the GPT shapes, this choice is within 1 % of the best at 80, 90
 // and 95 % uniform pruning and 6 % ahead of fixed 4096-element tiles on row-clustered masks.  Even
@@ -25,10 +26,22 @@ constexpr int kExpandThreads = 128;     // expansion only: little read traffic p
                                         // per compute unit (+15 % over 256 threads; the step kernels lose with 128)
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
 constexpr int64_t kTileCost = 32768;    // target weight of one tile workgroup
+constexpr int64_t kTileCostSparse = 49152;   // the same for a model with less than kSparseKeep of its elements kept: the
+                                        // kernels that do not read the dense gradient move too few bytes per tile there
+                                        // for the workgroups a compute unit holds (measured at 95 % pruning: the
+                                        // compressed-gradient step 0.755 against 0.705 of peak, the expansion 0.747
+                                        // against 0.718, the fused step level)
+constexpr double kSparseKeep = 0.07;
 constexpr int64_t kSegCost = 6144;      // weight of a segment's dense side (fp16 gradient lines read, fp16 weights written)
 constexpr int64_t kNnzCost = 24;        // weight of a kept element (idx, p, m, v read; p, m, v written)
-constexpr int kMaxTileSegs = (int)((kTileCost + kSegCost - 1) / kSegCost);   // reached where nothing is kept
-constexpr int kMaxTile = kMaxTileSegs * kSeg;   // dense elements of the largest tile (fp16 image in LDS)
+constexpr int kMaxTileSegs = (int)((kTileCostSparse + kSegCost - 1) / kSegCost);   // of any tile: reached where nothing is kept
+// The tile weight of a model (a plan, or a layer launched by itself) and the segments its heaviest
+// tile can hold: the size of the workgroups' LDS image, which is requested at launch.
+inline int64_t tile_cost_for(int64_t n, int64_t nnz)
+{
+    return (n > 0 && (double)nnz < kSparseKeep * (double)n) ? kTileCostSparse : kTileCost;
+}
+inline int tile_cost_segs(int64_t cost) { return (int)((cost + kSegCost - 1) / kSegCost); }
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
 constexpr int kStatReduceGrid = 1024;    // workgroups of the first level of the gradient-statistics reduction
@@ -119,6 +132,7 @@ struct LaunchSet {
     int64_t wgs;
     int segs_per_tile;   // single-layer tile launches: workgroup b owns segments [b * this, (b + 1) * this)
     float keep;          // kept fraction nnz / n of the work (plan average); steers the flat kernels' occupancy target
+    int max_segs;        // tile launches: segments the workgroups' LDS image holds (no tile of the launch has more)
 };
 // Segments per tile of a single-layer launch, from the layer's average density.
 int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense);
@@ -140,7 +154,8 @@ struct PlanTables {
 };
 hipError_t launch_plan_write(const PlanBatch &batch, const PlanTables &t, hipStream_t s);
 // Fills the tile and chunk records of every layer (reads the tables plan_write_kernel wrote and the layers' seg_ptr).
-hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, hipStream_t s);
+hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, int64_t tile_cost,
+                               hipStream_t s);
 hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float inv_scale, const OptK &k,
                        const GuardK &guard, hipStream_t s);
 hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s);

@@ -440,7 +440,8 @@ template <int MODE, int GSRC, int OPT, int T>
 __global__ void __launch_bounds__(T)
 tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guard)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds_w[kMaxTile];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_image[];      // ls.max_segs segments of fp16 (and the occupancy padding)
+    uint16_t *lds_w = reinterpret_cast<uint16_t *>(lds_image);
     constexpr bool kExchange = MODE == kModeStep && GSRC == kGradDense;
     __shared__ __attribute__((aligned(16))) int32_t xj[kExchange ? T * 4 : 4];      // per wave: 256 positions on their way to the gather
     __shared__ __attribute__((aligned(16))) uint16_t xg[kExchange ? T * 4 : 8];     // and the 256 gradient values on their way back
@@ -450,6 +451,7 @@ tile_kernel(const LaunchSet ls, float inv_scale, const OptK k, const GuardK guar
     samo_layer L;
     int s0, nsegs;
     pick_tile(ls, &L, &s0, &nsegs);
+    if (nsegs > ls.max_segs) nsegs = ls.max_segs;   // a record never holds more; the image must not be overrun whatever it says
     if (nsegs <= 0) return;                   // uniform per workgroup: a record without segments
     const int64_t base = (int64_t)s0 * kSeg;
     const int64_t rest = L.n - base;
@@ -560,13 +562,15 @@ template <int T>
 __global__ void __launch_bounds__(T)
 tile_fp32_kernel(const LaunchSet ls, float factor, const OptK k, const GuardK guard)
 {
-    __shared__ __attribute__((aligned(16))) float lds_f[kMaxTile];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_image[];      // ls.max_segs segments of fp32 (and the occupancy padding)
+    float *lds_f = reinterpret_cast<float *>(lds_image);
     bool skip;
     const float coef = guard_coef(guard, &skip);
     if (skip) return;
     samo_layer L;
     int s0, nsegs;
     pick_tile(ls, &L, &s0, &nsegs);
+    if (nsegs > ls.max_segs) nsegs = ls.max_segs;
     if (nsegs <= 0) return;
     const int64_t base = (int64_t)s0 * kSeg;
     const int64_t rest = L.n - base;
@@ -1000,10 +1004,10 @@ flat_step_kernel(const LaunchSet ls, const OptK k, const GuardK guard)
 // ------------------------------------------------------------------ tile records of a plan
 // Record k of a pruned layer owns the segments s whose running weight C(s) = kSegCost * s +
 // kNnzCost * seg_ptr[s] (the weight of everything before s) falls in
-// [k * kTileCost, (k + 1) * kTileCost): C is increasing, so the records partition the layer, each
-// weighs about kTileCost, and none holds more than kMaxTileSegs segments.  seg_ptr is the prefix
+// [k * tile_cost, (k + 1) * tile_cost): C is increasing, so the records partition the layer, each
+// weighs about tile_cost, and none holds more than tile_cost_segs(tile_cost) segments.  seg_ptr is the prefix
 // sum already, so a record's bounds are two binary searches, independent of every other record.
-// A record can be empty (a single segment heavier than kTileCost spans two buckets).  An unpruned
+// A record can be empty (a single segment heavier than tile_cost spans two buckets).  An unpruned
 // layer gets one record per segment.
 __device__ __forceinline__ int64_t first_seg_with_cost(const int32_t *__restrict__ seg_ptr, int64_t nseg, int64_t target)
 {
@@ -1018,7 +1022,7 @@ __device__ __forceinline__ int64_t first_seg_with_cost(const int32_t *__restrict
 
 __global__ void __launch_bounds__(kThreads)
 build_tile_recs_kernel(const samo_layer *__restrict__ layers, const int64_t *__restrict__ rec_start, int num_layers,
-                       int64_t total, WgRec *__restrict__ recs)
+                       int64_t total, int64_t tile_cost, int max_segs, WgRec *__restrict__ recs)
 {
     const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (t >= total) return;
@@ -1033,11 +1037,11 @@ build_tile_recs_kernel(const samo_layer *__restrict__ layers, const int64_t *__r
     const int64_t nseg = (L.n + kSeg - 1) / kSeg;
     int64_t first = k, count = 1;
     if (L.seg_ptr != nullptr) {
-        first = (k == 0) ? 0 : first_seg_with_cost(L.seg_ptr, nseg, k * kTileCost);
-        const int64_t end = (k + 1 == nrec) ? nseg : first_seg_with_cost(L.seg_ptr, nseg, (k + 1) * kTileCost);
+        first = (k == 0) ? 0 : first_seg_with_cost(L.seg_ptr, nseg, k * tile_cost);
+        const int64_t end = (k + 1 == nrec) ? nseg : first_seg_with_cost(L.seg_ptr, nseg, (k + 1) * tile_cost);
         count = end - first;
         if (count < 0) count = 0;                       // only with a seg_ptr that is not a prefix sum:
-        if (count > kMaxTileSegs) count = kMaxTileSegs; // stay inside the workgroup's LDS image
+        if (count > max_segs) count = max_segs;         // stay inside the workgroup's LDS image
     }
     recs[t].layer = lo;
     recs[t].local = (uint32_t)first | ((uint32_t)count << kRecSegShift);
@@ -1104,6 +1108,12 @@ static int lds_pad_for(int target_wgs, int static_bytes)
     const int want = (kLdsPerCu / (target_wgs + 1) + kLdsPerCu / target_wgs) / 2;
     return want > static_bytes ? want - static_bytes : 0;
 }
+// Dynamic LDS of a tile launch: the image of the largest tile, or more where the occupancy target asks for it.
+static int tile_lds_request(int target_wgs, int static_bytes, int image_bytes)
+{
+    const int pad = lds_pad_for(target_wgs, static_bytes);
+    return pad > image_bytes ? pad : image_bytes;
+}
 
 static int occ_tile_step(int gsrc, int opt, float keep)
 {
@@ -1111,7 +1121,8 @@ static int occ_tile_step(int gsrc, int opt, float keep)
     // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling at
     // 90 % pruning and above (8 workgroups: 0.75 of peak against 0.72 with 6), while at 80 % the
     // in-place streams are over half the traffic and 6 is the optimum again (0.74 against 0.68 with 8)
-    if (gsrc == kGradDense) return knob(SAMO_KNOB_OCC_TILE_STEP, 6);
+    // (5 where the model keeps so little that its tiles have the larger weight: 0.80 against 0.72 with 6)
+    if (gsrc == kGradDense) return knob(SAMO_KNOB_OCC_TILE_STEP, keep < (float)kSparseKeep ? 5 : 6);
     return knob(SAMO_KNOB_OCC_TILE_C16, keep > 0.15f ? 6 : 0);
 }
 
@@ -1154,10 +1165,12 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
                        const GuardK &guard, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    // static LDS of the kernel: the tile's fp16 image, and for the step that gathers the dense gradient
-    // the waves' exchange areas
-    const int static_lds = kMaxTile * 2 + (mode == kModeStep && gsrc == kGradDense ? kTileThreads * 4 * 6 : 0);
-    const int pad = lds_pad_for(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt, ls.keep), static_lds);
+    if (ls.max_segs < 1 || ls.max_segs > kMaxTileSegs) return hipErrorInvalidValue;
+    // static LDS of the kernel: for the step that gathers the dense gradient the waves' exchange areas;
+    // dynamic: the tile's fp16 image
+    const int static_lds = mode == kModeStep && gsrc == kGradDense ? kTileThreads * 4 * 6 : 32;
+    const int pad = tile_lds_request(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt, ls.keep),
+                                     static_lds, ls.max_segs * kSeg * 2);
     if (mode == kModeDecompress) {
         tile_kernel<kModeDecompress, kGradDense, kOptAdam, kExpandThreads><<<dim3((unsigned)ls.wgs), dim3(kExpandThreads), pad, s>>>(ls, inv_scale, k,
                                                                                                                           guard);
@@ -1177,8 +1190,9 @@ int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense)
 {
     if (dense || n <= 0) return 1;
     const double per_seg = (double)kSegCost + (double)kNnzCost * (double)kSeg * ((double)nnz / (double)n);
-    const int segs = (int)((double)kTileCost / per_seg + 0.5);
-    return segs < 1 ? 1 : (segs > kMaxTileSegs ? kMaxTileSegs : segs);
+    const int64_t cost = tile_cost_for(n, nnz);
+    const int segs = (int)((double)cost / per_seg + 0.5);
+    return segs < 1 ? 1 : (segs > tile_cost_segs(cost) ? tile_cost_segs(cost) : segs);
 }
 
 hipError_t launch_plan_write(const PlanBatch &batch, const PlanTables &t, hipStream_t s)
@@ -1187,11 +1201,12 @@ hipError_t launch_plan_write(const PlanBatch &batch, const PlanTables &t, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, hipStream_t s)
+hipError_t launch_plan_records(const PlanTables &t, int num_layers, int64_t ntiles, int64_t nchunks, int64_t tile_cost,
+                               hipStream_t s)
 {
     if (ntiles > 0)
         build_tile_recs_kernel<<<dim3((unsigned)ceil_div(ntiles, kThreads)), dim3(kThreads), 0, s>>>(
-            t.layers, t.tile_start, num_layers, ntiles, t.tiles);
+            t.layers, t.tile_start, num_layers, ntiles, tile_cost, tile_cost_segs(tile_cost), t.tiles);
     if (nchunks > 0)
         build_chunk_recs_kernel<<<dim3((unsigned)ceil_div(nchunks, kThreads)), dim3(kThreads), 0, s>>>(
             t.chunk_start, num_layers, nchunks, t.chunks);
@@ -1203,13 +1218,14 @@ static int occ_tile_step_fp32(float keep)
     // a tile carries twice the dense bytes of the fp16 path: half the workgroups (measured at 90 %:
     // 6.1 TB/s with 3 per CU, 5.6 with 2, 5.0 with 4; at 95 %, where a tile is larger still, 6.3 with 2
     // against 6.0 with 3)
-    return knob(SAMO_KNOB_OCC_TILE_STEP32, keep < 0.07f ? 2 : 3);
+    return knob(SAMO_KNOB_OCC_TILE_STEP32, keep < (float)kSparseKeep ? 2 : 3);
 }
 
 hipError_t launch_tile_fp32(const LaunchSet &ls, float factor, const OptK &k, const GuardK &guard, hipStream_t s)
 {
     if (ls.wgs <= 0) return hipSuccess;
-    const int pad = lds_pad_for(occ_tile_step_fp32(ls.keep), kMaxTile * 4);
+    if (ls.max_segs < 1 || ls.max_segs > kMaxTileSegs) return hipErrorInvalidValue;
+    const int pad = tile_lds_request(occ_tile_step_fp32(ls.keep), 0, ls.max_segs * kSeg * 4);
     tile_fp32_kernel<kTileThreads><<<dim3((unsigned)ls.wgs), dim3(kTileThreads), pad, s>>>(ls, factor, k, guard);
     return hipGetLastError();
 }

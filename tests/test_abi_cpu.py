@@ -163,6 +163,11 @@ def test_plan_workspace_size_follows_the_layer_sizes():
     chunks = -(-100_000 // 256) + -(-5000 // 256)
     pad = lambda x: -(-x // 256) * 256
     assert need.value == pad(2 * ctypes.sizeof(samo.LayerDesc)) + 2 * pad(3 * 8) + pad(8 * tiles) + pad(8 * chunks)
+    # a model that keeps less than 7 % of its elements is cut into tiles of one and a half times the weight
+    d[0].nnz, d[1].n, d[1].nnz = 50_000, 0, 0
+    assert L.samo_plan_workspace_bytes(d, 2, ctypes.byref(need)) == samo.SAMO_OK
+    tiles = -(-(6144 * 1024 + 24 * 50_000) // 49152)
+    assert need.value == pad(2 * ctypes.sizeof(samo.LayerDesc)) + 2 * pad(3 * 8) + pad(8 * tiles) + pad(8 * -(-50_000 // 256))
     assert L.samo_plan_workspace_bytes(d, 0, ctypes.byref(need)) == samo.SAMO_OK and need.value == 2 * 256
     assert samo.samo_index_workspace_bytes(1025) == 12
     assert L.samo_static_scratch_bytes() == 16 << 20

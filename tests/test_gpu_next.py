@@ -15,7 +15,13 @@ SIZES = [1, 3, 4, 5, 255, 256, 257, 4095, 4096, 4097, 100003]
 
 
 def _layer(n, keep, seed, dense=False):
-    mask = np.ones(n, np.uint8) if dense else si.bernoulli_mask(n, keep, seed)
+    if keep < 0:                              # -keep of the elements, in four dense stretches
+        mask = np.zeros(n, np.uint8)
+        run = max(1, int(-keep * n / 4))
+        for start in np.random.default_rng(seed).integers(0, n - run, 4):
+            mask[start:start + run] = 1
+    else:
+        mask = np.ones(n, np.uint8) if dense else si.bernoulli_mask(n, keep, seed)
     return HostLayer(n, mask, si.weights(n, seed), seed, dense=dense)
 
 
@@ -117,9 +123,9 @@ def test_fused_sgd_step(n, dense):
 
 
 # ------------------------------------------------------------------ batched: DP-shaped split, statistics, guard
-def _model(with_gc=True):
-    specs = [(3 * 4096, 0.1, False), (1, 1.0, False), (5000, 0.0, False), (4097, 0.3, False), (100003, 0.05, False),
-             (30001, 1.0, True), (40000, 0.97, False)]
+def _model(with_gc=True, specs=None):
+    specs = specs or [(3 * 4096, 0.1, False), (1, 1.0, False), (5000, 0.0, False), (4097, 0.3, False), (100003, 0.05, False),
+                      (30001, 1.0, True), (40000, 0.97, False)]
     hosts = [_layer(n, keep, 900 + i, dense) for i, (n, keep, dense) in enumerate(specs)]
     devs = [DevLayer(h, with_gc=with_gc, with_gc16=True) for h in hosts]
     return hosts, devs, samo.Plan([d.layer() for d in devs])
@@ -133,6 +139,37 @@ def _ref_stats(hosts, t, extra=None):
         total += oracle.sum_squares(gc)
         bad |= oracle.has_nonfinite(gc)
     return total, bad
+
+
+def test_a_model_that_keeps_under_seven_percent_is_cut_into_heavier_tiles():
+    """Below 7 % kept overall a plan's tiles weigh one and a half times as much (up to eight segments,
+    a larger LDS image): every tile kernel on such a plan, with a layer whose kept elements sit in a
+    few dense stretches, an empty one and sizes that end inside a segment."""
+    specs = [(200_003, 0.05, False), (9 * 1024, 0.0, False), (65_536, -0.03, False), (50_000, 0.06, False)]
+    hosts, devs, plan = _model(specs=specs)
+    n_total, nnz_total = plan.totals()
+    assert nnz_total < 0.07 * n_total
+    assert plan.num_tiles == sum(-(-(6144 * -(-h.n // 1024) + 24 * h.idx.shape[0]) // 49152) for h in hosts)
+    for t in (1, 2, 3):
+        for d, h in zip(devs, hosts):
+            d.set_grads(h.grads(t))
+            d.w.fill_(float("nan"))
+        if t == 1:
+            plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        elif t == 2:
+            plan.samo_gather_fp16_batched(False, INV)
+            plan.samo_adam_expand_batched(INV, samo.adam_cfg(t, **si.ADAM))
+        else:
+            plan.samo_gather_batched(INV)
+            plan.samo_adam_batched(samo.adam_cfg(t, **si.ADAM))
+            plan.samo_decompress_batched()
+        for d, h in zip(devs, hosts):
+            oracle.step(h.grads(t), h.n, h.idx, h.p, h.m, h.v, INV, OCFG, t)
+            got_p = d.p.cpu().numpy()
+            assert_close(got_p, h.p, "p t=%d" % t)
+            assert_close(d.m.cpu().numpy(), h.m, "m t=%d" % t)
+            assert_close(d.v.cpu().numpy(), h.v, "v t=%d" % t)
+            assert np.array_equal(host_bits(d.w), oracle.decompress(got_p, h.idx, h.n)), "w t=%d" % t
 
 
 def test_dp_split_batched_with_statistics():
