@@ -253,6 +253,9 @@ samo_status samo_fused_step_fp32(const float *d_g32, float *d_w32, int64_t n, co
  *
  * samo_plan_workspace_bytes: the workspace size for these layers (host
  *   arithmetic on n, nnz and on whether seg_ptr is NULL; nothing is dereferenced).
+ *   It is an upper bound: samo_plan_init may need a little less (a model that
+ *   keeps under 7 % of its elements is cut into heavier tiles when its dense
+ *   side is fp16 than when it is fp32, and the size is that of the lighter ones).
  * samo_plan_init: validates h_layers (a HOST array of descriptors holding
  *   DEVICE pointers), then enqueues on `stream` the kernels that write the
  *   tables into d_workspace (the descriptors travel in kernel arguments, a few
@@ -455,6 +458,10 @@ samo_status samo_mfma_rate_probe(int64_t iters, float *d_sink, int32_t workgroup
  *                        compute units and 128 x 128 for a remainder of at most half a round).
  *   SAMO_KNOB_WGRAD_ROUND  test aid: the number of tiles taken as one round in that rule, in
  *                        place of the device's compute-unit count.
+ *   SAMO_KNOB_TILE_COST    the weight of a plan's tiles in units of 1024 (6 .. 96; default 32, or 48 for a
+ *                        model that keeps under 7 % of its elements).  Read by samo_plan_workspace_bytes,
+ *                        samo_plan_init and every launch on a plan: set it before the plan is made and
+ *                        leave it while the plan is in use.
  * Returns SAMO_ERR_ARG for an unknown knob. */
 enum {
     SAMO_KNOB_OCC_TILE_STEP = 0,
@@ -468,7 +475,8 @@ enum {
     SAMO_KNOB_WGRAD_TILE = 8,
     SAMO_KNOB_WGRAD_ROUND = 9,
     SAMO_KNOB_INDEX_PASSES = 10,
-    SAMO_KNOB_COUNT = 11
+    SAMO_KNOB_TILE_COST = 11,
+    SAMO_KNOB_COUNT = 12
 };
 #define SAMO_KNOB_DEFAULT (-1)
 samo_status samo_debug_set(int32_t knob, int32_t value);

@@ -31,7 +31,7 @@ SAMO_OK = 0
 # samo_debug_set knobs
 (KNOB_OCC_TILE_STEP, KNOB_OCC_TILE_STEP32, KNOB_OCC_TILE_DECOMP, KNOB_OCC_TILE_C16, KNOB_OCC_FLAT_GATHER,
  KNOB_OCC_FLAT_STATS, KNOB_OCC_FLAT_STEP, KNOB_INDEX_SPIN_LIMIT, KNOB_WGRAD_TILE, KNOB_WGRAD_ROUND,
- KNOB_INDEX_PASSES) = range(11)
+ KNOB_INDEX_PASSES, KNOB_TILE_COST) = range(12)
 KNOB_DEFAULT = -1
 
 

@@ -286,7 +286,7 @@ LaunchSet single(const samo_layer &L, int64_t wgs)
 // layer's average density (the per-region balance of a plan needs seg_ptr's contents).
 LaunchSet single_tiles(const samo_layer &L)
 {
-    const int segs = single_layer_tile_segs(L.n, L.nnz, L.seg_ptr == nullptr);
+    const int segs = single_layer_tile_segs(L.n, L.nnz, L.seg_ptr == nullptr, L.w32 != nullptr);
     LaunchSet ls = single(L, ceil_div(ceil_div(L.n, kSeg), segs));
     ls.segs_per_tile = segs;
     ls.max_segs = segs;
@@ -562,7 +562,13 @@ samo_status plan_sizes(const samo_layer *h_layers, int32_t num_layers, bool chec
         z.nnz_total += L.nnz;
         z.nchunks += ceil_div(L.nnz, kChunk);
     }
-    z.tile_cost = tile_cost_for(z.n_total, z.nnz_total);     // one tile weight for the whole plan, by its kept fraction
+    // one tile weight for the whole plan, by its kept fraction and the width of its dense side; when only
+    // the sizes are asked for (the arrays need not be known yet), the lighter of the two: more records
+    z.tile_cost = tile_cost_for(z.n_total, z.nnz_total, (z.buffers & kHasW32) != 0);
+    if (!check) {
+        const int64_t other = tile_cost_for(z.n_total, z.nnz_total, false);
+        if (other < z.tile_cost) z.tile_cost = other;
+    }
     for (int32_t l = 0; l < num_layers; ++l) z.ntiles += tile_records(h_layers[l], z.tile_cost);
     if (z.ntiles > kMaxN || z.nchunks > kMaxN) return SAMO_ERR_SIZE;
     size_t at = round_up_256((size_t)num_layers * sizeof(samo_layer));
@@ -664,7 +670,7 @@ LaunchSet tiles_of(const samo_plan *plan)
     ls.wgs = plan->num_tiles;
     ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
-    ls.max_segs = tile_cost_segs(tile_cost_for(plan->n_total, plan->nnz_total));   // as samo_plan_init cut the tiles
+    ls.max_segs = tile_cost_segs(tile_cost_for(plan->n_total, plan->nnz_total, (plan->buffers & kHasW32) != 0));   // as samo_plan_init cut the tiles
     return ls;
 }
 

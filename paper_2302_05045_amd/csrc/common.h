@@ -10,10 +10,10 @@ namespace samo {
 
 // Launch shapes, chosen by measurement on MI355X.  A tile workgroup (256 threads) owns a run of
 // whole segments of a layer of about equal weight kTileCost, where a segment weighs kSegCost plus
-// kNnzCost per kept element: at 90-95 % pruning that is about 4 segments (4096 dense elements, 16
+// kNnzCost per kept element: at 90 % pruning that is about 4 segments (4096 dense elements, 16
 // per thread — 8 or 32 per thread lose 10-15 %), 3 at 80 %, 2 at 50 %, 5-6 where nothing is kept,
-// one segment per workgroup in an unpruned layer; a model that keeps under 7 % is cut with one and a
-// half times the weight (kTileCostSparse), 6-7 segments at 95 % pruning.  The weights follow the fused step's traffic
+// one segment per workgroup in an unpruned layer; a model that keeps under 7 % is cut with
+// twice the weight (kTileCostSparse), 8-9 segments at 95 % pruning.  The weights follow the fused step's traffic
 // (4 bytes per dense element, 28 per kept one) with the dense side weighted up: swept over
 // (4096..16384, 8..28, 20K..64K) on the GPT shapes, this choice is within 1 % of the best at 80, 90
 // and 95 % uniform pruning and 6 % ahead of fixed 4096-element tiles on row-clustered masks.  Even
@@ -26,20 +26,26 @@ constexpr int kExpandThreads = 128;     // expansion only: little read traffic p
                                         // per compute unit (+15 % over 256 threads; the step kernels lose with 128)
 constexpr int kSeg = SAMO_SEG_ELEMS;    // dense elements per seg_ptr entry
 constexpr int64_t kTileCost = 32768;    // target weight of one tile workgroup
-constexpr int64_t kTileCostSparse = 49152;   // the same for a model with less than kSparseKeep of its elements kept: the
+constexpr int64_t kTileCostSparse = 65536;   // the same for a model with less than kSparseKeep of its elements kept: the
                                         // kernels that do not read the dense gradient move too few bytes per tile there
-                                        // for the workgroups a compute unit holds (measured at 95 % pruning: the
-                                        // compressed-gradient step 0.755 against 0.705 of peak, the expansion 0.747
-                                        // against 0.718, the fused step level)
+                                        // for the workgroups a compute unit holds (measured at 95 % pruning, weights
+                                        // 32K / 48K / 64K: the compressed-gradient step 0.705 / 0.754 / 0.765 of peak,
+                                        // the expansion 0.716 / 0.747 / 0.765, the fused step 0.81 throughout)
+constexpr int64_t kTileCostSparse32 = 49152; // ... where the dense side is fp32 (single-precision SAMO): 0.78 / 0.80 / 0.73
 constexpr double kSparseKeep = 0.07;
 constexpr int64_t kSegCost = 6144;      // weight of a segment's dense side (fp16 gradient lines read, fp16 weights written)
 constexpr int64_t kNnzCost = 24;        // weight of a kept element (idx, p, m, v read; p, m, v written)
-constexpr int kMaxTileSegs = (int)((kTileCostSparse + kSegCost - 1) / kSegCost);   // of any tile: reached where nothing is kept
+constexpr int64_t kTileCostMax = 98304;   // what SAMO_KNOB_TILE_COST may ask for
+constexpr int kMaxTileSegs = (int)((kTileCostMax + kSegCost - 1) / kSegCost);   // of any tile: reached where nothing is kept
 // The tile weight of a model (a plan, or a layer launched by itself) and the segments its heaviest
 // tile can hold: the size of the workgroups' LDS image, which is requested at launch.
-inline int64_t tile_cost_for(int64_t n, int64_t nnz)
+int knob(int which, int fallback);
+inline int64_t tile_cost_for(int64_t n, int64_t nnz, bool dense_fp32)
 {
-    return (n > 0 && (double)nnz < kSparseKeep * (double)n) ? kTileCostSparse : kTileCost;
+    const int64_t forced = (int64_t)knob(SAMO_KNOB_TILE_COST, 0) * 1024;      // tuning aid
+    if (forced >= kSegCost && forced <= kTileCostMax) return forced;
+    if (n > 0 && (double)nnz < kSparseKeep * (double)n) return dense_fp32 ? kTileCostSparse32 : kTileCostSparse;
+    return kTileCost;
 }
 inline int tile_cost_segs(int64_t cost) { return (int)((cost + kSegCost - 1) / kSegCost); }
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
@@ -135,7 +141,7 @@ struct LaunchSet {
     int max_segs;        // tile launches: segments the workgroups' LDS image holds (no tile of the launch has more)
 };
 // Segments per tile of a single-layer launch, from the layer's average density.
-int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense);
+int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense, bool dense_fp32);
 // Up to kPlanBatchLayers layer descriptors of a plan with the starts of their tile and chunk records,
 // passed to plan_write_kernel by value: the host table reaches the device without a copy.
 constexpr int kPlanBatchLayers = 24;

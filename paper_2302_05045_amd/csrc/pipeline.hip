@@ -1121,14 +1121,15 @@ static int occ_tile_step(int gsrc, int opt, float keep)
     // with a compressed gradient (half the bytes per workgroup) every wave slot is worth filling at
     // 90 % pruning and above (8 workgroups: 0.75 of peak against 0.72 with 6), while at 80 % the
     // in-place streams are over half the traffic and 6 is the optimum again (0.74 against 0.68 with 8)
-    // (5 where the model keeps so little that its tiles have the larger weight: 0.80 against 0.72 with 6)
-    if (gsrc == kGradDense) return knob(SAMO_KNOB_OCC_TILE_STEP, keep < (float)kSparseKeep ? 5 : 6);
-    return knob(SAMO_KNOB_OCC_TILE_C16, keep > 0.15f ? 6 : 0);
+    // (where the model keeps so little that its tiles have twice the weight: 4, and 6 with the compressed gradient)
+    const bool sparse = keep < (float)kSparseKeep;
+    if (gsrc == kGradDense) return knob(SAMO_KNOB_OCC_TILE_STEP, sparse ? (opt == kOptSgd ? 3 : 4) : 6);
+    return knob(SAMO_KNOB_OCC_TILE_C16, (sparse || keep > 0.15f) ? 6 : 0);
 }
 
-static int occ_tile_decompress()
+static int occ_tile_decompress(float keep)
 {
-    return knob(SAMO_KNOB_OCC_TILE_DECOMP, 0);
+    return knob(SAMO_KNOB_OCC_TILE_DECOMP, keep < (float)kSparseKeep ? 8 : 0);
 }
 
 // Flat gather: one wave holds 1 KiB of indices and about 512 / keep bytes of dense lines in
@@ -1169,7 +1170,7 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
     // static LDS of the kernel: for the step that gathers the dense gradient the waves' exchange areas;
     // dynamic: the tile's fp16 image
     const int static_lds = mode == kModeStep && gsrc == kGradDense ? kTileThreads * 4 * 6 : 32;
-    const int pad = tile_lds_request(mode == kModeDecompress ? occ_tile_decompress() : occ_tile_step(gsrc, opt, ls.keep),
+    const int pad = tile_lds_request(mode == kModeDecompress ? occ_tile_decompress(ls.keep) : occ_tile_step(gsrc, opt, ls.keep),
                                      static_lds, ls.max_segs * kSeg * 2);
     if (mode == kModeDecompress) {
         tile_kernel<kModeDecompress, kGradDense, kOptAdam, kExpandThreads><<<dim3((unsigned)ls.wgs), dim3(kExpandThreads), pad, s>>>(ls, inv_scale, k,
@@ -1186,11 +1187,11 @@ hipError_t launch_tile(int mode, int gsrc, int opt, const LaunchSet &ls, float i
     return hipGetLastError();
 }
 
-int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense)
+int single_layer_tile_segs(int64_t n, int64_t nnz, bool dense, bool dense_fp32)
 {
     if (dense || n <= 0) return 1;
     const double per_seg = (double)kSegCost + (double)kNnzCost * (double)kSeg * ((double)nnz / (double)n);
-    const int64_t cost = tile_cost_for(n, nnz);
+    const int64_t cost = tile_cost_for(n, nnz, dense_fp32);
     const int segs = (int)((double)cost / per_seg + 0.5);
     return segs < 1 ? 1 : (segs > tile_cost_segs(cost) ? tile_cost_segs(cost) : segs);
 }

@@ -163,7 +163,8 @@ def test_plan_workspace_size_follows_the_layer_sizes():
     chunks = -(-100_000 // 256) + -(-5000 // 256)
     pad = lambda x: -(-x // 256) * 256
     assert need.value == pad(2 * ctypes.sizeof(samo.LayerDesc)) + 2 * pad(3 * 8) + pad(8 * tiles) + pad(8 * chunks)
-    # a model that keeps less than 7 % of its elements is cut into tiles of one and a half times the weight
+    # a model that keeps less than 7 % of its elements is cut into heavier tiles: 65536, or 49152 with an fp32 dense
+    # side; the size reported before the arrays are known is that of the lighter ones
     d[0].nnz, d[1].n, d[1].nnz = 50_000, 0, 0
     assert L.samo_plan_workspace_bytes(d, 2, ctypes.byref(need)) == samo.SAMO_OK
     tiles = -(-(6144 * 1024 + 24 * 50_000) // 49152)

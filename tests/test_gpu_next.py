@@ -142,14 +142,14 @@ def _ref_stats(hosts, t, extra=None):
 
 
 def test_a_model_that_keeps_under_seven_percent_is_cut_into_heavier_tiles():
-    """Below 7 % kept overall a plan's tiles weigh one and a half times as much (up to eight segments,
-    a larger LDS image): every tile kernel on such a plan, with a layer whose kept elements sit in a
+    """Below 7 % kept overall a plan's tiles weigh twice as much (up to eleven segments, a larger LDS
+    image): every tile kernel on such a plan, with a layer whose kept elements sit in a
     few dense stretches, an empty one and sizes that end inside a segment."""
     specs = [(200_003, 0.05, False), (9 * 1024, 0.0, False), (65_536, -0.03, False), (50_000, 0.06, False)]
     hosts, devs, plan = _model(specs=specs)
     n_total, nnz_total = plan.totals()
     assert nnz_total < 0.07 * n_total
-    assert plan.num_tiles == sum(-(-(6144 * -(-h.n // 1024) + 24 * h.idx.shape[0]) // 49152) for h in hosts)
+    assert plan.num_tiles == sum(-(-(6144 * -(-h.n // 1024) + 24 * h.idx.shape[0]) // 65536) for h in hosts)
     for t in (1, 2, 3):
         for d, h in zip(devs, hosts):
             d.set_grads(h.grads(t))
