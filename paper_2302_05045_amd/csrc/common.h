@@ -51,9 +51,7 @@ inline int tile_cost_segs(int64_t cost) { return (int)((cost + kSegCost - 1) / k
 constexpr int kFlatThreads = 64;        // flat kernels over the compressed arrays
 constexpr int kChunk = 256;             // compressed elements per workgroup in the flat kernels
 constexpr int kStatReduceGrid = 1024;    // workgroups of the first level of the gradient-statistics reduction
-constexpr int kTileUnrollFp32 = 4;      // the same for the single-precision tile kernel
-constexpr int kTileUnroll = 6;          // compressed elements in flight per thread in the tile kernels (4 and 6 tie on
-                                        // uniform masks, 6 is 1 % ahead where dense stretches make long slices, 8 loses)
+constexpr int kTileUnrollFp32 = 4;      // compressed elements in flight per thread in the single-precision tile kernel
 
 static_assert(kMaxTileSegs >= 1 && kMaxTileSegs < 256, "the segment count of a tile record is an 8-bit field");
 static_assert(kSeg % 8 == 0, "a tile is written out as whole 16-byte vectors");
