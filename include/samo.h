@@ -299,7 +299,8 @@ typedef struct {
     int64_t num_tiles, num_chunks;
     int64_t n_total, nnz_total;   /* sums over the descriptors as given */
     int32_t num_layers;
-    uint32_t buffers;       /* bit set: which arrays every layer of the plan provides */
+    uint32_t buffers;       /* bits 0-8: which arrays every layer of the plan provides; bits 16-23: the most
+                               segments one tile of the plan holds (sizes the tile kernels' LDS request) */
 } samo_plan;
 
 samo_status samo_plan_workspace_bytes(const samo_layer *h_layers, int32_t num_layers, size_t *bytes);
@@ -459,9 +460,8 @@ samo_status samo_mfma_rate_probe(int64_t iters, float *d_sink, int32_t workgroup
  *   SAMO_KNOB_WGRAD_ROUND  test aid: the number of tiles taken as one round in that rule, in
  *                        place of the device's compute-unit count.
  *   SAMO_KNOB_TILE_COST    the weight of a plan's tiles in units of 1024 (6 .. 96; default 32, or 48 for a
- *                        model that keeps under 7 % of its elements).  Read by samo_plan_workspace_bytes,
- *                        samo_plan_init and every launch on a plan: set it before the plan is made and
- *                        leave it while the plan is in use.
+ *                        model that keeps under 7 % of its elements; 48 there with an fp32 dense side).
+ *                        Read by samo_plan_workspace_bytes and samo_plan_init: set it before both.
  * Returns SAMO_ERR_ARG for an unknown knob. */
 enum {
     SAMO_KNOB_OCC_TILE_STEP = 0,

@@ -25,7 +25,8 @@ namespace {
 // Which arrays every layer of a plan provides (samo_plan::buffers).
 enum : uint32_t {
     kHasP = 1u << 0, kHasM = 1u << 1, kHasV = 1u << 2, kHasW = 1u << 3, kHasG = 1u << 4, kHasGc = 1u << 5,
-    kHasGc16 = 1u << 6, kHasW32 = 1u << 7, kHasG32 = 1u << 8, kHasAll = (1u << 9) - 1u
+    kHasGc16 = 1u << 6, kHasW32 = 1u << 7, kHasG32 = 1u << 8, kHasAll = (1u << 9) - 1u,
+    kPlanSegsShift = 16      // bits 16-23 of samo_plan::buffers: the most segments a tile of the plan holds
 };
 inline bool has(const samo_plan *plan, uint32_t bits) { return (plan->buffers & bits) == bits; }
 
@@ -646,7 +647,7 @@ samo_status samo_plan_init(const samo_layer *h_layers, int32_t num_layers, void 
     plan->n_total = z.n_total;
     plan->nnz_total = z.nnz_total;
     plan->num_layers = num_layers;
-    plan->buffers = z.buffers;
+    plan->buffers = z.buffers | ((uint32_t)tile_cost_segs(z.tile_cost) << kPlanSegsShift);
     return SAMO_OK;
 }
 
@@ -670,7 +671,7 @@ LaunchSet tiles_of(const samo_plan *plan)
     ls.wgs = plan->num_tiles;
     ls.segs_per_tile = 1;
     ls.keep = plan->n_total > 0 ? (float)((double)plan->nnz_total / (double)plan->n_total) : 1.f;
-    ls.max_segs = tile_cost_segs(tile_cost_for(plan->n_total, plan->nnz_total, (plan->buffers & kHasW32) != 0));   // as samo_plan_init cut the tiles
+    ls.max_segs = (int)((plan->buffers >> kPlanSegsShift) & 0xffu);     // as samo_plan_init cut the tiles (checked at launch)
     return ls;
 }
 
