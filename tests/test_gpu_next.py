@@ -172,6 +172,36 @@ def test_a_model_that_keeps_under_seven_percent_is_cut_into_heavier_tiles():
             assert np.array_equal(host_bits(d.w), oracle.decompress(got_p, h.idx, h.n)), "w t=%d" % t
 
 
+@pytest.mark.parametrize("cost_k", [6, 20, 96])
+def test_any_tile_weight_gives_the_same_model(cost_k):
+    """The tuning aid SAMO_KNOB_TILE_COST: tiles of one segment, of the largest weight (sixteen segments, a
+    32 KiB LDS image) and one in between; every tile kernel against the oracle."""
+    samo.samo_debug_set(samo.KNOB_TILE_COST, cost_k)
+    try:
+        hosts, devs, plan = _model()
+        for t in (1, 2):
+            for d, h in zip(devs, hosts):
+                d.set_grads(h.grads(t))
+                d.w.fill_(float("nan"))
+            if t == 1:
+                plan.samo_fused_step_batched(INV, samo.adam_cfg(t, **si.ADAM))
+            else:
+                plan.samo_gather_fp16_batched(False, INV)
+                plan.samo_adam_expand_batched(INV, samo.adam_cfg(t, **si.ADAM))
+                for d in devs:
+                    d.w.fill_(float("nan"))
+                plan.samo_decompress_batched()
+            for d, h in zip(devs, hosts):
+                oracle.step(h.grads(t), h.n, h.idx, h.p, h.m, h.v, INV, OCFG, t)
+                got_p = d.p.cpu().numpy()
+                assert_close(got_p, h.p, "p t=%d" % t)
+                assert_close(d.m.cpu().numpy(), h.m, "m t=%d" % t)
+                assert_close(d.v.cpu().numpy(), h.v, "v t=%d" % t)
+                assert np.array_equal(host_bits(d.w), oracle.decompress(got_p, h.idx, h.n)), "w t=%d" % t
+    finally:
+        samo.samo_debug_set(samo.KNOB_TILE_COST)
+
+
 def test_dp_split_batched_with_statistics():
     hosts, devs, plan = _model()
     stats = samo.GradStats(plan)
