@@ -101,6 +101,25 @@ def test_fp32_batched_mixed_model():
     plan.close()
 
 
+def test_fp32_batched_model_that_keeps_under_seven_percent():
+    """A single-precision plan below 7 % kept gets tiles of one and a half times the weight (eight
+    segments, a 32 KiB fp32 image): sizes that end inside a segment, an empty layer."""
+    specs = [(200_003, 0.05, False), (9 * 1024, 0.0, False), (65_536, 0.03, False), (50_000, 0.06, False)]
+    hosts = [Host(n, keep, 900 + i, dense) for i, (n, keep, dense) in enumerate(specs)]
+    devs = [Dev(h) for h in hosts]
+    plan = samo.Plan([d.layer(h) for d, h in zip(devs, hosts)])
+    assert plan.num_tiles == sum(-(-(6144 * -(-h.n // 1024) + 24 * h.idx.shape[0]) // 49152) for h in hosts)
+    for t in (1, 2):
+        grads = [_grad32(h.n, h.seed, t) for h in hosts]
+        for d, g in zip(devs, grads):
+            d.g.copy_(dev_f32(g))
+        plan.samo_fused_step_fp32_batched(1.0, samo.adam_cfg(t, **si.ADAM))
+        for d, h, g in zip(devs, hosts, grads):
+            oracle.step_fp32(g, h.w, h.idx, h.m, h.v, 1.0, OCFG, t)
+            _check(d, h, "sparse plan t=%d n=%d" % (t, h.n))
+    plan.close()
+
+
 def test_fp32_statistics_clipping_and_overflow_skip():
     specs = [(50_000, 0.1, False), (4097, 0.3, False), (30001, 1.0, True), (200_003, 0.05, False)]
     hosts = [Host(n, keep, 800 + i, dense) for i, (n, keep, dense) in enumerate(specs)]
